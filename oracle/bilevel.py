@@ -1,0 +1,102 @@
+"""Bi-level KV decoding, by definition (test infrastructure).
+
+Paper: Method, "Bi-level KVs Decoding" and its figure caption.  The paper names the
+attention-score mechanism as one relevance oracle but prints no formula; the reading taken
+here (listed with the other readings in the design notes) is the mean pre-softmax attention
+logit of the query tokens onto the dense keys of a chunk:
+
+    score[b, c] = mean over (t, h, j in chunk c) of  scale * Qd[b, t, h, :] . K[g(h), j, :]
+
+which factors into per-chunk mean keys and per-KV-head mean queries.  Selection keeps the
+min(k, C) best chunks, ties going to the lower chunk id.  The mixed KV set is the prefix, then
+per chunk either all its rows (dense) or its kept rows (sparse), concatenated in temporal order.
+Decoding is plain softmax attention of each query token over the mixed set (no mask among the
+query tokens: their own KVs are not part of the set).
+"""
+import numpy as np
+
+from .sets import mixed_source_index
+
+
+def chunk_scores(qd, k, chunk_bounds, scale=None):
+    """score[B, C] float64.  qd [B, T, Hq, D]; k [Hkv, N, D] dense keys."""
+    bsz, t, hq, d = qd.shape
+    hkv = k.shape[0]
+    grp = hq // hkv
+    scale = 1.0 / np.sqrt(d) if scale is None else float(scale)
+    b = np.asarray(chunk_bounds, dtype=np.int64)
+    c_n = len(b) - 1
+    k64 = np.asarray(k, dtype=np.float64)
+    kbar = np.stack([k64[:, b[c]:b[c + 1], :].mean(axis=1) for c in range(c_n)], axis=1) \
+        if c_n else np.zeros((hkv, 0, d))                                  # [Hkv, C, D]
+    q64 = np.asarray(qd, dtype=np.float64).reshape(bsz, t, hkv, grp, d)
+    qbar = q64.mean(axis=(1, 3))                                            # [B, Hkv, D]
+    return scale * np.einsum("bgd,gcd->bc", qbar, kbar) / hkv
+
+
+def select_topk(scores, k, decide_dtype=np.float32):
+    """(topk_idx [B, k'], dense_mask [B, C] uint8) with k' = min(k, C).
+
+    The comparison is made on the scores rounded to `decide_dtype` (the precision in which the
+    device takes the same decision); order is score descending, ties by ascending chunk id."""
+    scores = np.asarray(scores)
+    bsz, c_n = scores.shape
+    kk = max(0, min(int(k), c_n))
+    s = scores.astype(decide_dtype)
+    idx = np.zeros((bsz, kk), dtype=np.int32)
+    mask = np.zeros((bsz, c_n), dtype=np.uint8)
+    for bi in range(bsz):
+        order = sorted(range(c_n), key=lambda c: (-float(s[bi, c]), c))     # full sort
+        idx[bi] = order[:kk]
+        mask[bi, order[:kk]] = 1
+    return idx, mask
+
+
+def gather_bilevel(k, v, dense_mask, n_prefix, chunk_bounds, sparse_offsets, sparse_idx, l_cap=None):
+    """Mixed KV of every query.  k, v [Hkv, N, D] (any dtype, copied bit for bit);
+    dense_mask [B, C].  Returns (kmix, vmix [B, Hkv, Lcap, D] zero padded, mix_len [B] int32,
+    src_idx [B, Lcap] int32 padded with -1)."""
+    dense_mask = np.asarray(dense_mask)
+    bsz = dense_mask.shape[0]
+    srcs = [mixed_source_index(dense_mask[bi], n_prefix, chunk_bounds, sparse_offsets, sparse_idx)
+            for bi in range(bsz)]
+    lens = np.array([len(s) for s in srcs], dtype=np.int32)
+    l_cap = int(lens.max()) if l_cap is None else int(l_cap)
+    assert l_cap >= lens.max()
+    hkv, _, d = k.shape
+    kmix = np.zeros((bsz, hkv, l_cap, d), dtype=k.dtype)
+    vmix = np.zeros((bsz, hkv, l_cap, d), dtype=v.dtype)
+    src_idx = np.full((bsz, l_cap), -1, dtype=np.int32)
+    for bi, s in enumerate(srcs):
+        kmix[bi, :, :len(s)] = k[:, s]
+        vmix[bi, :, :len(s)] = v[:, s]
+        src_idx[bi, :len(s)] = s
+    return kmix, vmix, lens, src_idx
+
+
+def decode_lse(qd, kmix, vmix, mix_len, scale=None):
+    """(O [B, T, Hq, D], LSE [B, T, Hq]) float64: softmax attention of every query token over
+    the first mix_len[b] rows of its mixed KV."""
+    bsz, t, hq, d = qd.shape
+    hkv = kmix.shape[1]
+    grp = hq // hkv
+    scale = 1.0 / np.sqrt(d) if scale is None else float(scale)
+    out = np.zeros((bsz, t, hq, d), dtype=np.float64)
+    lse = np.zeros((bsz, t, hq), dtype=np.float64)
+    for bi in range(bsz):
+        ln = int(mix_len[bi])
+        for h in range(hq):
+            g = h // grp
+            kk = np.asarray(kmix[bi, g, :ln], dtype=np.float64)
+            vv = np.asarray(vmix[bi, g, :ln], dtype=np.float64)
+            s = scale * (np.asarray(qd[bi, :, h, :], dtype=np.float64) @ kk.T)   # [T, ln]
+            m = s.max(axis=1, keepdims=True)
+            e = np.exp(s - m)
+            l = e.sum(axis=1, keepdims=True)
+            out[bi, :, h, :] = (e / l) @ vv
+            lse[bi, :, h] = (m + np.log(l))[:, 0]
+    return out, lse
+
+
+def decode_mixed(qd, kmix, vmix, mix_len, scale=None):
+    return decode_lse(qd, kmix, vmix, mix_len, scale)[0]
