@@ -1,0 +1,182 @@
+/*
+ * vxl -- chunk-based pre-filling attention and bi-level KV decoding on one MI355X (gfx950).
+ *
+ * C ABI of libvxl.so.  The operations are those of Video-XL-2's task-aware KV
+ * sparsification (paper: Method, "Efficiency Optimization"):
+ *
+ *   vxl_chunk_prefill      "Chunk-based Pre-filling" and the caption of its figure
+ *   vxl_chunk_score_topk   "Bi-level KVs Decoding": relevance score per chunk, selection
+ *   vxl_gather_bilevel_kv  "Bi-level KVs Decoding": selective reload + concatenation
+ *   vxl_bilevel_decode     "Bi-level KVs Decoding": generation over the mixed KV set
+ *
+ * Conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller; the layout arrays given to
+ *     vxl_layout_create are HOST pointers (copied; the caller may free them afterwards).
+ *   - Tensors are dense, row-major, in the storage dtype of the descriptor:
+ *       Q, O   [n_q_heads,  n_tokens, head_dim]      K, V [n_kv_heads, n_tokens, head_dim]
+ *       Qd, Od [batch, n_q_tokens, n_q_heads, head_dim]
+ *       Kmix, Vmix [batch, n_kv_heads, l_cap, head_dim]
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - The four hot calls are asynchronous on `stream` (a hipStream_t; NULL = default stream),
+ *     never synchronise and never allocate: scratch comes from the caller's workspace, sized by
+ *     vxl_workspace_bytes.  Inputs are never written.  Outputs and workspace must not alias
+ *     inputs.  Base pointers must be 16-byte aligned.
+ *   - Every call returns a vxl_status.  Argument errors are detected on the host before
+ *     anything is launched; a failing HIP call is reported as VXL_ERR_HIP (the text of the
+ *     last one is available from vxl_last_error).
+ *   - Supported: dtype F32 or BF16; head_dim 64 or 128; n_q_heads a multiple of n_kv_heads;
+ *     n_chunks <= VXL_MAX_CHUNKS.  BF16 runs on the matrix cores with fp32 accumulation; F32
+ *     runs on the vector ALUs in fp32.
+ */
+#ifndef VXL_H
+#define VXL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VXL_MAX_CHUNKS 4096
+
+typedef enum {
+    VXL_OK = 0,
+    VXL_ERR_INVALID_ARG = 1,   /* null pointer, inconsistent sizes, malformed layout */
+    VXL_ERR_UNSUPPORTED = 2,   /* dtype / head_dim / chunk count outside the supported set */
+    VXL_ERR_WORKSPACE = 3,     /* workspace missing or smaller than vxl_workspace_bytes */
+    VXL_ERR_HIP = 4            /* a HIP runtime call failed */
+} vxl_status;
+
+typedef enum { VXL_F32 = 0, VXL_BF16 = 1 } vxl_dtype;
+
+typedef enum {
+    VXL_OP_PREFILL = 0,
+    VXL_OP_SCORE_TOPK = 1,
+    VXL_OP_GATHER = 2,
+    VXL_OP_DECODE = 3
+} vxl_op;
+
+typedef struct {
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t dtype;           /* vxl_dtype */
+    float softmax_scale;     /* 0 selects 1/sqrt(head_dim); otherwise must be > 0 */
+} vxl_attn_desc;
+
+typedef struct vxl_layout vxl_layout;   /* opaque: chunking + kept-token lists of one prompt */
+typedef void* vxl_stream;               /* a hipStream_t */
+
+/*
+ * Token layout of one prompt ("Chunk-based Pre-filling": the visual token sequence is divided
+ * into chunks; the kept tokens of a chunk are the ones later chunks may attend to, in the paper
+ * the timestamp tokens.  "Bi-level KVs Decoding": the same chunking indexes the dense and the
+ * sparse KVs; here the sparse KVs of a chunk are its kept rows).
+ *   n_tokens        N, total tokens; ids 0..n_prefix-1 are the system/text prefix
+ *   chunk_bounds    host int32 [n_chunks+1], strictly increasing, [0]==n_prefix, [n_chunks]==N
+ *   sparse_offsets  host int32 [n_chunks+1], CSR offsets, [0]==0, non-decreasing
+ *   sparse_idx      host int32 [sparse_offsets[n_chunks]], absolute token ids, strictly
+ *                   ascending inside a chunk and inside that chunk's bounds (may be NULL when
+ *                   no token is kept)
+ * The handle owns device copies of these arrays and the pre-filling tile schedule derived from
+ * them; creating it allocates device memory and synchronises `stream`.  n_chunks may be 0.
+ * Errors: VXL_ERR_INVALID_ARG for any violated condition above, VXL_ERR_UNSUPPORTED for
+ * n_chunks > VXL_MAX_CHUNKS, VXL_ERR_HIP.
+ */
+vxl_status vxl_layout_create(int32_t n_tokens, int32_t n_prefix, int32_t n_chunks,
+                             const int32_t* chunk_bounds, const int32_t* sparse_offsets,
+                             const int32_t* sparse_idx, vxl_stream stream, vxl_layout** out);
+vxl_status vxl_layout_destroy(vxl_layout* layout);
+
+/* Bytes of workspace the given hot call needs (0 on invalid arguments).  batch, n_q_tokens
+ * and l_cap are read by the ops that take them (SCORE_TOPK, GATHER: batch; DECODE: batch,
+ * n_q_tokens, l_cap); layout may be NULL for VXL_OP_DECODE. */
+size_t vxl_workspace_bytes(vxl_op op, const vxl_layout* layout, const vxl_attn_desc* desc,
+                           int32_t batch, int32_t n_q_tokens, int32_t l_cap);
+
+/* Upper bound of the mixed-KV length when at most k chunks are dense:
+ * n_prefix + all kept rows + the k largest (chunk length - kept count).  k is clamped to
+ * [0, n_chunks]. */
+int32_t vxl_mixed_kv_capacity(const vxl_layout* layout, int32_t k);
+
+/* Number of (query, key) pairs the pre-filling mask allows, in closed form; the effective
+ * FLOP count of vxl_chunk_prefill is 4 * head_dim * n_q_heads times this. */
+int64_t vxl_prefill_pair_count(const vxl_layout* layout);
+
+/*
+ * Chunk-based pre-filling attention ("Chunk-based Pre-filling"; figure caption: the chunk
+ * being processed attends to itself, to the historical kept tokens and to the system prompt).
+ * For query head h and token i of chunk c:
+ *   O[h,i,:] = softmax over j in ([0,P) u kept(0..c-1) u [b_c, i]) of scale*q_i.k_j, times V;
+ * prefix tokens attend causally to the prefix.  Internally the kept K/V rows are first
+ * compacted (prefix rows, then kept rows in chunk order) so that the history of chunk c is a
+ * prefix of one contiguous buffer.
+ *   Q, K, V, O   device, layouts above;  LSE device float [n_q_heads, n_tokens] or NULL
+ *                (natural-log sum-exp of the scaled logits of each row)
+ * Errors: VXL_ERR_INVALID_ARG, VXL_ERR_UNSUPPORTED, VXL_ERR_WORKSPACE, VXL_ERR_HIP.
+ */
+vxl_status vxl_chunk_prefill(const vxl_layout* layout, const vxl_attn_desc* desc,
+                             const void* Q, const void* K, const void* V, void* O, float* LSE,
+                             void* workspace, size_t workspace_bytes, vxl_stream stream);
+
+/*
+ * Relevance score of every chunk for every query and selection of the dense chunks
+ * ("Bi-level KVs Decoding": a relevance score for each video chunk, here by the
+ * attention-score mechanism).  score[b,c] = mean over (t, h, j in chunk c) of
+ * scale * Qd[b,t,h,:].K[g(h),j,:], computed as scale/Hkv * sum_g mean_q[b,g,:].mean_k[g,c,:].
+ * The min(k, n_chunks) best chunks are selected, ties going to the lower chunk id.
+ *   Qd          device [batch, n_q_tokens, n_q_heads, head_dim]
+ *   K           device dense keys (read only when kbar_ready == 0)
+ *   kbar        device float [n_kv_heads, n_chunks, head_dim] per-chunk mean keys: written when
+ *               kbar_ready == 0, read as a cache when kbar_ready != 0; NULL uses the workspace
+ *   topk_idx    device int32 [batch, min(k, n_chunks)], best first (may be NULL if k == 0)
+ *   dense_mask  device uint8 [batch, n_chunks], 1 = dense
+ *   scores      device float [batch, n_chunks] or NULL
+ */
+vxl_status vxl_chunk_score_topk(const vxl_layout* layout, const vxl_attn_desc* desc,
+                                const void* Qd, int32_t batch, int32_t n_q_tokens,
+                                const void* K, int32_t k, float* kbar, int32_t kbar_ready,
+                                int32_t* topk_idx, uint8_t* dense_mask, float* scores,
+                                void* workspace, size_t workspace_bytes, vxl_stream stream);
+
+/*
+ * Reload and concatenate ("Bi-level KVs Decoding": dense KVs for the relevant chunks, sparse
+ * KVs for the others, concatenated into the mixed KV set).  Row order of the mixed set: the
+ * prefix, then the chunks in temporal order, rows ascending inside a chunk.
+ *   dense_mask  device uint8 [batch, n_chunks]
+ *   Kmix, Vmix  device [batch, n_kv_heads, l_cap, head_dim]; rows >= mix_len[b] are left
+ *               untouched
+ *   mix_len     device int32 [batch] (written)
+ *   src_idx     device int32 [batch, l_cap] source token id of every mixed row, or NULL
+ * l_cap must be at least vxl_mixed_kv_capacity(layout, k) for the k that produced the mask;
+ * the host cannot see the mask, so it checks l_cap >= capacity for k = 0 and the kernel never
+ * writes beyond l_cap (mix_len is clamped to l_cap; a clamped value signals the overflow).
+ */
+vxl_status vxl_gather_bilevel_kv(const vxl_layout* layout, const vxl_attn_desc* desc,
+                                 const void* K, const void* V, const uint8_t* dense_mask,
+                                 int32_t batch, void* Kmix, void* Vmix, int32_t l_cap,
+                                 int32_t* mix_len, int32_t* src_idx,
+                                 void* workspace, size_t workspace_bytes, vxl_stream stream);
+
+/*
+ * GQA decode attention over the mixed KV set ("Bi-level KVs Decoding"): every query token
+ * attends to rows 0..mix_len[b]-1 of its mixed set; no mask among the query tokens.  Split-KV
+ * partial results are merged by log-sum-exp in a fixed order (deterministic).
+ *   Qd, O    device [batch, n_q_tokens, n_q_heads, head_dim];  LSE device float
+ *            [batch, n_q_tokens, n_q_heads] or NULL
+ *   mix_len  device int32 [batch]; entries must be in [1, l_cap]
+ */
+vxl_status vxl_bilevel_decode(const vxl_attn_desc* desc, const void* Qd, int32_t batch,
+                              int32_t n_q_tokens, const void* Kmix, const void* Vmix,
+                              int32_t l_cap, const int32_t* mix_len, void* O, float* LSE,
+                              void* workspace, size_t workspace_bytes, vxl_stream stream);
+
+const char* vxl_status_string(vxl_status s);
+const char* vxl_last_error(void);   /* text of the last failing HIP call on this thread */
+int vxl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VXL_H */

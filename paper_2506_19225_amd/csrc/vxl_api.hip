@@ -1,0 +1,356 @@
+// Host side of the C ABI: argument validation, the layout handle (device copies of the
+// chunking and the pre-filling tile schedule), workspace planning and kernel dispatch.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "vxl_internal.h"
+
+namespace vxl {
+
+static thread_local char g_last_error[512] = "";
+static int g_force_simple = 0;
+
+void set_last_error(const char* what, hipError_t e) {
+    snprintf(g_last_error, sizeof(g_last_error), "%s: %s", what, hipGetErrorString(e));
+}
+
+static bool desc_ok(const vxl_attn_desc* d, vxl_status* st) {
+    if (!d) { *st = VXL_ERR_INVALID_ARG; return false; }
+    if (d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->n_q_heads % d->n_kv_heads != 0 ||
+        !(d->softmax_scale >= 0.0f) || !std::isfinite(d->softmax_scale)) {
+        *st = VXL_ERR_INVALID_ARG; return false;
+    }
+    if ((d->dtype != VXL_F32 && d->dtype != VXL_BF16) || (d->head_dim != 64 && d->head_dim != 128)) {
+        *st = VXL_ERR_UNSUPPORTED; return false;
+    }
+    return true;
+}
+
+static float resolve_scale(const vxl_attn_desc* d) {
+    return d->softmax_scale > 0.0f ? d->softmax_scale : 1.0f / std::sqrt((float)d->head_dim);
+}
+
+static size_t elem_bytes(const vxl_attn_desc* d) { return d->dtype == VXL_BF16 ? 2 : 4; }
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+PrefillWorkspace prefill_workspace(const vxl_layout* L, const vxl_attn_desc* d) {
+    PrefillWorkspace w{};
+    if (d->dtype != VXL_BF16) { w.total = 0; return w; }
+    size_t off = 0;
+    w.kctx = off;
+    off += align_up((size_t)d->n_kv_heads * L->n_ctx_tiles * kKeyTile * d->head_dim * 2, 256);
+    w.vt = off;
+    off += align_up((size_t)d->n_kv_heads * (L->n_ctx_tiles + L->n_own_tiles) * kKeyTile * d->head_dim * 2, 256);
+    w.total = off;
+    return w;
+}
+
+DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
+    DecodePlan p{};
+    if (d->dtype != VXL_BF16) { p.n_split = 1; p.split_len = l_cap; p.total = 0; return p; }
+    const int rows = (d->n_q_heads / d->n_kv_heads) * T;
+    const int tiles = (l_cap + kKeyTile - 1) / kKeyTile;
+    // enough (batch, kv head, split) units to cover the 256 CUs a few times over, but at least
+    // two key tiles per split so the merge stays small
+    long units_wanted = 1024;
+    long per = (long)batch * d->n_kv_heads * ((rows + 127) / 128);
+    int want = (int)std::max<long>(1, (units_wanted + per - 1) / per);
+    int max_split = std::max(1, tiles / 2);
+    int n_split = std::min(want, max_split);
+    int tiles_per = (tiles + n_split - 1) / n_split;
+    n_split = (tiles + tiles_per - 1) / tiles_per;
+    p.n_split = n_split;
+    p.split_len = tiles_per * kKeyTile;
+    size_t off = 0;
+    p.part_o = off;
+    off += align_up((size_t)batch * d->n_kv_heads * n_split * rows * d->head_dim * sizeof(float), 256);
+    p.part_ml = off;
+    off += align_up((size_t)batch * d->n_kv_heads * n_split * rows * 2 * sizeof(float), 256);
+    p.total = off;
+    return p;
+}
+
+}  // namespace vxl
+
+using namespace vxl;
+
+extern "C" {
+
+int vxl_version(void) { return 100; }
+
+const char* vxl_status_string(vxl_status s) {
+    switch (s) {
+        case VXL_OK: return "ok";
+        case VXL_ERR_INVALID_ARG: return "invalid argument";
+        case VXL_ERR_UNSUPPORTED: return "unsupported dtype, head_dim or chunk count";
+        case VXL_ERR_WORKSPACE: return "workspace missing or too small";
+        case VXL_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char* vxl_last_error(void) { return g_last_error; }
+
+// Test hook: route BF16 calls through the plain vector-ALU kernels (an on-device cross-check
+// of the matrix-core kernels).  Not part of the public header.
+void vxl_debug_force_simple(int on) { g_force_simple = on; }
+
+vxl_status vxl_layout_create(int32_t n_tokens, int32_t n_prefix, int32_t n_chunks,
+                             const int32_t* chunk_bounds, const int32_t* sparse_offsets,
+                             const int32_t* sparse_idx, vxl_stream stream, vxl_layout** out) {
+    if (!out) return VXL_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (n_tokens <= 0 || n_prefix < 0 || n_chunks < 0 || !chunk_bounds || !sparse_offsets)
+        return VXL_ERR_INVALID_ARG;
+    if (n_chunks > VXL_MAX_CHUNKS) return VXL_ERR_UNSUPPORTED;
+    if (chunk_bounds[0] != n_prefix || chunk_bounds[n_chunks] != n_tokens || sparse_offsets[0] != 0)
+        return VXL_ERR_INVALID_ARG;
+    for (int c = 0; c < n_chunks; ++c) {
+        if (chunk_bounds[c + 1] <= chunk_bounds[c]) return VXL_ERR_INVALID_ARG;
+        if (sparse_offsets[c + 1] < sparse_offsets[c]) return VXL_ERR_INVALID_ARG;
+        if (sparse_offsets[c + 1] - sparse_offsets[c] > chunk_bounds[c + 1] - chunk_bounds[c])
+            return VXL_ERR_INVALID_ARG;
+    }
+    const int32_t s_total = sparse_offsets[n_chunks];
+    if (s_total > 0 && !sparse_idx) return VXL_ERR_INVALID_ARG;
+    for (int c = 0; c < n_chunks; ++c) {
+        for (int32_t i = sparse_offsets[c]; i < sparse_offsets[c + 1]; ++i) {
+            const int32_t t = sparse_idx[i];
+            if (t < chunk_bounds[c] || t >= chunk_bounds[c + 1]) return VXL_ERR_INVALID_ARG;
+            if (i > sparse_offsets[c] && t <= sparse_idx[i - 1]) return VXL_ERR_INVALID_ARG;
+        }
+    }
+
+    vxl_layout* L = new (std::nothrow) vxl_layout();
+    if (!L) return VXL_ERR_INVALID_ARG;
+    L->n_tokens = n_tokens; L->n_prefix = n_prefix; L->n_chunks = n_chunks; L->s_total = s_total;
+    L->bounds.assign(chunk_bounds, chunk_bounds + n_chunks + 1);
+    L->soff.assign(sparse_offsets, sparse_offsets + n_chunks + 1);
+    if (s_total) L->sidx.assign(sparse_idx, sparse_idx + s_total);
+
+    // segments and the closed-form pair count
+    int32_t tile_base = 0;
+    int64_t pairs = (int64_t)n_prefix * (n_prefix + 1) / 2;
+    if (n_prefix > 0) {
+        L->segs.push_back({0, n_prefix, 0, tile_base});
+        tile_base += (n_prefix + kKeyTile - 1) / kKeyTile;
+    }
+    for (int c = 0; c < n_chunks; ++c) {
+        const int32_t len = chunk_bounds[c + 1] - chunk_bounds[c];
+        const int32_t ctx = n_prefix + sparse_offsets[c];
+        L->segs.push_back({chunk_bounds[c], len, ctx, tile_base});
+        tile_base += (len + kKeyTile - 1) / kKeyTile;
+        pairs += (int64_t)len * ctx + (int64_t)len * (len + 1) / 2;
+    }
+    L->pair_count = pairs;
+    L->n_seg = (int32_t)L->segs.size();
+    L->n_own_tiles = tile_base;
+    L->l_ctx = n_prefix + s_total;
+    L->n_ctx_tiles = (L->l_ctx + kKeyTile - 1) / kKeyTile;
+
+    // source token of every slot of every V tile: history tiles first, then own tiles
+    std::vector<int32_t> tile_src((size_t)(L->n_ctx_tiles + L->n_own_tiles) * kKeyTile, -1);
+    for (int32_t r = 0; r < L->l_ctx; ++r) tile_src[r] = r < n_prefix ? r : L->sidx[r - n_prefix];
+    for (const Segment& sg : L->segs) {
+        int32_t* dst = tile_src.data() + (size_t)(L->n_ctx_tiles + sg.tile_base) * kKeyTile;
+        for (int32_t r = 0; r < sg.q_len; ++r) dst[r] = sg.q_start + r;
+    }
+
+    // work items, heaviest first (cost = key tiles visited)
+    std::vector<WorkItem> work[2];
+    for (int v = 0; v < 2; ++v) {
+        const int bm = 128 << v;
+        std::vector<std::pair<int64_t, WorkItem>> items;
+        for (int s = 0; s < L->n_seg; ++s) {
+            const Segment& sg = L->segs[s];
+            const int mt = (sg.q_len + bm - 1) / bm;
+            for (int m = 0; m < mt; ++m) {
+                const int last = std::min(sg.q_len, (m + 1) * bm) - 1;
+                const int64_t cost = (sg.ctx_len + kKeyTile - 1) / kKeyTile + last / kKeyTile + 1;
+                items.push_back({cost, {s, m}});
+            }
+        }
+        std::stable_sort(items.begin(), items.end(),
+                         [](const auto& a, const auto& b) { return a.first > b.first; });
+        for (auto& it : items) work[v].push_back(it.second);
+        L->n_work[v] = (int32_t)work[v].size();
+    }
+
+    // one device blob
+    size_t off = 0;
+    auto place = [&](size_t bytes) { size_t o = off; off += align_up(std::max<size_t>(bytes, 4), 256); return o; };
+    const size_t o_bounds = place((n_chunks + 1) * 4), o_soff = place((n_chunks + 1) * 4);
+    const size_t o_sidx = place((size_t)s_total * 4);
+    const size_t o_segs = place(L->segs.size() * sizeof(Segment));
+    const size_t o_tsrc = place(tile_src.size() * 4);
+    const size_t o_w0 = place(work[0].size() * sizeof(WorkItem));
+    const size_t o_w1 = place(work[1].size() * sizeof(WorkItem));
+    L->blob_bytes = off;
+    std::vector<char> host(off, 0);
+    memcpy(host.data() + o_bounds, L->bounds.data(), (n_chunks + 1) * 4);
+    memcpy(host.data() + o_soff, L->soff.data(), (n_chunks + 1) * 4);
+    if (s_total) memcpy(host.data() + o_sidx, L->sidx.data(), (size_t)s_total * 4);
+    memcpy(host.data() + o_segs, L->segs.data(), L->segs.size() * sizeof(Segment));
+    memcpy(host.data() + o_tsrc, tile_src.data(), tile_src.size() * 4);
+    if (!work[0].empty()) memcpy(host.data() + o_w0, work[0].data(), work[0].size() * sizeof(WorkItem));
+    if (!work[1].empty()) memcpy(host.data() + o_w1, work[1].data(), work[1].size() * sizeof(WorkItem));
+
+    hipError_t e = hipGetDevice(&L->device);
+    if (e == hipSuccess) e = hipMalloc(&L->d_blob, off);
+    if (e == hipSuccess) e = hipMemcpyAsync(L->d_blob, host.data(), off, hipMemcpyHostToDevice, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) {
+        set_last_error("vxl_layout_create", e);
+        if (L->d_blob) (void)hipFree(L->d_blob);
+        delete L;
+        return VXL_ERR_HIP;
+    }
+    char* base = (char*)L->d_blob;
+    L->d_bounds = (int32_t*)(base + o_bounds);
+    L->d_soff = (int32_t*)(base + o_soff);
+    L->d_sidx = (int32_t*)(base + o_sidx);
+    L->d_segs = (Segment*)(base + o_segs);
+    L->d_tile_src = (int32_t*)(base + o_tsrc);
+    L->d_work[0] = (WorkItem*)(base + o_w0);
+    L->d_work[1] = (WorkItem*)(base + o_w1);
+    *out = L;
+    return VXL_OK;
+}
+
+vxl_status vxl_layout_destroy(vxl_layout* L) {
+    if (!L) return VXL_OK;
+    vxl_status st = VXL_OK;
+    if (L->d_blob) {
+        hipError_t e = hipFree(L->d_blob);
+        if (e != hipSuccess) { set_last_error("hipFree", e); st = VXL_ERR_HIP; }
+    }
+    delete L;
+    return st;
+}
+
+int32_t vxl_mixed_kv_capacity(const vxl_layout* L, int32_t k) {
+    if (!L) return 0;
+    k = std::max(0, std::min(k, L->n_chunks));
+    std::vector<int32_t> extra(L->n_chunks);
+    for (int c = 0; c < L->n_chunks; ++c)
+        extra[c] = (L->bounds[c + 1] - L->bounds[c]) - (L->soff[c + 1] - L->soff[c]);
+    std::partial_sort(extra.begin(), extra.begin() + k, extra.end(), std::greater<int32_t>());
+    int64_t cap = (int64_t)L->n_prefix + L->s_total;
+    for (int i = 0; i < k; ++i) cap += extra[i];
+    return (int32_t)cap;
+}
+
+int64_t vxl_prefill_pair_count(const vxl_layout* L) { return L ? L->pair_count : 0; }
+
+size_t vxl_workspace_bytes(vxl_op op, const vxl_layout* L, const vxl_attn_desc* d, int32_t batch,
+                           int32_t n_q_tokens, int32_t l_cap) {
+    vxl_status st;
+    if (!desc_ok(d, &st)) return 0;
+    switch (op) {
+        case VXL_OP_PREFILL:
+            if (!L) return 0;
+            return std::max<size_t>(256, prefill_workspace(L, d).total);
+        case VXL_OP_SCORE_TOPK:
+            if (!L || batch <= 0) return 0;
+            return std::max<size_t>(256, align_up((size_t)d->n_kv_heads * std::max(1, L->n_chunks) * d->head_dim * 4, 256));
+        case VXL_OP_GATHER:
+            if (!L || batch <= 0) return 0;
+            return align_up((size_t)batch * (L->n_chunks + 2) * 4, 256);
+        case VXL_OP_DECODE:
+            if (batch <= 0 || n_q_tokens <= 0 || l_cap <= 0) return 0;
+            return std::max<size_t>(256, decode_plan(d, batch, n_q_tokens, l_cap).total);
+    }
+    return 0;
+}
+
+vxl_status vxl_chunk_prefill(const vxl_layout* L, const vxl_attn_desc* d, const void* Q,
+                             const void* K, const void* V, void* O, float* LSE, void* workspace,
+                             size_t workspace_bytes, vxl_stream stream) {
+    vxl_status st;
+    if (!L) return VXL_ERR_INVALID_ARG;
+    if (!desc_ok(d, &st)) return st;
+    if (!Q || !K || !V || !O) return VXL_ERR_INVALID_ARG;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return VXL_ERR_INVALID_ARG;
+    if (O == Q || O == K || O == V) return VXL_ERR_INVALID_ARG;
+    const float scale = resolve_scale(d);
+    if (d->dtype == VXL_BF16 && !g_force_simple) {
+        const size_t need = prefill_workspace(L, d).total;
+        if (!workspace || workspace_bytes < need || !aligned16(workspace)) return VXL_ERR_WORKSPACE;
+        return launch_prefill_bf16(L, d, scale, Q, K, V, O, LSE, workspace, (hipStream_t)stream);
+    }
+    return launch_prefill_simple(L, d, scale, Q, K, V, O, LSE, (hipStream_t)stream);
+}
+
+vxl_status vxl_chunk_score_topk(const vxl_layout* L, const vxl_attn_desc* d, const void* Qd,
+                                int32_t batch, int32_t n_q_tokens, const void* K, int32_t k,
+                                float* kbar, int32_t kbar_ready, int32_t* topk_idx,
+                                uint8_t* dense_mask, float* scores, void* workspace,
+                                size_t workspace_bytes, vxl_stream stream) {
+    vxl_status st;
+    if (!L) return VXL_ERR_INVALID_ARG;
+    if (!desc_ok(d, &st)) return st;
+    if (!Qd || batch <= 0 || n_q_tokens <= 0 || k < 0 || !dense_mask) return VXL_ERR_INVALID_ARG;
+    if (!aligned16(Qd)) return VXL_ERR_INVALID_ARG;
+    const int kk = std::min(k, L->n_chunks);
+    if (kk > 0 && !topk_idx) return VXL_ERR_INVALID_ARG;
+    if (kbar_ready && !kbar) return VXL_ERR_INVALID_ARG;
+    if (!kbar_ready && (!K || !aligned16(K))) return VXL_ERR_INVALID_ARG;
+    if (L->n_chunks == 0) return VXL_OK;      // nothing to score, nothing to write
+    float* kb = kbar;
+    if (!kb) {
+        const size_t need = vxl_workspace_bytes(VXL_OP_SCORE_TOPK, L, d, batch, n_q_tokens, 0);
+        if (!workspace || workspace_bytes < need || !aligned16(workspace)) return VXL_ERR_WORKSPACE;
+        kb = (float*)workspace;
+    }
+    if (!kbar_ready) {
+        st = launch_chunk_summarize(L, d, K, kb, (hipStream_t)stream);
+        if (st != VXL_OK) return st;
+    }
+    return launch_score_topk(L, d, resolve_scale(d), Qd, batch, n_q_tokens, kk, kb, topk_idx,
+                             dense_mask, scores, (hipStream_t)stream);
+}
+
+vxl_status vxl_gather_bilevel_kv(const vxl_layout* L, const vxl_attn_desc* d, const void* K,
+                                 const void* V, const uint8_t* dense_mask, int32_t batch,
+                                 void* Kmix, void* Vmix, int32_t l_cap, int32_t* mix_len,
+                                 int32_t* src_idx, void* workspace, size_t workspace_bytes,
+                                 vxl_stream stream) {
+    vxl_status st;
+    if (!L) return VXL_ERR_INVALID_ARG;
+    if (!desc_ok(d, &st)) return st;
+    if (!K || !V || !Kmix || !Vmix || !mix_len || batch <= 0) return VXL_ERR_INVALID_ARG;
+    if (L->n_chunks > 0 && !dense_mask) return VXL_ERR_INVALID_ARG;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(Kmix) || !aligned16(Vmix)) return VXL_ERR_INVALID_ARG;
+    if (l_cap < vxl_mixed_kv_capacity(L, 0)) return VXL_ERR_INVALID_ARG;
+    const size_t need = vxl_workspace_bytes(VXL_OP_GATHER, L, d, batch, 0, 0);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return VXL_ERR_WORKSPACE;
+    return launch_gather(L, d, K, V, dense_mask, batch, Kmix, Vmix, l_cap, mix_len, src_idx,
+                         (int32_t*)workspace, (hipStream_t)stream);
+}
+
+vxl_status vxl_bilevel_decode(const vxl_attn_desc* d, const void* Qd, int32_t batch,
+                              int32_t n_q_tokens, const void* Kmix, const void* Vmix, int32_t l_cap,
+                              const int32_t* mix_len, void* O, float* LSE, void* workspace,
+                              size_t workspace_bytes, vxl_stream stream) {
+    vxl_status st;
+    if (!desc_ok(d, &st)) return st;
+    if (!Qd || !Kmix || !Vmix || !mix_len || !O || batch <= 0 || n_q_tokens <= 0 || l_cap <= 0)
+        return VXL_ERR_INVALID_ARG;
+    if (!aligned16(Qd) || !aligned16(Kmix) || !aligned16(Vmix) || !aligned16(O)) return VXL_ERR_INVALID_ARG;
+    const float scale = resolve_scale(d);
+    if (d->dtype == VXL_BF16 && !g_force_simple) {
+        const size_t need = decode_plan(d, batch, n_q_tokens, l_cap).total;
+        if (!workspace || workspace_bytes < need || !aligned16(workspace)) return VXL_ERR_WORKSPACE;
+        return launch_decode_bf16(d, scale, Qd, batch, n_q_tokens, Kmix, Vmix, l_cap, mix_len, O,
+                                  LSE, workspace, (hipStream_t)stream);
+    }
+    return launch_decode_simple(d, scale, Qd, batch, n_q_tokens, Kmix, Vmix, l_cap, mix_len, O, LSE,
+                                (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,271 @@
+// Bi-level KV decoding, the integer / bandwidth-bound steps: per-chunk mean keys, relevance
+// scores + top-k selection (LDS bitonic sort), and the dense/sparse gather into the mixed KV.
+#include <math.h>
+
+#include "vxl_internal.h"
+
+namespace vxl {
+
+namespace {
+
+__device__ __forceinline__ float ld(const float* p) { return *p; }
+__device__ __forceinline__ float ld(const uint16_t* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+
+// ------------------------------------------------------------------------------------------
+// kbar[g, c, :] = mean of the dense key rows of chunk c.  One block per (chunk, kv head).
+// Thread (rg, dl) sums rows rg, rg + R, ... of column dl in row order, and the R partial sums
+// are added in a fixed order, so the result depends only on the values and their offsets
+// inside the chunk: two chunks with equal contents get bit-identical means (exact score ties).
+// ------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void chunk_summarize_kernel(const T* __restrict__ K,
+                                                              const int32_t* __restrict__ bounds,
+                                                              float* __restrict__ kbar, int n_tokens,
+                                                              int n_chunks) {
+    constexpr int R = 256 / D;                 // row groups: 2 for D=128, 4 for D=64
+    __shared__ float part[R][D];
+    const int c = blockIdx.x, g = blockIdx.y;
+    const int dl = threadIdx.x % D, rg = threadIdx.x / D;
+    const int lo = bounds[c], hi = bounds[c + 1];
+    const T* base = K + ((size_t)g * n_tokens) * D + dl;
+    // four independent accumulators per thread keep several loads in flight
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    int r = lo + rg;
+    for (; r + 3 * R < hi; r += 4 * R) {
+        a0 += ld(base + (size_t)r * D);
+        a1 += ld(base + (size_t)(r + R) * D);
+        a2 += ld(base + (size_t)(r + 2 * R) * D);
+        a3 += ld(base + (size_t)(r + 3 * R) * D);
+    }
+    for (; r < hi; r += R) a0 += ld(base + (size_t)r * D);
+    part[rg][dl] = (a0 + a1) + (a2 + a3);
+    __syncthreads();
+    if (rg == 0) {
+        float s = part[0][dl];
+#pragma unroll
+        for (int i = 1; i < R; ++i) s += part[i][dl];
+        kbar[((size_t)g * n_chunks + c) * D + dl] = s / (float)(hi - lo);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// One block per query b: mean query per kv head, scores of all chunks, bitonic sort of
+// (score, chunk id) in LDS, top-k ids + dense mask.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ bool ranks_before(float sa, int ia, float sb, int ib) {
+    return sa > sb || (sa == sb && ia < ib);     // score descending, ties to the lower chunk id
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void score_topk_kernel(
+    const T* __restrict__ Qd, const float* __restrict__ kbar, int T_q, int n_q_heads, int n_kv_heads,
+    int n_chunks, int k, int n_sort, float scale, int32_t* __restrict__ topk_idx,
+    uint8_t* __restrict__ dense_mask, float* __restrict__ scores) {
+    extern __shared__ unsigned char smem[];
+    float* qbar = (float*)smem;                               // [Hkv][D]
+    float* s_val = qbar + n_kv_heads * D;                     // [n_sort]
+    int* s_idx = (int*)(s_val + n_sort);                      // [n_sort]
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int group = n_q_heads / n_kv_heads;
+    const T* qb = Qd + (size_t)b * T_q * n_q_heads * D;
+    // mean query of every kv head: sum over tokens and over the heads of the group
+    for (int e = tid; e < n_kv_heads * D; e += 256) {
+        const int g = e / D, dd = e % D;
+        float a = 0.f;
+        for (int t = 0; t < T_q; ++t)
+            for (int hg = 0; hg < group; ++hg)
+                a += ld(qb + ((size_t)t * n_q_heads + g * group + hg) * D + dd);
+        qbar[e] = a / (float)(T_q * group);
+    }
+    __syncthreads();
+    // one wave per chunk: dot over (g, d), lanes stride over d
+    const int wave = tid >> 6, lane = tid & 63;
+    for (int c = wave; c < n_sort; c += 4) {
+        float a = -INFINITY;
+        if (c < n_chunks) {
+            float acc = 0.f;
+            for (int g = 0; g < n_kv_heads; ++g) {
+                const float* kb = kbar + ((size_t)g * n_chunks + c) * D;
+                float pg = 0.f;
+#pragma unroll
+                for (int x = 0; x < D / 64; ++x) pg = fmaf(qbar[g * D + lane + 64 * x], kb[lane + 64 * x], pg);
+                for (int o = 32; o > 0; o >>= 1) pg += __shfl_xor(pg, o);
+                acc += pg;
+            }
+            a = acc * (scale / (float)n_kv_heads);
+        }
+        if (lane == 0) {
+            s_val[c] = a;
+            s_idx[c] = c < n_chunks ? c : 0x7fffffff;
+            if (scores && c < n_chunks) scores[(size_t)b * n_chunks + c] = a;
+        }
+    }
+    __syncthreads();
+    // bitonic sort, best first
+    for (int size = 2; size <= n_sort; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int i = tid; i < n_sort / 2; i += 256) {
+                const int lo = 2 * i - (i & (stride - 1));
+                const int hi = lo + stride;
+                const bool up = ((lo & size) == 0);
+                const float va = s_val[lo], vb = s_val[hi];
+                const int ia = s_idx[lo], ib = s_idx[hi];
+                const bool a_first = ranks_before(va, ia, vb, ib);
+                if (a_first != up) { s_val[lo] = vb; s_val[hi] = va; s_idx[lo] = ib; s_idx[hi] = ia; }
+            }
+            __syncthreads();
+        }
+    }
+    // membership flags in LDS (the sorted scores are no longer needed), then one coalesced
+    // write of the mask
+    int* flag = (int*)s_val;
+    for (int c = tid; c < n_sort; c += 256) flag[c] = 0;
+    __syncthreads();
+    for (int i = tid; i < k; i += 256) {
+        const int c = s_idx[i];
+        topk_idx[(size_t)b * k + i] = c;
+        if (c < n_chunks) flag[c] = 1;       // (a NaN score could surface a padding slot)
+    }
+    __syncthreads();
+    for (int c = tid; c < n_chunks; c += 256) dense_mask[(size_t)b * n_chunks + c] = (uint8_t)flag[c];
+}
+
+// ------------------------------------------------------------------------------------------
+// Gather.  Step 1 (one block per query): exclusive scan of the rows every chunk contributes
+// (its length if dense, its kept count if sparse) -> dst_off[b, 0..C], mix_len[b].
+// Step 2: every group of LPR lanes copies one mixed row (all kv heads, K and V) with 16-byte
+// accesses; the source row is found by binary search in dst_off.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gather_scan_kernel(const uint8_t* __restrict__ dense_mask,
+                                                          const int32_t* __restrict__ bounds,
+                                                          const int32_t* __restrict__ soff, int n_chunks,
+                                                          int n_prefix, int l_cap,
+                                                          int32_t* __restrict__ dst_off,
+                                                          int32_t* __restrict__ mix_len) {
+    __shared__ int wave_tot[4];
+    __shared__ int carry;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int32_t* out = dst_off + (size_t)b * (n_chunks + 1);
+    if (tid == 0) carry = n_prefix;
+    __syncthreads();
+    for (int base = 0; base < n_chunks; base += 256) {
+        const int c = base + tid;
+        int v = 0;
+        if (c < n_chunks)
+            v = dense_mask[(size_t)b * n_chunks + c] ? bounds[c + 1] - bounds[c] : soff[c + 1] - soff[c];
+        int inc = v;                                         // inclusive scan inside the wave
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(inc, o);
+            if (lane >= o) inc += t;
+        }
+        if (lane == 63) wave_tot[wave] = inc;
+        __syncthreads();
+        int before = carry;
+        for (int w = 0; w < wave; ++w) before += wave_tot[w];
+        if (c < n_chunks) out[c] = before + inc - v;
+        __syncthreads();
+        if (tid == 0) carry += wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        out[n_chunks] = carry;
+        mix_len[b] = min(carry, l_cap);
+    }
+}
+
+template <int ROW_BYTES>
+__global__ __launch_bounds__(256) void gather_copy_kernel(
+    const uint4* __restrict__ K, const uint4* __restrict__ V, const uint8_t* __restrict__ dense_mask,
+    const int32_t* __restrict__ bounds, const int32_t* __restrict__ soff, const int32_t* __restrict__ sidx,
+    const int32_t* __restrict__ dst_off, int n_chunks, int n_prefix, int n_tokens, int n_kv_heads, int l_cap,
+    uint4* __restrict__ Kmix, uint4* __restrict__ Vmix, int32_t* __restrict__ src_idx) {
+    constexpr int LPR = ROW_BYTES / 16;                       // lanes per row
+    constexpr int ROWS = 256 / LPR;                           // rows per block pass
+    const int b = blockIdx.y;
+    const int32_t* off = dst_off + (size_t)b * (n_chunks + 1);
+    const int len = min(off[n_chunks], l_cap);
+    const int r = blockIdx.x * ROWS + threadIdx.x / LPR;
+    const int part = threadIdx.x % LPR;
+    if (r >= len) return;
+    int src;
+    if (r < n_prefix) {
+        src = r;
+    } else {
+        int lo = 0, hi = n_chunks;                            // last chunk with off[c] <= r
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (off[mid] <= r) lo = mid; else hi = mid;
+        }
+        const int o = r - off[lo];
+        src = dense_mask[(size_t)b * n_chunks + lo] ? bounds[lo] + o : sidx[soff[lo] + o];
+    }
+    if (src_idx && part == 0) src_idx[(size_t)b * l_cap + r] = src;
+    for (int g = 0; g < n_kv_heads; ++g) {
+        const size_t s_off = ((size_t)g * n_tokens + src) * LPR + part;
+        const size_t d_off = (((size_t)b * n_kv_heads + g) * l_cap + r) * LPR + part;
+        const uint4 kv = K[s_off];
+        const uint4 vv = V[s_off];
+        Kmix[d_off] = kv;
+        Vmix[d_off] = vv;
+    }
+}
+
+}  // namespace
+
+vxl_status launch_chunk_summarize(const vxl_layout* L, const vxl_attn_desc* d, const void* K,
+                                  float* kbar, hipStream_t s) {
+    const dim3 grid(L->n_chunks, d->n_kv_heads), block(256);
+#define VXL_LAUNCH(T, D)                                                                         \
+    hipLaunchKernelGGL((chunk_summarize_kernel<T, D>), grid, block, 0, s, (const T*)K, L->d_bounds, \
+                       kbar, L->n_tokens, L->n_chunks)
+    if (d->dtype == VXL_F32) { if (d->head_dim == 64) VXL_LAUNCH(float, 64); else VXL_LAUNCH(float, 128); }
+    else { if (d->head_dim == 64) VXL_LAUNCH(uint16_t, 64); else VXL_LAUNCH(uint16_t, 128); }
+#undef VXL_LAUNCH
+    VXL_HIP_TRY(hipGetLastError());
+    return VXL_OK;
+}
+
+vxl_status launch_score_topk(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Qd,
+                             int batch, int T, int k, const float* kbar, int32_t* topk_idx,
+                             uint8_t* dense_mask, float* scores, hipStream_t s) {
+    int n_sort = 2;
+    while (n_sort < L->n_chunks) n_sort <<= 1;
+    const size_t smem = (size_t)d->n_kv_heads * d->head_dim * 4 + (size_t)n_sort * 8;
+    if (smem > 60 * 1024) return VXL_ERR_UNSUPPORTED;
+    const dim3 grid(batch), block(256);
+#define VXL_LAUNCH(T_, D)                                                                          \
+    hipLaunchKernelGGL((score_topk_kernel<T_, D>), grid, block, smem, s, (const T_*)Qd, kbar, T,   \
+                       d->n_q_heads, d->n_kv_heads, L->n_chunks, k, n_sort, scale, topk_idx,       \
+                       dense_mask, scores)
+    if (d->dtype == VXL_F32) { if (d->head_dim == 64) VXL_LAUNCH(float, 64); else VXL_LAUNCH(float, 128); }
+    else { if (d->head_dim == 64) VXL_LAUNCH(uint16_t, 64); else VXL_LAUNCH(uint16_t, 128); }
+#undef VXL_LAUNCH
+    VXL_HIP_TRY(hipGetLastError());
+    return VXL_OK;
+}
+
+vxl_status launch_gather(const vxl_layout* L, const vxl_attn_desc* d, const void* K, const void* V,
+                         const uint8_t* dense_mask, int batch, void* Kmix, void* Vmix, int l_cap,
+                         int32_t* mix_len, int32_t* src_idx, int32_t* ws_offsets, hipStream_t s) {
+    hipLaunchKernelGGL(gather_scan_kernel, dim3(batch), dim3(256), 0, s, dense_mask, L->d_bounds,
+                       L->d_soff, L->n_chunks, L->n_prefix, l_cap, ws_offsets, mix_len);
+    VXL_HIP_TRY(hipGetLastError());
+    const int row_bytes = d->head_dim * (d->dtype == VXL_BF16 ? 2 : 4);
+#define VXL_LAUNCH(RB)                                                                             \
+    do {                                                                                           \
+        constexpr int rows = 256 / (RB / 16);                                                      \
+        const dim3 grid((l_cap + rows - 1) / rows, batch);                                         \
+        hipLaunchKernelGGL((gather_copy_kernel<RB>), grid, dim3(256), 0, s, (const uint4*)K,       \
+                           (const uint4*)V, dense_mask, L->d_bounds, L->d_soff, L->d_sidx,         \
+                           ws_offsets, L->n_chunks, L->n_prefix, L->n_tokens, d->n_kv_heads, l_cap, \
+                           (uint4*)Kmix, (uint4*)Vmix, src_idx);                                   \
+    } while (0)
+    if (row_bytes == 128) VXL_LAUNCH(128);
+    else if (row_bytes == 256) VXL_LAUNCH(256);
+    else VXL_LAUNCH(512);
+#undef VXL_LAUNCH
+    VXL_HIP_TRY(hipGetLastError());
+    return VXL_OK;
+}
+
+}  // namespace vxl

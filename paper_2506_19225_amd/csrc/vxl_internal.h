@@ -1,0 +1,114 @@
+// Internal declarations shared by the host API layer and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "vxl.h"
+
+namespace vxl {
+
+constexpr int kKeyTile = 64;      // keys per K/V tile of the matrix-core kernels
+constexpr int kRowBlock = 32;     // query rows per MFMA block (one 32x32 tile side)
+
+// One pre-filling segment: the prefix (if any) or a chunk.  Queries of a segment attend to the
+// first ctx_len rows of the compacted history buffer and, causally, to their own segment.
+struct Segment {
+    int32_t q_start;    // first token id
+    int32_t q_len;      // tokens in the segment
+    int32_t ctx_len;    // visible history rows: 0 for the prefix, P + sparse_offsets[c] for chunk c
+    int32_t tile_base;  // index of the segment's first own-V tile among the own tiles
+};
+
+struct WorkItem {
+    int32_t seg;
+    int32_t m_tile;     // query row tile inside the segment
+};
+
+}  // namespace vxl
+
+struct vxl_layout {
+    int32_t n_tokens = 0, n_prefix = 0, n_chunks = 0, s_total = 0;
+    std::vector<int32_t> bounds, soff, sidx;          // host copies
+    int device = 0;
+
+    // ---- device metadata (single allocation `d_blob`) ----
+    void* d_blob = nullptr;
+    size_t blob_bytes = 0;
+    int32_t* d_bounds = nullptr;      // [C+1]
+    int32_t* d_soff = nullptr;        // [C+1]
+    int32_t* d_sidx = nullptr;        // [S_total]
+    // pre-filling schedule
+    int32_t n_seg = 0;
+    int32_t l_ctx = 0;                // P + S_total rows of compacted history
+    int32_t n_ctx_tiles = 0;          // ceil(l_ctx / 64)
+    int32_t n_own_tiles = 0;          // sum over segments of ceil(q_len / 64)
+    std::vector<vxl::Segment> segs;   // host copy
+    vxl::Segment* d_segs = nullptr;   // [n_seg]
+    int32_t* d_tile_src = nullptr;    // [(n_ctx_tiles + n_own_tiles) * 64] source token per
+                                      // tile slot, -1 = padding
+    vxl::WorkItem* d_work[2] = {nullptr, nullptr};   // heaviest-first items for 128 / 256 rows
+    int32_t n_work[2] = {0, 0};
+    int64_t pair_count = 0;
+};
+
+namespace vxl {
+
+void set_last_error(const char* what, hipError_t e);
+
+#define VXL_HIP_TRY(expr)                                        \
+    do {                                                         \
+        hipError_t _e = (expr);                                  \
+        if (_e != hipSuccess) {                                  \
+            ::vxl::set_last_error(#expr, _e);                    \
+            return VXL_ERR_HIP;                                  \
+        }                                                        \
+    } while (0)
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- pre-filling ----
+struct PrefillWorkspace {      // byte offsets into the caller's workspace (bf16 path)
+    size_t kctx;               // [Hkv][n_ctx_tiles*64][D]
+    size_t vt;                 // [Hkv][n_ctx_tiles + n_own_tiles][D][64] (key-permuted tiles)
+    size_t total;
+};
+PrefillWorkspace prefill_workspace(const vxl_layout* L, const vxl_attn_desc* d);
+
+vxl_status launch_prefill_bf16(const vxl_layout* L, const vxl_attn_desc* d, float scale,
+                               const void* Q, const void* K, const void* V, void* O, float* LSE,
+                               void* ws, hipStream_t s);
+vxl_status launch_prefill_simple(const vxl_layout* L, const vxl_attn_desc* d, float scale,
+                                 const void* Q, const void* K, const void* V, void* O, float* LSE,
+                                 hipStream_t s);
+
+// ---- scoring / selection / gather ----
+vxl_status launch_chunk_summarize(const vxl_layout* L, const vxl_attn_desc* d, const void* K,
+                                  float* kbar, hipStream_t s);
+vxl_status launch_score_topk(const vxl_layout* L, const vxl_attn_desc* d, float scale,
+                             const void* Qd, int batch, int T, int k, const float* kbar,
+                             int32_t* topk_idx, uint8_t* dense_mask, float* scores, hipStream_t s);
+vxl_status launch_gather(const vxl_layout* L, const vxl_attn_desc* d, const void* K, const void* V,
+                         const uint8_t* dense_mask, int batch, void* Kmix, void* Vmix, int l_cap,
+                         int32_t* mix_len, int32_t* src_idx, int32_t* ws_offsets, hipStream_t s);
+
+// ---- decode ----
+struct DecodePlan {
+    int n_split;        // key splits per (batch, kv head)
+    int split_len;      // keys per split (multiple of 64)
+    size_t part_o;      // byte offsets into the workspace
+    size_t part_ml;
+    size_t total;
+};
+DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap);
+
+vxl_status launch_decode_bf16(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
+                              const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len,
+                              void* O, float* LSE, void* ws, hipStream_t s);
+vxl_status launch_decode_simple(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
+                                const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len,
+                                void* O, float* LSE, hipStream_t s);
+
+}  // namespace vxl

@@ -1,0 +1,219 @@
+"""ctypes binding of libvxl.so: the same entry points as include/vxl.h, argument marshalling
+only.  Every step of the path runs in the HIP kernels of the library; torch is used for device
+memory and streams.  Loading fails loudly when the library has not been built -- there is no
+fallback path."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+import torch  # imported before the library so that both use the one HIP runtime torch loaded
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libvxl.so")
+
+VXL_OK, VXL_ERR_INVALID_ARG, VXL_ERR_UNSUPPORTED, VXL_ERR_WORKSPACE, VXL_ERR_HIP = range(5)
+VXL_F32, VXL_BF16 = 0, 1
+OP_PREFILL, OP_SCORE_TOPK, OP_GATHER, OP_DECODE = range(4)
+MAX_CHUNKS = 4096
+
+
+class AttnDesc(C.Structure):
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("dtype", C.c_int32), ("softmax_scale", C.c_float)]
+
+
+class VxlError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().vxl_status_string(status).decode()
+        extra = lib().vxl_last_error().decode() if status == VXL_ERR_HIP else ""
+        super().__init__(f"{where}: {msg}" + (f" ({extra})" if extra else ""))
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library (raises if it has not been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2506_19225_amd.build` "
+                           "(or __graft_entry__.build()) first; there is no fallback path")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    dp = C.POINTER(AttnDesc)
+    L.vxl_version.restype = C.c_int
+    L.vxl_status_string.restype = C.c_char_p
+    L.vxl_status_string.argtypes = [C.c_int]
+    L.vxl_last_error.restype = C.c_char_p
+    L.vxl_layout_create.restype = C.c_int
+    L.vxl_layout_create.argtypes = [i32, i32, i32, vp, vp, vp, vp, C.POINTER(vp)]
+    L.vxl_layout_destroy.restype = C.c_int
+    L.vxl_layout_destroy.argtypes = [vp]
+    L.vxl_workspace_bytes.restype = sz
+    L.vxl_workspace_bytes.argtypes = [C.c_int, vp, dp, i32, i32, i32]
+    L.vxl_mixed_kv_capacity.restype = i32
+    L.vxl_mixed_kv_capacity.argtypes = [vp, i32]
+    L.vxl_prefill_pair_count.restype = C.c_int64
+    L.vxl_prefill_pair_count.argtypes = [vp]
+    L.vxl_chunk_prefill.restype = C.c_int
+    L.vxl_chunk_prefill.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.vxl_chunk_score_topk.restype = C.c_int
+    L.vxl_chunk_score_topk.argtypes = [vp, dp, vp, i32, i32, vp, i32, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.vxl_gather_bilevel_kv.restype = C.c_int
+    L.vxl_gather_bilevel_kv.argtypes = [vp, dp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, sz, vp]
+    L.vxl_bilevel_decode.restype = C.c_int
+    L.vxl_bilevel_decode.argtypes = [dp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.vxl_debug_force_simple.argtypes = [C.c_int]
+    L.vxl_debug_prefill_rows_per_wave.argtypes = [C.c_int]
+    _lib = L
+    return L
+
+
+def _check(status: int, where: str) -> None:
+    if status != VXL_OK:
+        raise VxlError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA tensors"
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def make_desc(n_q_heads: int, n_kv_heads: int, head_dim: int, dtype, softmax_scale: float = 0.0) -> AttnDesc:
+    if dtype in (torch.bfloat16, "bf16", VXL_BF16):
+        code = VXL_BF16
+    elif dtype in (torch.float32, "f32", VXL_F32):
+        code = VXL_F32
+    else:
+        raise ValueError(f"unsupported dtype {dtype}")
+    return AttnDesc(n_q_heads, n_kv_heads, head_dim, code, float(softmax_scale))
+
+
+def torch_dtype(desc: AttnDesc):
+    return torch.bfloat16 if desc.dtype == VXL_BF16 else torch.float32
+
+
+class Layout:
+    """Owns a vxl_layout handle (vxl_layout_create / vxl_layout_destroy)."""
+
+    def __init__(self, n_prefix: int, chunk_bounds, sparse_offsets, sparse_idx, stream=None,
+                 n_tokens: Optional[int] = None):
+        self.bounds = np.ascontiguousarray(chunk_bounds, dtype=np.int32)
+        self.soff = np.ascontiguousarray(sparse_offsets, dtype=np.int32)
+        self.sidx = np.ascontiguousarray(sparse_idx, dtype=np.int32)
+        self.n_prefix = int(n_prefix)
+        self.n_chunks = len(self.bounds) - 1
+        self.n_tokens = int(self.bounds[-1]) if n_tokens is None else int(n_tokens)
+        handle = C.c_void_p()
+        st = lib().vxl_layout_create(
+            self.n_tokens, self.n_prefix, self.n_chunks, self.bounds.ctypes.data, self.soff.ctypes.data,
+            self.sidx.ctypes.data if self.sidx.size else None, _stream(stream), C.byref(handle))
+        _check(st, "vxl_layout_create")
+        self.handle = handle
+
+    def close(self) -> None:
+        if getattr(self, "handle", None):
+            lib().vxl_layout_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def mixed_kv_capacity(self, k: int) -> int:
+        return int(lib().vxl_mixed_kv_capacity(self.handle, int(k)))
+
+    def pair_count(self) -> int:
+        return int(lib().vxl_prefill_pair_count(self.handle))
+
+
+def workspace_bytes(op: int, layout: Optional[Layout], desc: AttnDesc, batch: int = 0,
+                    n_q_tokens: int = 0, l_cap: int = 0) -> int:
+    return int(lib().vxl_workspace_bytes(op, layout.handle if layout is not None else None,
+                                         C.byref(desc), batch, n_q_tokens, l_cap))
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def chunk_prefill(layout: Layout, desc: AttnDesc, q, k, v, out, lse=None, workspace=None, stream=None):
+    """vxl_chunk_prefill: q/out [Hq,N,D], k/v [Hkv,N,D]; lse float32 [Hq,N] or None."""
+    st = lib().vxl_chunk_prefill(layout.handle, C.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
+                                 _ptr(lse), _ptr(workspace), workspace.numel() if workspace is not None else 0,
+                                 _stream(stream))
+    _check(st, "vxl_chunk_prefill")
+    return out
+
+
+def chunk_score_topk(layout: Layout, desc: AttnDesc, qd, k, top_k: int, topk_idx, dense_mask,
+                     scores=None, kbar=None, kbar_ready: bool = False, workspace=None, stream=None):
+    """vxl_chunk_score_topk: qd [B,T,Hq,D]; topk_idx int32 [B,min(k,C)]; dense_mask uint8 [B,C]."""
+    b, t = int(qd.shape[0]), int(qd.shape[1])
+    st = lib().vxl_chunk_score_topk(layout.handle, C.byref(desc), _ptr(qd), b, t, _ptr(k), int(top_k),
+                                    _ptr(kbar), int(bool(kbar_ready)), _ptr(topk_idx), _ptr(dense_mask),
+                                    _ptr(scores), _ptr(workspace),
+                                    workspace.numel() if workspace is not None else 0, _stream(stream))
+    _check(st, "vxl_chunk_score_topk")
+
+
+def gather_bilevel_kv(layout: Layout, desc: AttnDesc, k, v, dense_mask, kmix, vmix, mix_len,
+                      src_idx=None, workspace=None, stream=None):
+    """vxl_gather_bilevel_kv: kmix/vmix [B,Hkv,Lcap,D]; mix_len int32 [B]; src_idx int32 [B,Lcap]."""
+    b, l_cap = int(kmix.shape[0]), int(kmix.shape[2])
+    st = lib().vxl_gather_bilevel_kv(layout.handle, C.byref(desc), _ptr(k), _ptr(v), _ptr(dense_mask), b,
+                                     _ptr(kmix), _ptr(vmix), l_cap, _ptr(mix_len), _ptr(src_idx),
+                                     _ptr(workspace), workspace.numel() if workspace is not None else 0,
+                                     _stream(stream))
+    _check(st, "vxl_gather_bilevel_kv")
+
+
+def bilevel_decode(desc: AttnDesc, qd, kmix, vmix, mix_len, out, lse=None, workspace=None, stream=None):
+    """vxl_bilevel_decode: qd/out [B,T,Hq,D]; kmix/vmix [B,Hkv,Lcap,D]; mix_len int32 [B]."""
+    b, t = int(qd.shape[0]), int(qd.shape[1])
+    l_cap = int(kmix.shape[2])
+    st = lib().vxl_bilevel_decode(C.byref(desc), _ptr(qd), b, t, _ptr(kmix), _ptr(vmix), l_cap,
+                                  _ptr(mix_len), _ptr(out), _ptr(lse), _ptr(workspace),
+                                  workspace.numel() if workspace is not None else 0, _stream(stream))
+    _check(st, "vxl_bilevel_decode")
+    return out
+
+
+def debug_force_simple(on: bool) -> None:
+    """Route BF16 calls through the plain vector-ALU kernels (on-device cross-check)."""
+    lib().vxl_debug_force_simple(int(bool(on)))
+
+
+def debug_prefill_rows_per_wave(blocks: int) -> None:
+    lib().vxl_debug_prefill_rows_per_wave(int(blocks))
+
+
+# ---------------------------------------------------------------------------------------------
+# host <-> device marshalling of the storage dtypes (numpy has no bfloat16)
+# ---------------------------------------------------------------------------------------------
+def to_device(x: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
+    """float32 numpy array holding storage-precision values -> device tensor of that dtype."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+    if dtype == "bf16":
+        return t.to(torch.bfloat16).to(device)     # exact: values are bf16-representable
+    return t.to(device)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy()

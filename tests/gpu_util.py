@@ -1,0 +1,95 @@
+"""Helpers of the GPU parity tests: run the four C-ABI calls through the ctypes binding on
+seeded inputs and return host arrays; tolerance checks as stated for the path."""
+import numpy as np
+import torch
+
+from paper_2506_19225_amd import vxl, workloads as wl
+
+# Matching rules: fp32 storage -- max abs error <= 1e-5; bf16 storage with fp32 accumulation --
+# max abs error <= 2e-2 and relative Frobenius error <= 1e-2, per query head.
+TOL_F32_ABS = 1e-5
+TOL_BF16_ABS = 2e-2
+TOL_BF16_REL = 1e-2
+
+
+def assert_close(got, want, dtype, head_axis=0, what=""):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, (got.shape, want.shape)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    err = np.abs(got - want)
+    if dtype == "f32":
+        assert err.max() <= TOL_F32_ABS, f"{what}: max abs err {err.max():.3e}"
+        return
+    assert err.max() <= TOL_BF16_ABS, f"{what}: max abs err {err.max():.3e}"
+    g = np.moveaxis(got, head_axis, 0).reshape(got.shape[head_axis], -1)
+    w = np.moveaxis(want, head_axis, 0).reshape(want.shape[head_axis], -1)
+    rel = np.linalg.norm(g - w, axis=1) / np.maximum(np.linalg.norm(w, axis=1), 1e-30)
+    assert rel.max() <= TOL_BF16_REL, f"{what}: rel Frobenius err {rel.max():.3e} (per head {rel})"
+
+
+def make_layout(lay: wl.Layout) -> vxl.Layout:
+    return vxl.Layout(lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx)
+
+
+def desc_of(w: wl.Workload, scale: float = 0.0):
+    return vxl.make_desc(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, scale)
+
+
+def gpu_prefill(w, lay, q, k, v, scale=0.0, want_lse=False, gl=None, dev=None):
+    """Returns O (float32 host array [Hq,N,D]) and optionally LSE."""
+    gl = gl or make_layout(lay)
+    desc = desc_of(w, scale)
+    dq, dk, dv = (dev if dev is not None else [vxl.to_device(x, w.dtype) for x in (q, k, v)])
+    out = torch.full_like(dq, float("nan"))
+    lse = torch.full(dq.shape[:2], float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
+    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_PREFILL, gl, desc))
+    vxl.chunk_prefill(gl, desc, dq, dk, dv, out, lse, ws)
+    torch.cuda.synchronize()
+    res = vxl.to_host(out)
+    return (res, vxl.to_host(lse)) if want_lse else res
+
+
+def gpu_score_topk(w, lay, qd, k, top_k, gl=None, scale=0.0):
+    gl = gl or make_layout(lay)
+    desc = desc_of(w, scale)
+    dqd, dk = vxl.to_device(qd, w.dtype), vxl.to_device(k, w.dtype)
+    bsz, c_n = qd.shape[0], lay.n_chunks
+    kk = min(top_k, c_n)
+    idx = torch.full((bsz, max(kk, 1)), -7, dtype=torch.int32, device="cuda")
+    mask = torch.full((bsz, max(c_n, 1)), 9, dtype=torch.uint8, device="cuda")
+    scores = torch.full((bsz, max(c_n, 1)), float("nan"), dtype=torch.float32, device="cuda")
+    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_SCORE_TOPK, gl, desc, bsz, qd.shape[1]))
+    vxl.chunk_score_topk(gl, desc, dqd, dk, top_k, idx, mask, scores, workspace=ws)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy()[:, :kk], mask.cpu().numpy()[:, :c_n], scores.cpu().numpy()[:, :c_n]
+
+
+def gpu_gather(w, lay, k, v, dense_mask, l_cap, gl=None, dev=None):
+    """Returns kmix, vmix (float32 host), mix_len, src_idx; untouched rows keep a sentinel."""
+    gl = gl or make_layout(lay)
+    desc = desc_of(w)
+    dk, dv = dev if dev is not None else (vxl.to_device(k, w.dtype), vxl.to_device(v, w.dtype))
+    bsz = dense_mask.shape[0]
+    dm = torch.from_numpy(np.ascontiguousarray(dense_mask, dtype=np.uint8)).cuda()
+    kmix = torch.full((bsz, w.n_kv_heads, l_cap, w.head_dim), 7.0, dtype=dk.dtype, device="cuda")
+    vmix = torch.full_like(kmix, 7.0)
+    mix_len = torch.full((bsz,), -1, dtype=torch.int32, device="cuda")
+    src = torch.full((bsz, l_cap), -5, dtype=torch.int32, device="cuda")
+    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_GATHER, gl, desc, bsz))
+    vxl.gather_bilevel_kv(gl, desc, dk, dv, dm, kmix, vmix, mix_len, src, ws)
+    torch.cuda.synchronize()
+    return kmix, vmix, mix_len, src
+
+
+def gpu_decode(w, qd, kmix_dev, vmix_dev, mix_len_dev, scale=0.0, want_lse=False):
+    desc = desc_of(w, scale)
+    dqd = vxl.to_device(qd, w.dtype)
+    out = torch.full_like(dqd, float("nan"))
+    lse = torch.full(dqd.shape[:3], float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
+    bsz, t = qd.shape[0], qd.shape[1]
+    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_DECODE, None, desc, bsz, t, kmix_dev.shape[2]))
+    vxl.bilevel_decode(desc, dqd, kmix_dev, vmix_dev, mix_len_dev, out, lse, ws)
+    torch.cuda.synchronize()
+    res = vxl.to_host(out)
+    return (res, vxl.to_host(lse)) if want_lse else res

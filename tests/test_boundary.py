@@ -1,0 +1,93 @@
+"""CPU-side checks of the C-ABI boundary: the library loads, exports every symbol the header
+declares, and rejects malformed arguments on the host before touching a device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2506_19225_amd import vxl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "vxl.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vxl_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = vxl.lib()
+    names = declared_symbols()
+    assert {"vxl_chunk_prefill", "vxl_chunk_score_topk", "vxl_gather_bilevel_kv", "vxl_bilevel_decode",
+            "vxl_layout_create", "vxl_layout_destroy", "vxl_workspace_bytes", "vxl_mixed_kv_capacity",
+            "vxl_status_string", "vxl_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"libvxl.so does not export {n}"
+    assert lib.vxl_version() >= 100
+    assert lib.vxl_status_string(0) == b"ok"
+    assert b"workspace" in lib.vxl_status_string(vxl.VXL_ERR_WORKSPACE)
+
+
+def create(n_tokens, n_prefix, bounds, soff, sidx):
+    b = np.asarray(bounds, np.int32)
+    o = np.asarray(soff, np.int32)
+    i = np.asarray(sidx, np.int32)
+    h = C.c_void_p()
+    st = vxl.lib().vxl_layout_create(n_tokens, n_prefix, len(b) - 1, b.ctypes.data, o.ctypes.data,
+                                     i.ctypes.data if i.size else None, None, C.byref(h))
+    return st, h
+
+
+@pytest.mark.parametrize("args", [
+    (10, 2, [2, 6, 9], [0, 1, 2], [2, 6]),          # last bound != n_tokens
+    (10, 2, [3, 6, 10], [0, 1, 2], [3, 6]),         # first bound != n_prefix
+    (10, 2, [2, 6, 6, 10], [0, 1, 1, 2], [2, 6]),   # empty chunk
+    (10, 2, [2, 6, 10], [1, 1, 2], [2, 6]),         # offsets do not start at 0
+    (10, 2, [2, 6, 10], [0, 2, 1], [2, 3]),         # offsets decrease
+    (10, 2, [2, 6, 10], [0, 1, 2], [6, 7]),         # kept id outside its chunk
+    (10, 2, [2, 6, 10], [0, 2, 3], [3, 3, 7]),      # duplicate kept id
+    (10, 2, [2, 6, 10], [0, 2, 3], [4, 3, 7]),      # unsorted kept ids
+    (0, 0, [0], [0], []),                           # no tokens
+])
+def test_layout_create_rejects_malformed_layouts_on_the_host(args):
+    st, h = create(*args)
+    assert st == vxl.VXL_ERR_INVALID_ARG and not h.value
+
+
+def test_layout_create_rejects_null_and_oversized():
+    h = C.c_void_p()
+    assert vxl.lib().vxl_layout_create(4, 0, 1, None, None, None, None, C.byref(h)) == vxl.VXL_ERR_INVALID_ARG
+    n = vxl.MAX_CHUNKS + 1
+    st, h = create(n, 0, list(range(n + 1)), [0] * (n + 1), [])
+    assert st == vxl.VXL_ERR_UNSUPPORTED
+
+
+def test_hot_calls_reject_bad_descriptors_before_launch():
+    lib = vxl.lib()
+    fake = C.c_void_p(0x1000)          # never dereferenced: validation fails first
+    for desc, want in [
+        (vxl.make_desc(28, 4, 96, "bf16"), vxl.VXL_ERR_UNSUPPORTED),
+        (vxl.make_desc(28, 5, 128, "bf16"), vxl.VXL_ERR_INVALID_ARG),
+        (vxl.make_desc(28, 4, 128, "bf16", -1.0), vxl.VXL_ERR_INVALID_ARG),
+        (vxl.AttnDesc(28, 4, 128, 7, 0.0), vxl.VXL_ERR_UNSUPPORTED),
+    ]:
+        st = lib.vxl_bilevel_decode(C.byref(desc), fake, 1, 1, fake, fake, 64, fake, fake, None, fake, 1 << 20, None)
+        assert st == want
+        assert lib.vxl_workspace_bytes(vxl.OP_DECODE, None, C.byref(desc), 1, 1, 64) == 0
+    good = vxl.make_desc(28, 4, 128, "bf16")
+    assert lib.vxl_bilevel_decode(C.byref(good), None, 1, 1, fake, fake, 64, fake, fake, None, fake, 1 << 20, None) \
+        == vxl.VXL_ERR_INVALID_ARG
+    assert lib.vxl_bilevel_decode(C.byref(good), fake, 0, 1, fake, fake, 64, fake, fake, None, fake, 1 << 20, None) \
+        == vxl.VXL_ERR_INVALID_ARG
+    odd = C.c_void_p(0x1004)           # misaligned base pointer
+    assert lib.vxl_bilevel_decode(C.byref(good), odd, 1, 1, fake, fake, 64, fake, fake, None, fake, 1 << 20, None) \
+        == vxl.VXL_ERR_INVALID_ARG
+    assert lib.vxl_bilevel_decode(C.byref(good), fake, 1, 1, fake, fake, 4096, fake, fake, None, None, 0, None) \
+        == vxl.VXL_ERR_WORKSPACE
+    assert lib.vxl_chunk_prefill(None, C.byref(good), fake, fake, fake, fake, None, fake, 1 << 20, None) \
+        == vxl.VXL_ERR_INVALID_ARG
+    assert lib.vxl_workspace_bytes(vxl.OP_DECODE, None, C.byref(good), 1, 32, 4096) > 0
+    assert lib.vxl_mixed_kv_capacity(None, 3) == 0

@@ -1,0 +1,348 @@
+"""GPU parity: every C-ABI call against the float64 oracle on the same seeded inputs.
+Integer outputs and gathered KV are compared bit for bit; attention outputs within the stated
+tolerances (gpu_util)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_19225_amd import vxl, workloads as wl
+
+from gpu_util import (assert_close, desc_of, gpu_decode, gpu_gather, gpu_prefill, gpu_score_topk,
+                      make_layout)
+
+pytestmark = pytest.mark.gpu
+
+
+def lay_args(lay):
+    return lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx
+
+
+def oracle_prefill(q, k, v, lay, **kw):
+    return oracle.prefill_blk(q, k, v, lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx, **kw)
+
+
+# --------------------------------------------------------------------------------- prefill
+def test_prefill_config0_fp32():
+    w = wl.WORKLOADS["config0"]
+    lay = wl.make_layout(w)
+    q, k, v = wl.make_qkv(w, lay)
+    got, lse = gpu_prefill(w, lay, q, k, v, want_lse=True)
+    want, wlse = oracle_prefill(q, k, v, lay, return_lse=True)
+    assert_close(got, want, "f32", what="config0 prefill")
+    assert np.abs(lse - wlse).max() < 1e-4
+
+
+TINY_CASES = [
+    # (dtype, Hq, Hkv, D, P, n_chunks, len_lo, len_hi, seed)
+    ("f32", 2, 1, 64, 0, 3, 1, 40, 100),
+    ("f32", 4, 2, 128, 5, 4, 3, 70, 101),
+    ("bf16", 4, 2, 128, 0, 3, 1, 50, 102),
+    ("bf16", 6, 2, 64, 7, 5, 2, 90, 103),
+    ("bf16", 7, 1, 128, 70, 4, 60, 200, 104),
+    ("bf16", 2, 2, 128, 129, 3, 127, 300, 105),
+]
+
+
+@pytest.mark.parametrize("case", TINY_CASES, ids=lambda c: f"{c[0]}-h{c[1]}-d{c[3]}-p{c[4]}-s{c[8]}")
+@pytest.mark.parametrize("qb", [1, 2])
+def test_prefill_ragged_layouts(case, qb):
+    dtype, hq, hkv, d, p, nc, lo, hi, seed = case
+    if dtype == "f32" and qb == 2:
+        pytest.skip("row-block count only applies to the matrix-core kernel")
+    rng = np.random.default_rng(seed)
+    lay = wl.random_layout(rng, p, nc, lo, hi)
+    w = wl.tiny_workload(dtype, hq, hkv, d, T=2, B=1, k=1, seed=seed)
+    q, k, v = wl.make_qkv(w, lay)
+    vxl.debug_prefill_rows_per_wave(qb)
+    try:
+        got, lse = gpu_prefill(w, lay, q, k, v, want_lse=True)
+    finally:
+        vxl.debug_prefill_rows_per_wave(1)
+    want, wlse = oracle_prefill(q, k, v, lay, return_lse=True)
+    assert_close(got, want, dtype, what=f"ragged prefill {case}")
+    assert np.abs(lse - wlse).max() < (1e-4 if dtype == "f32" else 2e-2)
+
+
+def test_prefill_edge_layouts_bf16():
+    """No prefix and no kept tokens (block diagonal); everything kept (dense causal); one chunk;
+    prefix only."""
+    w = wl.tiny_workload("bf16", 4, 2, 128, T=1, B=1, k=1, seed=7, value_scale=0.5)
+    lens = [65, 130, 64]
+    empty = [np.zeros(0, np.int32)] * 3
+    full, s = [], 3
+    for ln in lens:
+        full.append(np.arange(s, s + ln))
+        s += ln
+    for lay in (wl.layout_from_lists(0, lens, empty),
+                wl.layout_from_lists(3, lens, full),
+                wl.layout_from_lists(0, [200], [np.zeros(0, np.int32)]),
+                wl.layout_from_lists(150, [], [])):
+        q, k, v = wl.make_qkv(w, lay)
+        got = gpu_prefill(w, lay, q, k, v)
+        assert_close(got, oracle_prefill(q, k, v, lay), "bf16", what="edge layout")
+
+
+@pytest.mark.parametrize("qb", [1, 2])
+def test_prefill_medium_bf16_sharp_softmax(qb):
+    """Several 256-token chunks at GQA 14/2, with logits of std ~3 so that the running maximum
+    moves and the rescaling path is exercised."""
+    w = wl.tiny_workload("bf16", 14, 2, 128, T=4, B=1, k=2, seed=21, value_scale=1.0)
+    lens = [256, 256, 320, 192, 256]
+    kept, s = [], 256
+    for ln in lens:
+        kept.append(wl.strided_kept(s, ln, ln // 8))
+        s += ln
+    lay = wl.layout_from_lists(256, lens, kept)
+    q, k, v = wl.make_qkv(w, lay)
+    q = wl.round_to_bf16(q * np.float32(3.0))        # q.k/sqrt(128) then has std 3
+    vxl.debug_prefill_rows_per_wave(qb)
+    try:
+        got, lse = gpu_prefill(w, lay, q, k, v, want_lse=True)
+    finally:
+        vxl.debug_prefill_rows_per_wave(1)
+    want, wlse = oracle_prefill(q, k, v, lay, return_lse=True)
+    assert_close(got, want, "bf16", what="medium sharp prefill")
+    assert np.abs(lse - wlse).max() < 2e-2
+
+
+def test_prefill_matrix_core_kernel_agrees_with_vector_kernel_on_device():
+    w = wl.tiny_workload("bf16", 8, 2, 128, T=1, B=1, k=1, seed=31, value_scale=0.3)
+    rng = np.random.default_rng(31)
+    lay = wl.random_layout(rng, 33, 6, 30, 260)
+    q, k, v = wl.make_qkv(w, lay)
+    a = gpu_prefill(w, lay, q, k, v)
+    vxl.debug_force_simple(True)
+    try:
+        b = gpu_prefill(w, lay, q, k, v)
+    finally:
+        vxl.debug_force_simple(False)
+    want = oracle_prefill(q, k, v, lay)
+    assert_close(a, want, "bf16", what="mfma")
+    assert_close(b, want, "bf16", what="simple")
+
+
+def sample_rows(lay, rng, n_full_chunks=3):
+    """First/last row of every segment plus all rows of a few chunks (first, middle, last)."""
+    rows = set(range(min(lay.n_prefix, 4))) | ({lay.n_prefix - 1} if lay.n_prefix else set())
+    c_n = lay.n_chunks
+    for c in range(c_n):
+        rows.add(int(lay.chunk_bounds[c]))
+        rows.add(int(lay.chunk_bounds[c + 1]) - 1)
+    picks = sorted(set([0, 1, c_n // 2, c_n - 2, c_n - 1][:n_full_chunks + 2]) & set(range(c_n)))
+    for c in picks:
+        rows |= set(range(int(lay.chunk_bounds[c]), int(lay.chunk_bounds[c + 1])))
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+@pytest.mark.parametrize("qb", [1, 2])
+def test_prefill_config1_sampled_rows(qb):
+    w = wl.WORKLOADS["config1"]
+    lay = wl.make_layout(w)
+    q, k, v = wl.make_qkv(w, lay)
+    vxl.debug_prefill_rows_per_wave(qb)
+    try:
+        got = gpu_prefill(w, lay, q, k, v)
+    finally:
+        vxl.debug_prefill_rows_per_wave(1)
+    rows = sample_rows(lay, np.random.default_rng(0))
+    want = oracle_prefill(q, k, v, lay, rows=rows)
+    assert_close(got[:, rows], want, "bf16", what="config1 prefill")
+    assert np.isfinite(got).all()
+
+
+def test_prefill_locality_and_determinism_bit_exact():
+    """Changing K/V of a token that is not kept changes only later rows of its own chunk, bit
+    for bit; two runs on the same inputs are bit-identical."""
+    w = wl.tiny_workload("bf16", 4, 2, 128, T=1, B=1, k=1, seed=41, value_scale=0.3)
+    lens = [100, 140, 90]
+    kept = [np.array([40, 41, 99]), np.array([140, 200]), np.array([281])]
+    lay = wl.layout_from_lists(40, lens, kept)
+    q, k, v = wl.make_qkv(w, lay)
+    base = gpu_prefill(w, lay, q, k, v)
+    again = gpu_prefill(w, lay, q, k, v)
+    assert np.array_equal(base, again)
+    j = 170                                            # chunk 1 = [140, 280), not kept
+    k2, v2 = k.copy(), v.copy()
+    k2[:, j] = wl.round_to_bf16(k2[:, j] + 1.0)
+    v2[:, j] = wl.round_to_bf16(v2[:, j] - 2.0)
+    pert = gpu_prefill(w, lay, q, k2, v2)
+    changed = (pert != base).any(axis=(0, 2))
+    assert changed[170:280].any()
+    assert not changed[:170].any() and not changed[280:].any()
+
+
+# --------------------------------------------------------------------------------- score / top-k
+def check_topk(w, lay, qd, k, top_k):
+    idx, mask, scores = gpu_score_topk(w, lay, qd, k, top_k)
+    want_s = oracle.chunk_scores(qd, k, lay.chunk_bounds)
+    assert np.abs(scores - want_s).max() <= 2e-5 * np.abs(want_s).max() + 1e-7
+    want_idx, want_mask = oracle.select_topk(want_s, top_k)
+    kk = min(top_k, lay.n_chunks)
+    # the decision is only defined when the rank-k margin exceeds the fp32 score error
+    srt = np.sort(want_s, axis=1)[:, ::-1]
+    if 0 < kk < lay.n_chunks:
+        margin = (srt[:, kk - 1] - srt[:, kk]).min()
+        assert margin > 1e-6 * np.abs(want_s).max(), "degenerate seed: rank-k margin too small"
+    assert np.array_equal(mask, want_mask)
+    assert np.array_equal(np.sort(idx, axis=1), np.sort(want_idx, axis=1))
+    # the device's own order is consistent with its own scores (descending, ties by id)
+    for b in range(idx.shape[0]):
+        key = [(-scores[b, c], c) for c in idx[b]]
+        assert key == sorted(key)
+    return idx, mask
+
+
+def test_score_topk_config0_and_config1():
+    for name in ("config0", "config1"):
+        w = wl.WORKLOADS[name]
+        lay = wl.make_layout(w)
+        _, k, _ = wl.make_qkv(w, lay, with_q=False)
+        qd = wl.make_decode_queries(w)
+        for top_k in (0, 1, w.k, lay.n_chunks, lay.n_chunks + 5):
+            check_topk(w, lay, qd, k, top_k)
+
+
+def test_score_topk_ragged_and_ties():
+    rng = np.random.default_rng(51)
+    for dtype, d in (("f32", 64), ("bf16", 128)):
+        w = wl.tiny_workload(dtype, 6, 2, d, T=3, B=3, k=2, seed=51)
+        lay = wl.random_layout(rng, 5, 13, 1, 300)
+        _, k, _ = wl.make_qkv(w, lay, with_q=False)
+        qd = wl.make_decode_queries(w)
+        for top_k in (1, 4, 13):
+            check_topk(w, lay, qd, k, top_k)
+    # exact ties: chunks 1, 3, 4 hold identical keys -> identical scores -> lower ids win
+    w = wl.tiny_workload("bf16", 4, 2, 128, T=2, B=1, k=2, seed=52)
+    ln = 70
+    lay = wl.layout_from_lists(3, [ln] * 5, [np.zeros(0, np.int32)] * 5)
+    _, k, _ = wl.make_qkv(w, lay, with_q=False)
+    qd = np.abs(wl.make_decode_queries(w))
+    blk = np.abs(k[:, 3 + ln:3 + 2 * ln]).copy()
+    for c in (1, 3, 4):
+        k[:, 3 + c * ln:3 + (c + 1) * ln] = blk
+    for c in (0, 2):
+        k[:, 3 + c * ln:3 + (c + 1) * ln] = -np.abs(k[:, 3 + c * ln:3 + (c + 1) * ln])
+    idx, mask, scores = gpu_score_topk(w, lay, qd, k, 2)
+    assert scores[0, 1] == scores[0, 3] == scores[0, 4]
+    assert list(idx[0]) == [1, 3] and list(mask[0]) == [0, 1, 0, 1, 0]
+
+
+# --------------------------------------------------------------------------------- gather
+def check_gather(w, lay, k, v, masks, l_cap):
+    kmix, vmix, mix_len, src = gpu_gather(w, lay, k, v, masks, l_cap)
+    wk, wv, wlen, wsrc = oracle.gather_bilevel(k, v, masks, *lay_args(lay), l_cap=l_cap)
+    assert np.array_equal(mix_len.cpu().numpy(), wlen)
+    hk, hv, hsrc = vxl.to_host(kmix), vxl.to_host(vmix), src.cpu().numpy()
+    for b in range(masks.shape[0]):
+        n = wlen[b]
+        assert np.array_equal(hsrc[b, :n], wsrc[b, :n])
+        assert np.array_equal(hk[b, :, :n], wk[b, :, :n])          # bit-exact (exact upcast)
+        assert np.array_equal(hv[b, :, :n], wv[b, :, :n])
+        assert (hk[b, :, n:] == 7.0).all() and (hsrc[b, n:] == -5).all()   # rows beyond untouched
+    return kmix, vmix, mix_len
+
+
+def test_gather_bit_exact():
+    rng = np.random.default_rng(61)
+    for name in ("config0", "config1"):
+        w = wl.WORKLOADS[name]
+        lay = wl.make_layout(w)
+        _, k, v = wl.make_qkv(w, lay, with_q=False)
+        masks = np.zeros((3, lay.n_chunks), np.uint8)
+        masks[1] = 1
+        masks[2, rng.choice(lay.n_chunks, size=w.k, replace=False)] = 1
+        check_gather(w, lay, k, v, masks, lay.n_tokens)
+    w = wl.tiny_workload("bf16", 4, 2, 64, T=1, B=4, k=2, seed=62)
+    lay = wl.random_layout(rng, 9, 300, 1, 20)                       # more chunks than one scan pass
+    _, k, v = wl.make_qkv(w, lay, with_q=False)
+    masks = rng.integers(0, 2, size=(4, lay.n_chunks)).astype(np.uint8)
+    check_gather(w, lay, k, v, masks, lay.n_tokens + 11)
+
+
+# --------------------------------------------------------------------------------- decode
+def test_decode_config0_fp32_and_tiny_bf16():
+    rng = np.random.default_rng(71)
+    w = wl.WORKLOADS["config0"]
+    lay = wl.make_layout(w)
+    _, k, v = wl.make_qkv(w, lay, with_q=False)
+    qd = wl.make_decode_queries(w)
+    _, mask = oracle.select_topk(oracle.chunk_scores(qd, k, lay.chunk_bounds), w.k)
+    kmix, vmix, mix_len = check_gather(w, lay, k, v, mask, 400)
+    got, lse = gpu_decode(w, qd, kmix, vmix, mix_len, want_lse=True)
+    wk, wv, wlen, _ = oracle.gather_bilevel(k, v, mask, *lay_args(lay), l_cap=400)
+    want, wlse = oracle.decode_lse(qd, wk, wv, wlen)
+    assert_close(got, want, "f32", head_axis=2, what="config0 decode")
+    assert np.abs(lse - wlse).max() < 1e-4
+    for t_q, bsz, d in ((1, 2, 128), (5, 3, 64), (40, 1, 128)):
+        w = wl.tiny_workload("bf16", 14, 2, d, T=t_q, B=bsz, k=2, seed=72 + t_q)
+        lay = wl.random_layout(rng, 17, 9, 5, 120)
+        _, k, v = wl.make_qkv(w, lay, with_q=False)
+        qd = wl.make_decode_queries(w)
+        masks = rng.integers(0, 2, size=(bsz, lay.n_chunks)).astype(np.uint8)
+        kmix, vmix, mix_len = check_gather(w, lay, k, v, masks, lay.n_tokens)
+        got, lse = gpu_decode(w, qd, kmix, vmix, mix_len, want_lse=True)
+        wk, wv, wlen, _ = oracle.gather_bilevel(k, v, masks, *lay_args(lay), l_cap=lay.n_tokens)
+        want, wlse = oracle.decode_lse(qd, wk, wv, wlen)
+        assert_close(got, want, "bf16", head_axis=2, what=f"tiny decode T={t_q}")
+        assert np.abs(lse - wlse).max() < 2e-2
+
+
+def run_bilevel_chain(w, lay, k, v, qd, top_k):
+    """score -> gather -> decode entirely on the device, no host round trip in between."""
+    gl = make_layout(lay)
+    desc = desc_of(w)
+    dk, dv, dqd = (vxl.to_device(x, w.dtype) for x in (k, v, qd))
+    bsz, t = qd.shape[0], qd.shape[1]
+    kk = min(top_k, lay.n_chunks)
+    idx = torch.zeros((bsz, max(kk, 1)), dtype=torch.int32, device="cuda")
+    mask = torch.zeros((bsz, lay.n_chunks), dtype=torch.uint8, device="cuda")
+    l_cap = gl.mixed_kv_capacity(top_k)
+    kmix = torch.zeros((bsz, w.n_kv_heads, l_cap, w.head_dim), dtype=dk.dtype, device="cuda")
+    vmix = torch.zeros_like(kmix)
+    mix_len = torch.zeros((bsz,), dtype=torch.int32, device="cuda")
+    out = torch.zeros_like(dqd)
+    ws1 = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_SCORE_TOPK, gl, desc, bsz, t))
+    ws2 = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_GATHER, gl, desc, bsz))
+    ws3 = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_DECODE, None, desc, bsz, t, l_cap))
+    vxl.chunk_score_topk(gl, desc, dqd, dk, top_k, idx, mask, workspace=ws1)
+    vxl.gather_bilevel_kv(gl, desc, dk, dv, mask, kmix, vmix, mix_len, None, ws2)
+    vxl.bilevel_decode(desc, dqd, kmix, vmix, mix_len, out, None, ws3)
+    torch.cuda.synchronize()
+    return vxl.to_host(out), mask.cpu().numpy(), mix_len.cpu().numpy(), l_cap
+
+
+@pytest.mark.parametrize("name", ["config0", "config1"])
+def test_bilevel_chain(name):
+    w = wl.WORKLOADS[name]
+    lay = wl.make_layout(w)
+    _, k, v = wl.make_qkv(w, lay, with_q=False)
+    qd = wl.make_decode_queries(w)
+    got, mask, mix_len, l_cap = run_bilevel_chain(w, lay, k, v, qd, w.k)
+    s = oracle.chunk_scores(qd, k, lay.chunk_bounds)
+    _, wmask = oracle.select_topk(s, w.k)
+    assert np.array_equal(mask, wmask)
+    wk, wv, wlen, _ = oracle.gather_bilevel(k, v, wmask, *lay_args(lay), l_cap=l_cap)
+    assert np.array_equal(mix_len, wlen)
+    assert wlen[0] == {"config0": 352, "config1": 4096}[name]
+    want = oracle.decode_mixed(qd, wk, wv, wlen)
+    assert_close(got, want, w.dtype, head_axis=2, what=f"{name} chain decode")
+
+
+def test_all_dense_decode_equals_prefill_free_full_attention():
+    """Sparse set = whole chunk and k = C: the mixed KV is the full KV cache."""
+    w = wl.tiny_workload("bf16", 14, 2, 128, T=3, B=2, k=4, seed=81, value_scale=0.4)
+    lens = [70, 64, 130, 33]
+    kept, s = [], 10
+    for ln in lens:
+        kept.append(np.arange(s, s + ln))
+        s += ln
+    lay = wl.layout_from_lists(10, lens, kept)
+    _, k, v = wl.make_qkv(w, lay, with_q=False)
+    qd = wl.make_decode_queries(w)
+    got, mask, mix_len, l_cap = run_bilevel_chain(w, lay, k, v, qd, 4)
+    assert mask.all() and (mix_len == lay.n_tokens).all() and l_cap == lay.n_tokens
+    full_k = np.broadcast_to(k[None], (2,) + k.shape)
+    full_v = np.broadcast_to(v[None], (2,) + v.shape)
+    want = oracle.decode_mixed(qd, full_k, full_v, [lay.n_tokens] * 2)
+    assert_close(got, want, "bf16", head_axis=2, what="all-dense decode")
