@@ -54,23 +54,23 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
     DecodePlan p{};
     if (d->dtype != VXL_BF16) { p.n_split = 1; p.split_len = l_cap; p.total = 0; return p; }
     const int rows = (d->n_q_heads / d->n_kv_heads) * T;
+    const int row_tile = rows > 128 ? 256 : 128;
+    const int n_rtile = (rows + row_tile - 1) / row_tile;
     const int tiles = (l_cap + kKeyTile - 1) / kKeyTile;
-    // enough (batch, kv head, split) units to cover the 256 CUs a few times over, but at least
-    // two key tiles per split so the merge stays small
-    long units_wanted = 1024;
-    long per = (long)batch * d->n_kv_heads * ((rows + 127) / 128);
-    int want = (int)std::max<long>(1, (units_wanted + per - 1) / per);
-    int max_split = std::max(1, tiles / 2);
-    int n_split = std::min(want, max_split);
-    int tiles_per = (tiles + n_split - 1) / n_split;
-    n_split = (tiles + tiles_per - 1) / tiles_per;
-    p.n_split = n_split;
+    // Split the keys until about two workgroups per compute unit exist, but keep the partial
+    // results (fp32 rows per split) below roughly twice the KV bytes they summarise.
+    const long base_blocks = (long)batch * d->n_kv_heads * n_rtile;
+    long want = (512 + base_blocks - 1) / base_blocks;
+    const long cap = std::max<long>(1, 2L * l_cap / rows);
+    want = std::max<long>(1, std::min<long>(std::min<long>(want, cap), tiles));
+    const int tiles_per = (int)((tiles + want - 1) / want);
+    p.n_split = (tiles + tiles_per - 1) / tiles_per;
     p.split_len = tiles_per * kKeyTile;
     size_t off = 0;
     p.part_o = off;
-    off += align_up((size_t)batch * d->n_kv_heads * n_split * rows * d->head_dim * sizeof(float), 256);
+    off += align_up((size_t)batch * d->n_kv_heads * p.n_split * rows * d->head_dim * sizeof(float), 256);
     p.part_ml = off;
-    off += align_up((size_t)batch * d->n_kv_heads * n_split * rows * 2 * sizeof(float), 256);
+    off += align_up((size_t)batch * d->n_kv_heads * p.n_split * rows * sizeof(float), 256);
     p.total = off;
     return p;
 }

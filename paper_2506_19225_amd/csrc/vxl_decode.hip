@@ -1,16 +1,235 @@
-// GQA decode attention over the mixed KV set: split-KV partials on the matrix cores and the
+// GQA decode attention over the mixed KV set (bf16, matrix cores): split-KV partials and the
 // fixed-order log-sum-exp merge.
-#include <math.h>
-
+//
+// The G*T query rows that share one KV head (G = query heads per KV head) are stacked along the
+// query dimension: row rho = t*G + hg.  A workgroup owns one (query b, KV head g, row tile,
+// key split) and streams its slice of Kmix/Vmix exactly once through LDS (64-key tiles, double
+// buffered); every wave owns QB blocks of 32 query rows.  Each workgroup writes a normalised
+// partial output and the base-2 log-sum-exp of its scaled logits; the merge kernel combines the
+// splits of a row in split order, so the result does not depend on scheduling.
 #include "vxl_internal.h"
+#include "vxl_mfma.h"
 
 namespace vxl {
 
+namespace {
+
+template <int D, int QB>
+struct DecodeCfg {
+    static constexpr int RT = 128 * QB;            // query rows per workgroup
+    static constexpr int KROW = D + 8;             // LDS row strides (elements)
+    static constexpr int VROW = D + 16;
+    static constexpr int K_ELEMS = kKeyTile * KROW;
+    static constexpr int V_ELEMS = kKeyTile * VROW;
+    static constexpr int LDS_BYTES = 2 * (K_ELEMS + V_ELEMS) * 2;
+    static constexpr int LD = D / 32;              // 16-byte loads per thread per tile (K and V each)
+};
+
+template <int D, int QB>
+__global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void decode_split_kernel(
+    const uint16_t* __restrict__ Qd, const uint16_t* __restrict__ Kmix, const uint16_t* __restrict__ Vmix,
+    const int32_t* __restrict__ mix_len, float* __restrict__ part_o, float* __restrict__ part_lse, int T_q,
+    int n_q_heads, int n_kv_heads, int group, int l_cap, int n_rtile, int split_len, float scale) {
+    using C = DecodeCfg<D, QB>;
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+    uint16_t* Ks = lds;
+    uint16_t* Vs = lds + 2 * C::K_ELEMS;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hi = lane >> 5;
+    const int split = blockIdx.x, n_split = gridDim.x;
+    const int g = blockIdx.y % n_kv_heads, rt = blockIdx.y / n_kv_heads;
+    const int b = blockIdx.z;
+    const int n_rows = group * T_q;
+    const int len = min(max(mix_len[b], 0), l_cap);
+    const int k_lo = split * split_len;
+    const int k_hi = min(k_lo + split_len, len);
+    const int wrow0 = rt * C::RT + wave * 32 * QB;
+    const size_t part_base = (((size_t)b * n_kv_heads + g) * n_split + split) * (size_t)n_rows;
+
+    if (k_lo >= k_hi) {                            // empty split: only its weight (zero) is recorded
+        for (int r = rt * C::RT + tid; r < min(n_rows, (rt + 1) * C::RT); r += 256)
+            part_lse[part_base + r] = -INFINITY;
+        return;
+    }
+
+    bf16x8 qreg[QB][D / 16];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const int rho = min(wrow0 + qb * 32 + l32, n_rows - 1);
+        const int t = rho / group, hg = rho % group;
+        const uint4* src = (const uint4*)(Qd + (((size_t)b * T_q + t) * n_q_heads + g * group + hg) * D);
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) qreg[qb][ks] = __builtin_bit_cast(bf16x8, src[ks * 2 + hi]);
+    }
+    f32x16 o[QB][D / 32];
+    float m_run[QB], l_run[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        m_run[qb] = -INFINITY;
+        l_run[qb] = 0.f;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) o[qb][db] = zero16();
+    }
+    const float c2 = scale * kLog2e;
+    const bool wave_active = wrow0 < n_rows;       // waves without rows only help with the copies
+
+    const uint16_t* kbase = Kmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D;
+    const uint16_t* vbase = Vmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D;
+    uint4 kreg[C::LD], vreg[C::LD];
+    auto fetch = [&](int key0) {
+#pragma unroll
+        for (int i = 0; i < C::LD; ++i) {
+            const int idx = tid + 256 * i, r = idx / (D / 8), part = idx % (D / 8);
+            // rows past the end of the split are clamped to its last row: their scores are
+            // masked, and a finite V row keeps 0 * v finite
+            const size_t row = (size_t)min(key0 + r, k_hi - 1) * D;
+            kreg[i] = ((const uint4*)(kbase + row))[part];
+            vreg[i] = ((const uint4*)(vbase + row))[part];
+        }
+    };
+    auto stage = [&](int buf) {
+        uint16_t* kd = Ks + buf * C::K_ELEMS;
+        uint16_t* vd = Vs + buf * C::V_ELEMS;
+#pragma unroll
+        for (int i = 0; i < C::LD; ++i) {
+            const int idx = tid + 256 * i, r = idx / (D / 8), part = idx % (D / 8);
+            *(uint4*)(kd + r * C::KROW + part * 8) = kreg[i];
+            *(uint4*)(vd + r * C::VROW + part * 8) = vreg[i];
+        }
+    };
+
+    const int n_t = (k_hi - k_lo + kKeyTile - 1) / kKeyTile;
+    fetch(k_lo);
+    stage(0);
+    __syncthreads();
+    for (int ti = 0; ti < n_t; ++ti) {
+        const int buf = ti & 1;
+        const int key0 = k_lo + ti * kKeyTile;
+        if (ti + 1 < n_t) fetch(key0 + kKeyTile);
+        if (wave_active) {
+            f32x16 s[QB][2];
+            qk_tile<D, QB, C::KROW>(Ks + buf * C::K_ELEMS, qreg, l32, hi, s);
+            if (key0 + kKeyTile > k_hi) {
+                const int lim = k_hi - key0 - 1;
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            s[qb][kb][r] = acc_key(kb, r, hi) <= lim ? s[qb][kb][r] : -INFINITY;
+            }
+            bf16x8 pb[QB][2][2];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+                softmax_tile<D / 32>(s[qb], c2, m_run[qb], l_run[qb], o[qb], pb[qb]);
+            pv_tile<D, QB, C::VROW>(Vs + buf * C::V_ELEMS, pb, lane, o);
+        }
+        if (ti + 1 < n_t) stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    if (!wave_active) return;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const int rho = wrow0 + qb * 32 + l32;
+        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
+        if (rho >= n_rows) continue;
+        const float inv = 1.f / l_tot;
+        float* orow = part_o + (part_base + rho) * D;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                float4 v;
+                v.x = o[qb][db][rq * 4 + 0] * inv;
+                v.y = o[qb][db][rq * 4 + 1] * inv;
+                v.z = o[qb][db][rq * 4 + 2] * inv;
+                v.w = o[qb][db][rq * 4 + 3] * inv;
+                *(float4*)(orow + db * 32 + rq * 8 + hi * 4) = v;
+            }
+        if (hi == 0) part_lse[part_base + rho] = m_run[qb] * c2 + __builtin_amdgcn_logf(l_tot);
+    }
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16(float v) {
+    uint32_t b = __float_as_uint(v);
+    if ((b & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return (uint16_t)(b >> 16);
+}
+
+// One thread per (row, d): combine the splits in split order.
+template <int D>
+__global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restrict__ part_o,
+                                                           const float* __restrict__ part_lse,
+                                                           uint16_t* __restrict__ O, float* __restrict__ LSE,
+                                                           int T_q, int n_q_heads, int n_kv_heads, int group,
+                                                           int n_split) {
+    constexpr int RPB = 256 / D;                    // rows per block
+    const int n_rows = group * T_q;
+    const int rho = blockIdx.x * RPB + threadIdx.x / D, d = threadIdx.x % D;
+    const int g = blockIdx.y, b = blockIdx.z;
+    if (rho >= n_rows) return;
+    const size_t base = ((size_t)b * n_kv_heads + g) * n_split;
+    float mx = -INFINITY;
+    for (int s = 0; s < n_split; ++s) mx = fmaxf(mx, part_lse[(base + s) * n_rows + rho]);
+    float wsum = 0.f, acc = 0.f;
+    for (int s = 0; s < n_split; ++s) {
+        const float lse = part_lse[(base + s) * n_rows + rho];
+        if (lse == -INFINITY) continue;
+        const float w = __builtin_amdgcn_exp2f(lse - mx);
+        wsum += w;
+        acc = fmaf(w, part_o[((base + s) * n_rows + rho) * D + d], acc);
+    }
+    const int t = rho / group, hg = rho % group;
+    const size_t row = ((size_t)b * T_q + t) * n_q_heads + g * group + hg;
+    O[row * D + d] = f32_to_bf16(acc / wsum);
+    if (LSE && d == 0) LSE[row] = (mx + __builtin_amdgcn_logf(wsum)) * kLn2;
+}
+
+}  // namespace
+
+template <int D, int QB>
+static vxl_status run_decode(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
+                             const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len, void* O,
+                             float* LSE, void* ws, hipStream_t s) {
+    using C = DecodeCfg<D, QB>;
+    const DecodePlan p = decode_plan(d, batch, T, l_cap);
+    float* part_o = (float*)((char*)ws + p.part_o);
+    float* part_lse = (float*)((char*)ws + p.part_ml);
+    const int group = d->n_q_heads / d->n_kv_heads;
+    const int n_rows = group * T;
+    const int n_rtile = (n_rows + C::RT - 1) / C::RT;
+    static bool attr_done = false;
+    if (!attr_done) {
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_split_kernel<D, QB>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((decode_split_kernel<D, QB>), dim3(p.n_split, n_rtile * d->n_kv_heads, batch), dim3(256),
+                       C::LDS_BYTES, s, (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix,
+                       mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap, n_rtile,
+                       p.split_len, scale);
+    VXL_HIP_TRY(hipGetLastError());
+    constexpr int rpb = 256 / D;
+    hipLaunchKernelGGL((decode_merge_kernel<D>), dim3((n_rows + rpb - 1) / rpb, d->n_kv_heads, batch), dim3(256),
+                       0, s, part_o, part_lse, (uint16_t*)O, LSE, T, d->n_q_heads, d->n_kv_heads, group,
+                       p.n_split);
+    VXL_HIP_TRY(hipGetLastError());
+    return VXL_OK;
+}
+
 vxl_status launch_decode_bf16(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
-                              const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len,
-                              void* O, float* LSE, void* ws, hipStream_t s) {
-    (void)ws;
-    return launch_decode_simple(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, s);
+                              const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len, void* O,
+                              float* LSE, void* ws, hipStream_t s) {
+    const int n_rows = (d->n_q_heads / d->n_kv_heads) * T;
+    const bool big = n_rows > 128;
+    if (d->head_dim == 128)
+        return big ? run_decode<128, 2>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s)
+                   : run_decode<128, 1>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s);
+    return big ? run_decode<64, 2>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s)
+               : run_decode<64, 1>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s);
 }
 
 }  // namespace vxl

@@ -1,0 +1,125 @@
+// Device building blocks of the matrix-core attention kernels (gfx950, wave64).
+//
+// Both kernels compute the scores transposed, S^T = K.Q^T with v_mfma_f32_32x32x16_bf16:
+//   A operand (K tile, from LDS): lane (l32, hi) holds K[key = l32][d = 16*ks + 8*hi .. +7]
+//   B operand (Q, in registers):  lane (l32, hi) holds Q[query = l32][d = 16*ks + 8*hi .. +7]
+//   accumulator: lane (l32, hi), register r holds S^T[key = 8*(r/4) + 4*hi + r%4][query = l32]
+// so a lane owns one query column (its partner lane ^ 32 owns the other half of the keys) and
+// the softmax statistics need one cross-lane exchange.  The probabilities then feed the second
+// product O^T = V^T.P^T directly as its B operand: for the 16-key step j of a 32-key block the
+// registers r = 8j .. 8j+7 of a lane are the keys 16j + 4*hi + {0,1,2,3, 8,9,10,11}.  The A
+// operand V^T[d][those keys] is produced from a row-major V tile in LDS by the transposing LDS
+// read (ds_read_b64_tr_b16): inside a group of 16 lanes, lane i receives element (i % 4) of the
+// 8-byte pieces addressed by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+namespace vxl {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ f32x16 zero16() {
+    f32x16 z;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+    return z;
+}
+
+// Tile-relative key index of accumulator register r of key block kb for lane half hi.
+__device__ __forceinline__ constexpr int acc_key(int kb, int r, int hi) {
+    return kb * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
+}
+
+// S^T[qb][kb] = K tile (64 keys, row-major in LDS, row stride KROW elements) times Q^T.
+template <int D, int QB, int KROW>
+__device__ __forceinline__ void qk_tile(const uint16_t* kt, const bf16x8 (&qreg)[QB][D / 16], int l32,
+                                        int hi, f32x16 (&s)[QB][2]) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) s[qb][kb] = zero16();
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            const bf16x8 a = *(const bf16x8*)(kt + (kb * 32 + l32) * KROW + ks * 16 + hi * 8);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+                s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][ks], s[qb][kb], 0, 0, 0);
+        }
+}
+
+// Online-softmax update of one query block: running max m (raw logits), running sum l (this
+// lane's half of the keys), rescale of the output accumulators, probabilities packed to bf16 in
+// B-operand order.  c2 = softmax_scale * log2(e).
+template <int DB>
+__device__ __forceinline__ void softmax_tile(f32x16 (&s)[2], float c2, float& m_run, float& l_run,
+                                             f32x16 (&o)[DB], bf16x8 (&pb)[2][2]) {
+    float mx = s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c2);
+    const float mc = m_use * c2;
+    float sum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][r], c2, -mc));
+            sum += p;
+            pb[kb][r >> 3][r & 7] = (__bf16)p;
+        }
+    l_run = l_run * alpha + sum;
+    m_run = m_new;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+}
+
+// A operand of the second product for the 16-key step (kb, j) and the 32-wide d block db, read
+// transposed from a row-major V tile (64 keys x D, row stride VROW elements) in LDS.
+template <int VROW>
+__device__ __forceinline__ bf16x8 load_vt_operand(const uint16_t* vt, int kb, int j, int db, int lane) {
+    const int hi = lane >> 5, dhalf = (lane >> 4) & 1, s = lane & 15;
+    const uint16_t* p = vt + (kb * 32 + j * 16 + 4 * hi + (s >> 2)) * VROW + db * 32 + dhalf * 16 + 4 * (s & 3);
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * VROW));
+    const s16x8 both = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+}
+
+// O^T[db][qb] += V^T . P^T over the 64 keys of the tile.
+template <int D, int QB, int VROW>
+__device__ __forceinline__ void pv_tile(const uint16_t* vt, const bf16x8 (&pb)[QB][2][2], int lane,
+                                        f32x16 (&o)[QB][D / 32]) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db) {
+                const bf16x8 a = load_vt_operand<VROW>(vt, kb, j, db, lane);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+                    o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb][kb][j], o[qb][db], 0, 0, 0);
+            }
+}
+
+}  // namespace vxl

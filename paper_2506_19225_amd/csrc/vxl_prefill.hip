@@ -301,7 +301,14 @@ vxl_status enable_big_lds(F kernel, int bytes) {
 }  // namespace
 
 static int g_prefill_qb = 1;
+static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 extern "C" void vxl_debug_prefill_rows_per_wave(int blocks) { g_prefill_qb = blocks == 2 ? 2 : 1; }
+// Measurement hook: when both events are set, every vxl_chunk_prefill records them on its stream
+// immediately before and after the main attention kernel (the pre-pass is outside the bracket).
+extern "C" void vxl_debug_prefill_events(void* start, void* stop) {
+    g_ev_start = (hipEvent_t)start;
+    g_ev_stop = (hipEvent_t)stop;
+}
 
 template <int D, int QB>
 static vxl_status run_prefill(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Q,
@@ -330,12 +337,15 @@ static vxl_status run_prefill(const vxl_layout* L, const vxl_attn_desc* d, float
         attr_done = true;
     }
     const int v = QB - 1;
+    const bool timed = g_ev_start && g_ev_stop;
+    if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_start, s));
     const unsigned n_blocks = (unsigned)L->n_work[v] * (unsigned)d->n_q_heads;
     hipLaunchKernelGGL((prefill_mfma_kernel<D, QB>), dim3(n_blocks), dim3(256), C::LDS_BYTES, s,
                        (const uint16_t*)Q, (const uint16_t*)K, kctx, vt, (uint16_t*)O, LSE, L->d_segs,
                        L->d_work[v], L->n_tokens, d->n_q_heads, d->n_q_heads / d->n_kv_heads,
                        L->n_ctx_tiles, n_tiles_all, scale);
     VXL_HIP_TRY(hipGetLastError());
+    if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_stop, s));
     return VXL_OK;
 }
 

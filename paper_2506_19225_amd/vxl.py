@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
     L.vxl_bilevel_decode.argtypes = [dp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     L.vxl_debug_force_simple.argtypes = [C.c_int]
     L.vxl_debug_prefill_rows_per_wave.argtypes = [C.c_int]
+    L.vxl_debug_prefill_events.argtypes = [vp, vp]
     _lib = L
     return L
 
@@ -202,6 +203,14 @@ def debug_force_simple(on: bool) -> None:
 
 def debug_prefill_rows_per_wave(blocks: int) -> None:
     lib().vxl_debug_prefill_rows_per_wave(int(blocks))
+
+
+def debug_prefill_events(start: Optional[torch.cuda.Event], stop: Optional[torch.cuda.Event]) -> None:
+    """Measurement hook: record the two events (created with enable_timing=True and already
+    recorded once, so that their handles exist) around the main pre-filling kernel of every
+    following vxl_chunk_prefill; (None, None) switches it off."""
+    lib().vxl_debug_prefill_events(start.cuda_event if start is not None else None,
+                                   stop.cuda_event if stop is not None else None)
 
 
 # ---------------------------------------------------------------------------------------------
