@@ -44,8 +44,8 @@ PrefillWorkspace prefill_workspace(const vxl_layout* L, const vxl_attn_desc* d) 
     size_t off = 0;
     w.kctx = off;
     off += align_up((size_t)d->n_kv_heads * L->n_ctx_tiles * kKeyTile * d->head_dim * 2, 256);
-    w.vt = off;
-    off += align_up((size_t)d->n_kv_heads * (L->n_ctx_tiles + L->n_own_tiles) * kKeyTile * d->head_dim * 2, 256);
+    w.vctx = off;
+    off += align_up((size_t)d->n_kv_heads * L->n_ctx_tiles * kKeyTile * d->head_dim * 2, 256);
     w.total = off;
     return w;
 }

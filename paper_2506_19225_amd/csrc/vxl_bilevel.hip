@@ -65,16 +65,35 @@ __global__ __launch_bounds__(256) void score_topk_kernel(
     float* qbar = (float*)smem;                               // [Hkv][D]
     float* s_val = qbar + n_kv_heads * D;                     // [n_sort]
     int* s_idx = (int*)(s_val + n_sort);                      // [n_sort]
+    float* hsum = (float*)(s_idx + n_sort);                   // [Hq][D] per-head sums over tokens
     const int b = blockIdx.x, tid = threadIdx.x;
     const int group = n_q_heads / n_kv_heads;
     const T* qb = Qd + (size_t)b * T_q * n_q_heads * D;
-    // mean query of every kv head: sum over tokens and over the heads of the group
+    // mean query of every kv head.  Step 1: every thread owns 16-byte columns of the [T, Hq*D]
+    // query matrix and sums them over the tokens (independent 16-byte loads, token order).
+    constexpr int EPC = 16 / (int)sizeof(T);                  // elements per 16-byte piece
+    const int row_pieces = n_q_heads * D / EPC;
+    for (int p = tid; p < row_pieces; p += 256) {
+        float acc[EPC];
+#pragma unroll
+        for (int i = 0; i < EPC; ++i) acc[i] = 0.f;
+        const uint4* src = (const uint4*)qb + p;
+#pragma unroll 4
+        for (int t = 0; t < T_q; ++t) {
+            const uint4 v = src[(size_t)t * row_pieces];
+            const T* e = (const T*)&v;
+#pragma unroll
+            for (int i = 0; i < EPC; ++i) acc[i] += ld(e + i);
+        }
+#pragma unroll
+        for (int i = 0; i < EPC; ++i) hsum[p * EPC + i] = acc[i];
+    }
+    __syncthreads();
+    // Step 2: add the heads of a group in head order.
     for (int e = tid; e < n_kv_heads * D; e += 256) {
         const int g = e / D, dd = e % D;
         float a = 0.f;
-        for (int t = 0; t < T_q; ++t)
-            for (int hg = 0; hg < group; ++hg)
-                a += ld(qb + ((size_t)t * n_q_heads + g * group + hg) * D + dd);
+        for (int hg = 0; hg < group; ++hg) a += hsum[(g * group + hg) * D + dd];
         qbar[e] = a / (float)(T_q * group);
     }
     __syncthreads();
@@ -230,8 +249,9 @@ vxl_status launch_score_topk(const vxl_layout* L, const vxl_attn_desc* d, float 
                              uint8_t* dense_mask, float* scores, hipStream_t s) {
     int n_sort = 2;
     while (n_sort < L->n_chunks) n_sort <<= 1;
-    const size_t smem = (size_t)d->n_kv_heads * d->head_dim * 4 + (size_t)n_sort * 8;
-    if (smem > 60 * 1024) return VXL_ERR_UNSUPPORTED;
+    const size_t smem = (size_t)d->n_kv_heads * d->head_dim * 4 + (size_t)n_sort * 8 +
+                        (size_t)d->n_q_heads * d->head_dim * 4;
+    if (smem > 64 * 1024) return VXL_ERR_UNSUPPORTED;
     const dim3 grid(batch), block(256);
 #define VXL_LAUNCH(T_, D)                                                                          \
     hipLaunchKernelGGL((score_topk_kernel<T_, D>), grid, block, smem, s, (const T_*)Qd, kbar, T,   \

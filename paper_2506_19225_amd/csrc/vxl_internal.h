@@ -71,8 +71,8 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- pre-filling ----
 struct PrefillWorkspace {      // byte offsets into the caller's workspace (bf16 path)
-    size_t kctx;               // [Hkv][n_ctx_tiles*64][D]
-    size_t vt;                 // [Hkv][n_ctx_tiles + n_own_tiles][D][64] (key-permuted tiles)
+    size_t kctx;               // [Hkv][n_ctx_tiles*64][D] compacted history keys
+    size_t vctx;               // [Hkv][n_ctx_tiles*64][D] compacted history values
     size_t total;
 };
 PrefillWorkspace prefill_workspace(const vxl_layout* L, const vxl_attn_desc* d);

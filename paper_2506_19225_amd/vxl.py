@@ -72,6 +72,7 @@ def lib() -> C.CDLL:
     L.vxl_debug_force_simple.argtypes = [C.c_int]
     L.vxl_debug_prefill_rows_per_wave.argtypes = [C.c_int]
     L.vxl_debug_prefill_events.argtypes = [vp, vp]
+    L.vxl_debug_flags.argtypes = [C.c_int]
     _lib = L
     return L
 
