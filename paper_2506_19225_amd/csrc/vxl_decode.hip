@@ -17,8 +17,8 @@ namespace {
 template <int D, int QB>
 struct DecodeCfg {
     static constexpr int RT = 128 * QB;            // query rows per workgroup
-    static constexpr int KROW = D + 8;             // LDS row strides (elements)
-    static constexpr int VROW = D + 16;
+    static constexpr int KROW = LdsRows<D>::K;   // LDS row strides (elements)
+    static constexpr int VROW = LdsRows<D>::V;
     static constexpr int K_ELEMS = kKeyTile * KROW;
     static constexpr int V_ELEMS = kKeyTile * VROW;
     static constexpr int LDS_BYTES = 2 * (K_ELEMS + V_ELEMS) * 2;
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void decode_split_kernel(
 #pragma unroll
         for (int i = 0; i < C::LD; ++i) {
             const int idx = tid + 256 * i, r = idx / (D / 8), part = idx % (D / 8);
-            *(uint4*)(kd + r * C::KROW + part * 8) = kreg[i];
+            *(uint4*)(kd + k_tile_off<D>(r, part)) = kreg[i];
             *(uint4*)(vd + r * C::VROW + part * 8) = vreg[i];
         }
     };

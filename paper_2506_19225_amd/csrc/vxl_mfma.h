@@ -25,6 +25,29 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
+// LDS row strides (in elements) of the row-major K and V tiles.  Measured on gfx950, the LDS
+// behaves as 32 banks of 8 bytes, each half-wave (lanes 0-31, lanes 32-63) served separately:
+// an access pattern runs at full rate when the 8-byte pieces touched by the 32 lanes of a
+// half-wave fall into distinct banks.  The K operand read (lane = row, 16 bytes at a common
+// column) needs an odd stride in 8-byte units: D*2 + 8 bytes.  The transposing V read (4 rows x
+// 64 contiguous bytes per half-wave) needs the stride to be 8 or 24 (mod 32) units: 320 bytes
+// for D = 128, 192 bytes for D = 64.
+template <int D> struct LdsRows {
+    static constexpr int K = D;                       // unpadded; pieces are XOR-swizzled instead
+    static constexpr int V = D == 128 ? 160 : 96;
+};
+
+// Element offset of 16-byte piece `piece` of row `row` in the K tile.  Rows are unpadded (so
+// every piece stays 16-byte aligned) and the piece index is XOR-ed with the row's position
+// inside a group of 16 256-byte lines: the 32 rows a half-wave reads at one logical piece then
+// cover every bank exactly twice, which is the full rate of a 16-byte access.
+template <int D>
+__device__ __forceinline__ int k_tile_off(int row, int piece) {
+    constexpr int PPR = D / 8;                        // pieces per row
+    constexpr int RPL = 16 / PPR;                     // rows per 256-byte line
+    return row * D + ((piece ^ ((row / RPL) & (PPR - 1))) << 3);
+}
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -40,7 +63,7 @@ __device__ __forceinline__ constexpr int acc_key(int kb, int r, int hi) {
     return kb * 32 + 8 * (r >> 2) + 4 * hi + (r & 3);
 }
 
-// S^T[qb][kb] = K tile (64 keys, row-major in LDS, row stride KROW elements) times Q^T.
+// S^T[qb][kb] = K tile (64 keys, row-major in LDS, pieces placed by k_tile_off) times Q^T.
 template <int D, int QB, int KROW>
 __device__ __forceinline__ void qk_tile(const uint16_t* kt, const bf16x8 (&qreg)[QB][D / 16], int l32,
                                         int hi, f32x16 (&s)[QB][2]) {
@@ -52,7 +75,7 @@ __device__ __forceinline__ void qk_tile(const uint16_t* kt, const bf16x8 (&qreg)
     for (int ks = 0; ks < D / 16; ++ks)
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
-            const bf16x8 a = *(const bf16x8*)(kt + (kb * 32 + l32) * KROW + ks * 16 + hi * 8);
+            const bf16x8 a = *(const bf16x8*)(kt + k_tile_off<D>(kb * 32 + l32, ks * 2 + hi));
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
                 s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][ks], s[qb][kb], 0, 0, 0);
@@ -105,7 +128,7 @@ __device__ __forceinline__ bf16x8 load_vt_operand(const uint16_t* vt, int kb, in
     return __builtin_bit_cast(bf16x8, both);
 }
 
-// O^T[db][qb] += V^T . P^T over the 64 keys of the tile.
+// O^T[qb][db] += V^T . P^T over the 64 keys of the tile.
 template <int D, int QB, int VROW>
 __device__ __forceinline__ void pv_tile(const uint16_t* vt, const bf16x8 (&pb)[QB][2][2], int lane,
                                         f32x16 (&o)[QB][D / 32]) {

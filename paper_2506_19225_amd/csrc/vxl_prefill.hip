@@ -43,8 +43,8 @@ __global__ __launch_bounds__(256) void compact_kv_kernel(const uint4* __restrict
 template <int D, int QB>
 struct PrefillCfg {
     static constexpr int BM = 128 * QB;          // query rows per workgroup (4 waves x QB x 32)
-    static constexpr int KROW = D + 8;           // LDS row strides (elements)
-    static constexpr int VROW = D + 16;
+    static constexpr int KROW = LdsRows<D>::K;   // LDS row strides (elements)
+    static constexpr int VROW = LdsRows<D>::V;
     static constexpr int K_ELEMS = kKeyTile * KROW;
     static constexpr int V_ELEMS = kKeyTile * VROW;
     static constexpr int LDS_BYTES = 2 * (K_ELEMS + V_ELEMS) * 2;
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
     do {                                                                                            \
         _Pragma("unroll") for (int i = 0; i < C::LD; ++i) {                                         \
             const int r_ = ld_r + i * ROWS_PER_PASS;                                                \
-            *(uint4*)(Ks + (buf_) * C::K_ELEMS + r_ * C::KROW + ld_part * 8) = kreg[i];             \
+            *(uint4*)(Ks + (buf_) * C::K_ELEMS + k_tile_off<D>(r_, ld_part)) = kreg[i];              \
             *(uint4*)(Vs + (buf_) * C::V_ELEMS + r_ * C::VROW + ld_part * 8) = vreg[i];             \
         }                                                                                           \
     } while (0)
