@@ -35,7 +35,8 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void decode_split_kernel(
     uint16_t* Ks = lds;
     uint16_t* Vs = lds + 2 * C::K_ELEMS;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hi = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: scalar control flow
     const int split = blockIdx.x, n_split = gridDim.x;
     const int g = blockIdx.y % n_kv_heads, rt = blockIdx.y / n_kv_heads;
     const int b = blockIdx.z;

@@ -82,37 +82,50 @@ __device__ __forceinline__ void qk_tile(const uint16_t* kt, const bf16x8 (&qreg)
         }
 }
 
-// Online-softmax update of one query block: running max m (raw logits), running sum l (this
-// lane's half of the keys), rescale of the output accumulators, probabilities packed to bf16 in
-// B-operand order.  c2 = softmax_scale * log2(e).
+// Online-softmax update of one query block.  m_run is the reference logit of the running
+// exponentials (raw units), l_run this lane's half of the running sum, c2 = softmax_scale*log2(e).
+// The reference is raised -- and l_run and the output accumulators rescaled -- only when some
+// lane of the wave sees a logit more than 2^8 above its reference (in the exp2 domain), a
+// wave-uniform decision: until then the probabilities stay below 2^8, which fp32 and bf16
+// represent with unchanged relative precision, and the final division by l_run is the same.
+// The sum is taken over the bf16-rounded probabilities (the weights the second product uses).
 template <int DB>
 __device__ __forceinline__ void softmax_tile(f32x16 (&s)[2], float c2, float& m_run, float& l_run,
                                              f32x16 (&o)[DB], bf16x8 (&pb)[2][2]) {
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
     float mx = s[0][0];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c2);
-    const float mc = m_use * c2;
-    float sum = 0.f;
+    const bool grow = (mx - m_run) * c2 > 8.f;              // also true for the first finite logit
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+        l_run *= alpha;
+        m_run = m_new;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+    }
+    const float mc = (m_run == -INFINITY ? 0.f : m_run) * c2;
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][r], c2, -mc));
-            sum += p;
-            pb[kb][r >> 3][r & 7] = (__bf16)p;
+        for (int r = 0; r < 16; r += 2) {
+            bf16x2 pr;
+            pr[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[kb][r], c2, -mc));
+            pr[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[kb][r + 1], c2, -mc));
+            if (kb == 0) sum0 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum0, false);
+            else sum1 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum1, false);
+            pb[kb][r >> 3][r & 7] = pr[0];
+            pb[kb][r >> 3][(r & 7) + 1] = pr[1];
         }
-    l_run = l_run * alpha + sum;
-    m_run = m_new;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+    l_run += sum0 + sum1;
 }
 
 // A operand of the second product for the 16-key step (kb, j) and the 32-wide d block db, read

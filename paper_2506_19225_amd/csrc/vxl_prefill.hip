@@ -51,18 +51,23 @@ struct PrefillCfg {
     static constexpr int LD = D / 32;            // 16-byte loads per thread per K (and per V) tile
 };
 
-template <int D, int QB>
+template <int D, int QB, bool PROF = false>
 __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     const uint16_t* __restrict__ Kctx, const uint16_t* __restrict__ Vctx, uint16_t* __restrict__ O,
     float* __restrict__ LSE, const Segment* __restrict__ segs, const WorkItem* __restrict__ work,
-    int n_tokens, int n_q_heads, int group, int ctx_rows_pad, float scale, int n_items, int xpg, int dbg) {
+    int n_tokens, int n_q_heads, int group, int ctx_rows_pad, float scale, int n_items, int xpg, int dbg,
+    unsigned long long* __restrict__ prof = nullptr) {
     using C = PrefillCfg<D, QB>;
+    // PROF instances (measurement only) accumulate per-wave cycle counts of the loop phases.
+    unsigned long long pt[6] = {0, 0, 0, 0, 0, 0};
+    auto tick = [&]() -> unsigned long long { return PROF ? (unsigned long long)clock64() : 0ull; };
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
     uint16_t* Ks = lds;                          // [2][64][KROW]
     uint16_t* Vs = lds + 2 * C::K_ELEMS;         // [2][64][VROW]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hi = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: scalar control flow
     // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  With xpg XCDs per KV
     // head, all workgroups that read the K/V of one KV head land on the same xpg XCDs.
     int item, h;
@@ -76,6 +81,8 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
         item = blockIdx.x / n_q_heads;
         h = blockIdx.x % n_q_heads;
     }
+    item = __builtin_amdgcn_readfirstlane(item);                   // uniform: scalar loads and branches
+    h = __builtin_amdgcn_readfirstlane(h);
     const int g = h / group;
     const WorkItem wi = work[item];
     const Segment sg = segs[wi.seg];
@@ -115,28 +122,46 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
     const uint16_t* vown = V + ((size_t)g * n_tokens + sg.q_start) * D;
     const int ld_r = tid / (D / 8), ld_part = tid % (D / 8);        // this thread's row / 16-byte piece
     constexpr int ROWS_PER_PASS = 256 / (D / 8);
-    uint4 kreg[C::LD], vreg[C::LD];
+    // Prefetch registers as named scalars (LD = 4 pairs for D = 128, 2 for D = 64): they must stay
+    // in VGPRs across the scheduling fence below.
+    uint4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
+    kr2 = kr3 = vr2 = vr3 = zero4();
 
+#define VXL_FETCH1(i_, kr_, vr_)                                                                    \
+    do {                                                                                            \
+        const uint32_t off_ = (uint32_t)min(ld_r + (i_) * ROWS_PER_PASS, rlim_) * (D * 2) + ld_part * 16; \
+        kr_ = *(const uint4*)(kb_ + off_);                                                          \
+        vr_ = *(const uint4*)(vb_ + off_);                                                          \
+    } while (0)
 #define VXL_FETCH(ti_)                                                                              \
     do {                                                                                            \
         const int t_ = (dbg & 1) ? 0 : (ti_);                                                       \
         const bool ctx_ = t_ < n_ctx_t;                                                             \
         const int row0_ = ctx_ ? t_ * kKeyTile : (t_ - n_ctx_t) * kKeyTile;                         \
-        const int rmax_ = ctx_ ? 0x7fffffff : sg.q_len - 1;                                         \
-        const uint16_t* kb_ = ctx_ ? kctx_g : kown;                                                 \
-        const uint16_t* vb_ = ctx_ ? vctx_g : vown;                                                 \
-        _Pragma("unroll") for (int i = 0; i < C::LD; ++i) {                                         \
-            const size_t off_ = (size_t)min(row0_ + ld_r + i * ROWS_PER_PASS, rmax_) * D + ld_part * 8; \
-            kreg[i] = *(const uint4*)(kb_ + off_);                                                  \
-            vreg[i] = *(const uint4*)(vb_ + off_);                                                  \
+        /* rows of the tile beyond the segment end are clamped to its last row */                   \
+        const int rlim_ = ctx_ ? kKeyTile - 1 : min(kKeyTile - 1, sg.q_len - 1 - row0_);            \
+        const char* kb_ = (const char*)(ctx_ ? kctx_g : kown) + (size_t)row0_ * (D * 2);            \
+        const char* vb_ = (const char*)(ctx_ ? vctx_g : vown) + (size_t)row0_ * (D * 2);            \
+        VXL_FETCH1(0, kr0, vr0);                                                                    \
+        VXL_FETCH1(1, kr1, vr1);                                                                    \
+        if constexpr (C::LD > 2) {                                                                  \
+            VXL_FETCH1(2, kr2, vr2);                                                                \
+            VXL_FETCH1(3, kr3, vr3);                                                                \
         }                                                                                           \
+    } while (0)
+#define VXL_STAGE1(buf_, i_, kr_, vr_)                                                              \
+    do {                                                                                            \
+        const int r_ = ld_r + (i_) * ROWS_PER_PASS;                                                 \
+        *(uint4*)(Ks + (buf_) * C::K_ELEMS + k_tile_off<D>(r_, ld_part)) = kr_;                     \
+        *(uint4*)(Vs + (buf_) * C::V_ELEMS + r_ * C::VROW + ld_part * 8) = vr_;                     \
     } while (0)
 #define VXL_STAGE(buf_)                                                                             \
     do {                                                                                            \
-        _Pragma("unroll") for (int i = 0; i < C::LD; ++i) {                                         \
-            const int r_ = ld_r + i * ROWS_PER_PASS;                                                \
-            *(uint4*)(Ks + (buf_) * C::K_ELEMS + k_tile_off<D>(r_, ld_part)) = kreg[i];              \
-            *(uint4*)(Vs + (buf_) * C::V_ELEMS + r_ * C::VROW + ld_part * 8) = vreg[i];             \
+        VXL_STAGE1(buf_, 0, kr0, vr0);                                                              \
+        VXL_STAGE1(buf_, 1, kr1, vr1);                                                              \
+        if constexpr (C::LD > 2) {                                                                  \
+            VXL_STAGE1(buf_, 2, kr2, vr2);                                                          \
+            VXL_STAGE1(buf_, 3, kr3, vr3);                                                          \
         }                                                                                           \
     } while (0)
 
@@ -146,7 +171,10 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
 
     for (int ti = 0; ti < n_t; ++ti) {
         const int buf = ti & 1;
+        const unsigned long long t0 = tick();
         VXL_FETCH(min(ti + 1, n_t - 1));          // unconditional: the loads stay in flight below
+        __builtin_amdgcn_sched_barrier(0);        // keep them ahead of the arithmetic
+        unsigned long long t1 = t0, t2 = t0, t3 = t0;
 
         const bool is_ctx = ti < n_ctx_t;
         const int key0 = is_ctx ? ti * kKeyTile : (ti - n_ctx_t) * kKeyTile;   // tile start in its space
@@ -155,6 +183,7 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
         if (!skip) {
             f32x16 s[QB][2];
             qk_tile<D, QB, C::KROW>(Ks + buf * C::K_ELEMS, qreg, l32, hi, s);
+            if (PROF) { __builtin_amdgcn_sched_barrier(0); asm volatile("s_nop 0" :: "v"(s[0][0][15]), "v"(s[0][1][15])); t1 = tick(); }
             // ---- mask (ragged last history tile, causal own tiles) ----
             const bool need_mask = is_ctx ? (key0 + kKeyTile > sg.ctx_len) : (key0 + kKeyTile - 1 > wrow0);
             if (need_mask) {
@@ -173,13 +202,25 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
                 softmax_tile<D / 32>(s[qb], c2, m_run[qb], l_run[qb], o[qb], pb[qb]);
+            if (PROF) { __builtin_amdgcn_sched_barrier(0); asm volatile("s_nop 0" :: "v"(pb[0][1][1])); t2 = tick(); }
             pv_tile<D, QB, C::VROW>(Vs + buf * C::V_ELEMS, pb, lane, o);
+            if (PROF) { __builtin_amdgcn_sched_barrier(0); asm volatile("s_nop 0" :: "v"(o[0][0][15]), "v"(o[0][D / 32 - 1][15])); t3 = tick(); }
         }
         VXL_STAGE(buf ^ 1);
+        const unsigned long long t4 = tick();
         __syncthreads();
+        if (PROF) {
+            const unsigned long long t5 = tick();
+            pt[0] += t1 - t0; pt[1] += t2 - t1; pt[2] += t3 - t2; pt[3] += t4 - t3; pt[4] += t5 - t4; pt[5] += 1;
+        }
+    }
+    if (PROF && prof && lane == 0) {
+        for (int i = 0; i < 6; ++i) prof[((size_t)blockIdx.x * 4 + wave) * 6 + i] = pt[i];
     }
 #undef VXL_FETCH
+#undef VXL_FETCH1
 #undef VXL_STAGE
+#undef VXL_STAGE1
 
     // ---- normalise and store: lane owns query column l32; 4 consecutive d per register quad ----
 #pragma unroll
@@ -213,7 +254,11 @@ vxl_status enable_big_lds(F kernel, int bytes) {
 
 static int g_prefill_qb = 1;
 static int g_prefill_dbg = 0;
+static unsigned long long* g_prof_buf = nullptr;
 extern "C" void vxl_debug_flags(int flags) { g_prefill_dbg = flags; }
+// Measurement only: a device buffer of 6 counters per wave (4 per workgroup) makes the next
+// vxl_chunk_prefill calls run the instrumented instance of the kernel (D = 128, one row block).
+extern "C" void vxl_debug_prefill_profile(void* buf) { g_prof_buf = (unsigned long long*)buf; }
 static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 extern "C" void vxl_debug_prefill_rows_per_wave(int blocks) { g_prefill_qb = blocks == 2 ? 2 : 1; }
 // Measurement hook: when both events are set, every vxl_chunk_prefill records them on its stream
@@ -240,7 +285,7 @@ static vxl_status run_prefill(const vxl_layout* L, const vxl_attn_desc* d, float
     }
     static bool attr_done = false;
     if (!attr_done) {
-        vxl_status st = enable_big_lds(prefill_mfma_kernel<D, QB>, C::LDS_BYTES);
+        vxl_status st = enable_big_lds(prefill_mfma_kernel<D, QB, false>, C::LDS_BYTES);
         if (st != VXL_OK) return st;
         attr_done = true;
     }
@@ -251,10 +296,23 @@ static vxl_status run_prefill(const vxl_layout* L, const vxl_attn_desc* d, float
     const int xpg = (!(g_prefill_dbg & 2) && 8 % d->n_kv_heads == 0) ? 8 / d->n_kv_heads : 0;
     const unsigned n_blocks = xpg ? 8u * (unsigned)((L->n_work[v] * group + xpg - 1) / xpg)
                                   : (unsigned)L->n_work[v] * (unsigned)d->n_q_heads;
-    hipLaunchKernelGGL((prefill_mfma_kernel<D, QB>), dim3(n_blocks), dim3(256), C::LDS_BYTES, s,
-                       (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V, kctx, vctx, (uint16_t*)O, LSE,
-                       L->d_segs, L->d_work[v], L->n_tokens, d->n_q_heads, group, n_rows_pad, scale,
-                       L->n_work[v], xpg, g_prefill_dbg);
+    if (g_prof_buf) {
+        static bool attr2 = false;
+        if (!attr2) {
+            vxl_status st = enable_big_lds(prefill_mfma_kernel<D, QB, true>, C::LDS_BYTES);
+            if (st != VXL_OK) return st;
+            attr2 = true;
+        }
+        hipLaunchKernelGGL((prefill_mfma_kernel<D, QB, true>), dim3(n_blocks), dim3(256), C::LDS_BYTES, s,
+                           (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V, kctx, vctx, (uint16_t*)O,
+                           LSE, L->d_segs, L->d_work[v], L->n_tokens, d->n_q_heads, group, n_rows_pad, scale,
+                           L->n_work[v], xpg, g_prefill_dbg, g_prof_buf);
+    } else {
+        hipLaunchKernelGGL((prefill_mfma_kernel<D, QB, false>), dim3(n_blocks), dim3(256), C::LDS_BYTES, s,
+                           (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V, kctx, vctx, (uint16_t*)O,
+                           LSE, L->d_segs, L->d_work[v], L->n_tokens, d->n_q_heads, group, n_rows_pad, scale,
+                           L->n_work[v], xpg, g_prefill_dbg, (unsigned long long*)nullptr);
+    }
     VXL_HIP_TRY(hipGetLastError());
     if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_stop, s));
     return VXL_OK;
