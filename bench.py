@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--rows-per-wave", type=int, default=0, help="debug: 1 or 2 32-row blocks per wave")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the separate gather/decode measurements")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy (a dispatch of known size against which "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled)")
     return ap.parse_args()
 
 
@@ -121,6 +124,13 @@ def main():
         vxl.chunk_score_topk(gl, desc, dqd, dk, top_k, idx, mask, workspace=ws_sc)
         vxl.gather_bilevel_kv(gl, desc, dk, dv, mask, kmix, vmix, mix_len, None, ws_ga)
         vxl.bilevel_decode(desc, dqd, kmix, vmix, mix_len, od, None, ws_de)
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
