@@ -13,38 +13,60 @@ __device__ __forceinline__ float ld(const uint16_t* p) { return __uint_as_float(
 
 // ------------------------------------------------------------------------------------------
 // kbar[g, c, :] = mean of the dense key rows of chunk c.  One block per (chunk, kv head).
-// Thread (rg, dl) sums rows rg, rg + R, ... of column dl in row order, and the R partial sums
-// are added in a fixed order, so the result depends only on the values and their offsets
-// inside the chunk: two chunks with equal contents get bit-identical means (exact score ties).
+// A thread owns one 16-byte column piece and the rows rg, rg + RG, ... of the chunk, which it
+// sums in row order (four independent accumulators: rows 0,4,8.. / 1,5,9.. of its sequence);
+// the RG partial sums are then added in group order.  The summation tree depends only on the
+// values and their offsets inside the chunk: two chunks with equal contents get bit-identical
+// means, hence exactly tied scores.
 // ------------------------------------------------------------------------------------------
 template <typename T, int D>
 __global__ __launch_bounds__(256) void chunk_summarize_kernel(const T* __restrict__ K,
                                                               const int32_t* __restrict__ bounds,
                                                               float* __restrict__ kbar, int n_tokens,
                                                               int n_chunks) {
-    constexpr int R = 256 / D;                 // row groups: 2 for D=128, 4 for D=64
-    __shared__ float part[R][D];
+    constexpr int EPC = 16 / (int)sizeof(T);        // elements per 16-byte piece
+    constexpr int PPR = D / EPC;                    // pieces per row
+    constexpr int RG = 256 / PPR;                   // row groups
+    __shared__ float part[RG][D];
     const int c = blockIdx.x, g = blockIdx.y;
-    const int dl = threadIdx.x % D, rg = threadIdx.x / D;
+    const int piece = threadIdx.x % PPR, rg = threadIdx.x / PPR;
     const int lo = bounds[c], hi = bounds[c + 1];
-    const T* base = K + ((size_t)g * n_tokens) * D + dl;
-    // four independent accumulators per thread keep several loads in flight
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-    int r = lo + rg;
-    for (; r + 3 * R < hi; r += 4 * R) {
-        a0 += ld(base + (size_t)r * D);
-        a1 += ld(base + (size_t)(r + R) * D);
-        a2 += ld(base + (size_t)(r + 2 * R) * D);
-        a3 += ld(base + (size_t)(r + 3 * R) * D);
-    }
-    for (; r < hi; r += R) a0 += ld(base + (size_t)r * D);
-    part[rg][dl] = (a0 + a1) + (a2 + a3);
-    __syncthreads();
-    if (rg == 0) {
-        float s = part[0][dl];
+    const uint4* base = (const uint4*)(K + (size_t)g * n_tokens * D) + piece;
+    float acc[4][EPC];
 #pragma unroll
-        for (int i = 1; i < R; ++i) s += part[i][dl];
-        kbar[((size_t)g * n_chunks + c) * D + dl] = s / (float)(hi - lo);
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < EPC; ++i) acc[u][i] = 0.f;
+    int r = lo + rg;
+    for (; r + 3 * RG < hi; r += 4 * RG) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = base[(size_t)(r + u * RG) * PPR];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const T* e = (const T*)&v[u];
+#pragma unroll
+            for (int i = 0; i < EPC; ++i) acc[u][i] += ld(e + i);
+        }
+    }
+    for (int u = 0; r < hi; r += RG, ++u) {
+        const uint4 v = base[(size_t)r * PPR];
+        const T* e = (const T*)&v;
+#pragma unroll
+        for (int i = 0; i < EPC; ++i) {
+            if (u == 0) acc[0][i] += ld(e + i);
+            else if (u == 1) acc[1][i] += ld(e + i);
+            else acc[2][i] += ld(e + i);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < EPC; ++i) part[rg][piece * EPC + i] = (acc[0][i] + acc[1][i]) + (acc[2][i] + acc[3][i]);
+    __syncthreads();
+    if (threadIdx.x < D) {
+        float s = part[0][threadIdx.x];
+#pragma unroll
+        for (int i = 1; i < RG; ++i) s += part[i][threadIdx.x];
+        kbar[((size_t)g * n_chunks + c) * D + threadIdx.x] = s / (float)(hi - lo);
     }
 }
 
@@ -78,7 +100,7 @@ __global__ __launch_bounds__(256) void score_topk_kernel(
 #pragma unroll
         for (int i = 0; i < EPC; ++i) acc[i] = 0.f;
         const uint4* src = (const uint4*)qb + p;
-#pragma unroll 4
+#pragma unroll 8
         for (int t = 0; t < T_q; ++t) {
             const uint4 v = src[(size_t)t * row_pieces];
             const T* e = (const T*)&v;
@@ -97,27 +119,30 @@ __global__ __launch_bounds__(256) void score_topk_kernel(
         qbar[e] = a / (float)(T_q * group);
     }
     __syncthreads();
-    // one wave per chunk: dot over (g, d), lanes stride over d
-    const int wave = tid >> 6, lane = tid & 63;
-    for (int c = wave; c < n_sort; c += 4) {
+    // one thread per chunk: dot over (g, d) in that order (independent 16-byte loads of kbar)
+    for (int c = tid; c < n_sort; c += 256) {
         float a = -INFINITY;
         if (c < n_chunks) {
             float acc = 0.f;
             for (int g = 0; g < n_kv_heads; ++g) {
-                const float* kb = kbar + ((size_t)g * n_chunks + c) * D;
+                const float4* kb = (const float4*)(kbar + ((size_t)g * n_chunks + c) * D);
+                const float* qg = qbar + g * D;
                 float pg = 0.f;
-#pragma unroll
-                for (int x = 0; x < D / 64; ++x) pg = fmaf(qbar[g * D + lane + 64 * x], kb[lane + 64 * x], pg);
-                for (int o = 32; o > 0; o >>= 1) pg += __shfl_xor(pg, o);
+#pragma unroll 8
+                for (int x = 0; x < D / 4; ++x) {
+                    const float4 kv = kb[x];
+                    pg = fmaf(qg[4 * x + 0], kv.x, pg);
+                    pg = fmaf(qg[4 * x + 1], kv.y, pg);
+                    pg = fmaf(qg[4 * x + 2], kv.z, pg);
+                    pg = fmaf(qg[4 * x + 3], kv.w, pg);
+                }
                 acc += pg;
             }
             a = acc * (scale / (float)n_kv_heads);
+            if (scores) scores[(size_t)b * n_chunks + c] = a;
         }
-        if (lane == 0) {
-            s_val[c] = a;
-            s_idx[c] = c < n_chunks ? c : 0x7fffffff;
-            if (scores && c < n_chunks) scores[(size_t)b * n_chunks + c] = a;
-        }
+        s_val[c] = a;
+        s_idx[c] = c < n_chunks ? c : 0x7fffffff;
     }
     __syncthreads();
     // bitonic sort, best first

@@ -4,9 +4,10 @@
 // The G*T query rows that share one KV head (G = query heads per KV head) are stacked along the
 // query dimension: row rho = t*G + hg.  A workgroup owns one (query b, KV head g, row tile,
 // key split) and streams its slice of Kmix/Vmix exactly once through LDS (64-key tiles, double
-// buffered); every wave owns QB blocks of 32 query rows.  Each workgroup writes a normalised
-// partial output and the base-2 log-sum-exp of its scaled logits; the merge kernel combines the
-// splits of a row in split order, so the result does not depend on scheduling.
+// buffered, next tile prefetched into registers); every wave owns QB blocks of 32 query rows.
+// Each workgroup writes a normalised partial output and the base-2 log-sum-exp of its scaled
+// logits; the merge kernel combines the splits of a row with weights and a summation order
+// that depend only on the split index, so the result does not depend on scheduling.
 #include "vxl_internal.h"
 #include "vxl_mfma.h"
 
@@ -17,12 +18,11 @@ namespace {
 template <int D, int QB>
 struct DecodeCfg {
     static constexpr int RT = 128 * QB;            // query rows per workgroup
-    static constexpr int KROW = LdsRows<D>::K;   // LDS row strides (elements)
+    static constexpr int KROW = LdsRows<D>::K;     // LDS row strides (elements)
     static constexpr int VROW = LdsRows<D>::V;
     static constexpr int K_ELEMS = kKeyTile * KROW;
     static constexpr int V_ELEMS = kKeyTile * VROW;
     static constexpr int LDS_BYTES = 2 * (K_ELEMS + V_ELEMS) * 2;
-    static constexpr int LD = D / 32;              // 16-byte loads per thread per tile (K and V each)
 };
 
 template <int D, int QB>
@@ -74,39 +74,25 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void decode_split_kernel(
     const float c2 = scale * kLog2e;
     const bool wave_active = wrow0 < n_rows;       // waves without rows only help with the copies
 
-    const uint16_t* kbase = Kmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D;
-    const uint16_t* vbase = Vmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D;
-    uint4 kreg[C::LD], vreg[C::LD];
-    auto fetch = [&](int key0) {
-#pragma unroll
-        for (int i = 0; i < C::LD; ++i) {
-            const int idx = tid + 256 * i, r = idx / (D / 8), part = idx % (D / 8);
-            // rows past the end of the split are clamped to its last row: their scores are
-            // masked, and a finite V row keeps 0 * v finite
-            const size_t row = (size_t)min(key0 + r, k_hi - 1) * D;
-            kreg[i] = ((const uint4*)(kbase + row))[part];
-            vreg[i] = ((const uint4*)(vbase + row))[part];
-        }
-    };
-    auto stage = [&](int buf) {
-        uint16_t* kd = Ks + buf * C::K_ELEMS;
-        uint16_t* vd = Vs + buf * C::V_ELEMS;
-#pragma unroll
-        for (int i = 0; i < C::LD; ++i) {
-            const int idx = tid + 256 * i, r = idx / (D / 8), part = idx % (D / 8);
-            *(uint4*)(kd + k_tile_off<D>(r, part)) = kreg[i];
-            *(uint4*)(vd + r * C::VROW + part * 8) = vreg[i];
-        }
-    };
-
+    const char* kbase = (const char*)(Kmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
+    const char* vbase = (const char*)(Vmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
+    const int ld_r = tid / (D / 8), ld_part = tid % (D / 8);
+    TileRegs<D, C::VROW> tr;
     const int n_t = (k_hi - k_lo + kKeyTile - 1) / kKeyTile;
-    fetch(k_lo);
-    stage(0);
+    // rows past the end of the split are clamped to its last row (scores masked, V finite)
+    tr.fetch(kbase + (size_t)k_lo * (D * 2), vbase + (size_t)k_lo * (D * 2), ld_r, ld_part,
+             min(kKeyTile - 1, k_hi - 1 - k_lo));
+    tr.stage(Ks, Vs, ld_r, ld_part);
     __syncthreads();
     for (int ti = 0; ti < n_t; ++ti) {
         const int buf = ti & 1;
         const int key0 = k_lo + ti * kKeyTile;
-        if (ti + 1 < n_t) fetch(key0 + kKeyTile);
+        {   // next tile (the last iteration re-reads its own): unconditional, fenced, in flight below
+            const int nk0 = k_lo + min(ti + 1, n_t - 1) * kKeyTile;
+            tr.fetch(kbase + (size_t)nk0 * (D * 2), vbase + (size_t)nk0 * (D * 2), ld_r, ld_part,
+                     min(kKeyTile - 1, k_hi - 1 - nk0));
+            __builtin_amdgcn_sched_barrier(0);
+        }
         if (wave_active) {
             f32x16 s[QB][2];
             qk_tile<D, QB, C::KROW>(Ks + buf * C::K_ELEMS, qreg, l32, hi, s);
@@ -126,7 +112,7 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void decode_split_kernel(
                 softmax_tile<D / 32>(s[qb], c2, m_run[qb], l_run[qb], o[qb], pb[qb]);
             pv_tile<D, QB, C::VROW>(Vs + buf * C::V_ELEMS, pb, lane, o);
         }
-        if (ti + 1 < n_t) stage(buf ^ 1);
+        tr.stage(Ks + (buf ^ 1) * C::K_ELEMS, Vs + (buf ^ 1) * C::V_ELEMS, ld_r, ld_part);
         __syncthreads();
     }
 
@@ -160,33 +146,62 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float v) {
     return (uint16_t)(b >> 16);
 }
 
-// One thread per (row, d): combine the splits in split order.
+// One workgroup per query row.  Weights w_s = exp2(lse_s - max) go to LDS; the thread grid
+// (split group sg, float4 column) accumulates the splits s = sg, sg + SG, ... in that order and
+// the SG partial sums are added in group order: a fixed summation tree.
 template <int D>
 __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restrict__ part_o,
                                                            const float* __restrict__ part_lse,
                                                            uint16_t* __restrict__ O, float* __restrict__ LSE,
                                                            int T_q, int n_q_heads, int n_kv_heads, int group,
                                                            int n_split) {
-    constexpr int RPB = 256 / D;                    // rows per block
+    constexpr int NV = D / 4;                       // float4 columns per row
+    constexpr int SG = 256 / NV;                    // split groups
+    extern __shared__ float sm[];
+    float* w = sm;                                  // [n_split]
+    float* red = sm + ((n_split + 3) & ~3);         // [SG][D]
+    __shared__ float wave_max[4];
     const int n_rows = group * T_q;
-    const int rho = blockIdx.x * RPB + threadIdx.x / D, d = threadIdx.x % D;
-    const int g = blockIdx.y, b = blockIdx.z;
-    if (rho >= n_rows) return;
+    const int rho = blockIdx.x, g = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     const size_t base = ((size_t)b * n_kv_heads + g) * n_split;
+
     float mx = -INFINITY;
-    for (int s = 0; s < n_split; ++s) mx = fmaxf(mx, part_lse[(base + s) * n_rows + rho]);
-    float wsum = 0.f, acc = 0.f;
-    for (int s = 0; s < n_split; ++s) {
-        const float lse = part_lse[(base + s) * n_rows + rho];
-        if (lse == -INFINITY) continue;
-        const float w = __builtin_amdgcn_exp2f(lse - mx);
-        wsum += w;
-        acc = fmaf(w, part_o[((base + s) * n_rows + rho) * D + d], acc);
+    for (int s = tid; s < n_split; s += 256) {
+        const float v = part_lse[(base + s) * n_rows + rho];
+        w[s] = v;
+        mx = fmaxf(mx, v);
     }
-    const int t = rho / group, hg = rho % group;
-    const size_t row = ((size_t)b * T_q + t) * n_q_heads + g * group + hg;
-    O[row * D + d] = f32_to_bf16(acc / wsum);
-    if (LSE && d == 0) LSE[row] = (mx + __builtin_amdgcn_logf(wsum)) * kLn2;
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if ((tid & 63) == 0) wave_max[tid >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
+    for (int s = tid; s < n_split; s += 256) w[s] = w[s] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(w[s] - mx);
+    __syncthreads();
+
+    const int sg = tid / NV, dq = tid % NV;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = sg; s < n_split; s += SG) {
+        const float ws = w[s];
+        if (ws != 0.f) {
+            const float4 v = *(const float4*)(part_o + ((base + s) * n_rows + rho) * D + dq * 4);
+            acc.x = fmaf(ws, v.x, acc.x);
+            acc.y = fmaf(ws, v.y, acc.y);
+            acc.z = fmaf(ws, v.z, acc.z);
+            acc.w = fmaf(ws, v.w, acc.w);
+        }
+    }
+    *(float4*)(red + sg * D + dq * 4) = acc;
+    __syncthreads();
+    if (tid < D) {
+        float a = 0.f, wsum = 0.f;
+#pragma unroll
+        for (int i = 0; i < SG; ++i) a += red[i * D + tid];
+        for (int s = 0; s < n_split; ++s) wsum += w[s];
+        const int t = rho / group, hg = rho % group;
+        const size_t row = ((size_t)b * T_q + t) * n_q_heads + g * group + hg;
+        O[row * D + tid] = f32_to_bf16(a / wsum);
+        if (LSE && tid == 0) LSE[row] = (mx + __builtin_amdgcn_logf(wsum)) * kLn2;
+    }
 }
 
 }  // namespace
@@ -213,10 +228,9 @@ static vxl_status run_decode(const vxl_attn_desc* d, float scale, const void* Qd
                        mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap, n_rtile,
                        p.split_len, scale);
     VXL_HIP_TRY(hipGetLastError());
-    constexpr int rpb = 256 / D;
-    hipLaunchKernelGGL((decode_merge_kernel<D>), dim3((n_rows + rpb - 1) / rpb, d->n_kv_heads, batch), dim3(256),
-                       0, s, part_o, part_lse, (uint16_t*)O, LSE, T, d->n_q_heads, d->n_kv_heads, group,
-                       p.n_split);
+    const size_t merge_lds = (size_t)(((p.n_split + 3) & ~3) + 256 / (D / 4) * D) * sizeof(float);
+    hipLaunchKernelGGL((decode_merge_kernel<D>), dim3(n_rows, d->n_kv_heads, batch), dim3(256), merge_lds, s,
+                       part_o, part_lse, (uint16_t*)O, LSE, T, d->n_q_heads, d->n_kv_heads, group, p.n_split);
     VXL_HIP_TRY(hipGetLastError());
     return VXL_OK;
 }

@@ -48,6 +48,45 @@ __device__ __forceinline__ int k_tile_off(int row, int piece) {
     return row * D + ((piece ^ ((row / RPL) & (PPR - 1))) << 3);
 }
 
+// Register staging of one 64-key K tile and V tile by a 256-thread workgroup: every thread
+// carries D/32 16-byte pieces of each.  The pieces are named members, not an array: they have to
+// live in VGPRs across a scheduling fence between the global loads and the LDS stores.
+template <int D, int VROW>
+struct TileRegs {
+    static constexpr int LD = D / 32;
+    static constexpr int RPP = 256 / (D / 8);         // rows covered by one pass of the 256 threads
+    uint4 k0, k1, k2, k3, v0, v1, v2, v3;
+
+    // kb / vb: wave-uniform byte pointers to row 0 of the tile; rows beyond rlim are clamped to it
+    // (the caller masks their scores; a clamped V row is finite, so 0 * v stays 0).
+    __device__ __forceinline__ void fetch(const char* kb, const char* vb, int ld_r, int ld_part, int rlim) {
+#define VXL_TILE_OFF(i_) ((uint32_t)min(ld_r + (i_) * RPP, rlim) * (D * 2) + ld_part * 16)
+        k0 = *(const uint4*)(kb + VXL_TILE_OFF(0));
+        v0 = *(const uint4*)(vb + VXL_TILE_OFF(0));
+        k1 = *(const uint4*)(kb + VXL_TILE_OFF(1));
+        v1 = *(const uint4*)(vb + VXL_TILE_OFF(1));
+        if constexpr (LD > 2) {
+            k2 = *(const uint4*)(kb + VXL_TILE_OFF(2));
+            v2 = *(const uint4*)(vb + VXL_TILE_OFF(2));
+            k3 = *(const uint4*)(kb + VXL_TILE_OFF(3));
+            v3 = *(const uint4*)(vb + VXL_TILE_OFF(3));
+        }
+#undef VXL_TILE_OFF
+    }
+    __device__ __forceinline__ void stage(uint16_t* kt, uint16_t* vt, int ld_r, int ld_part) const {
+        *(uint4*)(kt + k_tile_off<D>(ld_r, ld_part)) = k0;
+        *(uint4*)(vt + ld_r * VROW + ld_part * 8) = v0;
+        *(uint4*)(kt + k_tile_off<D>(ld_r + RPP, ld_part)) = k1;
+        *(uint4*)(vt + (ld_r + RPP) * VROW + ld_part * 8) = v1;
+        if constexpr (LD > 2) {
+            *(uint4*)(kt + k_tile_off<D>(ld_r + 2 * RPP, ld_part)) = k2;
+            *(uint4*)(vt + (ld_r + 2 * RPP) * VROW + ld_part * 8) = v2;
+            *(uint4*)(kt + k_tile_off<D>(ld_r + 3 * RPP, ld_part)) = k3;
+            *(uint4*)(vt + (ld_r + 3 * RPP) * VROW + ld_part * 8) = v3;
+        }
+    }
+};
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
