@@ -200,22 +200,31 @@ def measure_bilevel(torch, vxl, w, gl, desc, dk, dv, dqd, mask, l_cap, mixlen):
     ws_ga = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_GATHER, gl, desc, B))
 
     def timed(fn, iters):
+        """us per call of fn(i), i = 0..iters-1, replayed from one captured HIP graph (the calls
+        are a few microseconds long: launched one by one they would measure the host)."""
         for i in range(3):
             fn(i)
         torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(iters):
+                fn(i)
+        graph.replay()
+        torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 3
         a.record()
-        for i in range(iters):
-            fn(i)
+        for _ in range(reps):
+            graph.replay()
         b.record()
         torch.cuda.synchronize()
-        return a.elapsed_time(b) * 1e3 / iters           # us per call
+        return a.elapsed_time(b) * 1e3 / (iters * reps)
 
-    iters = 4 * n_rot
+    iters = 2 * n_rot
     us_gather = timed(lambda i: vxl.gather_bilevel_kv(gl, desc, dk, dv, mask, kmixes[i % n_rot],
                                                       vmixes[i % n_rot], mix_len, None, ws_ga), iters)
     gather_bytes = 2 * kv_bytes                             # read + write, K and V
-    res = {"mixed_kv_bytes": kv_bytes, "rotating_buffers": n_rot,
+    res = {"mixed_kv_bytes": kv_bytes, "rotating_buffers": n_rot, "timing": "HIP graph replay",
            "gather": {"us": us_gather, "GBps": gather_bytes / us_gather / 1e3,
                       "frac_hbm": gather_bytes / us_gather / 1e3 / PEAK_HBM_GBS}}
     # decode, batched: all T tokens in one call

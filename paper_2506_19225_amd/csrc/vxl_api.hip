@@ -57,6 +57,24 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
     const int row_tile = rows > 128 ? 256 : 128;
     const int n_rtile = (rows + row_tile - 1) / row_tile;
     const int tiles = (l_cap + kKeyTile - 1) / kKeyTile;
+    if (rows <= kRowBlock) {
+        // Step mode: every wave of a workgroup owns whole tiles; one workgroup per compute unit
+        // (its four tile pairs fill the LDS), tiles spread evenly over at most ~256 workgroups.
+        const long units = (long)batch * d->n_kv_heads;
+        const long max_split = std::max<long>(1, 256 / units);
+        long n_split = std::min<long>((tiles + 3) / 4, max_split);
+        const int tpw = (int)((tiles + 4 * n_split - 1) / (4 * n_split));
+        n_split = (tiles + 4 * tpw - 1) / (4 * tpw);
+        p.n_split = (int)n_split;
+        p.split_len = 4 * tpw * kKeyTile;
+        size_t off = 0;
+        p.part_o = off;
+        off += align_up((size_t)batch * d->n_kv_heads * p.n_split * rows * d->head_dim * sizeof(float), 256);
+        p.part_ml = off;
+        off += align_up((size_t)batch * d->n_kv_heads * p.n_split * rows * sizeof(float), 256);
+        p.total = off;
+        return p;
+    }
     // Split the keys until about two workgroups per compute unit exist, but keep the partial
     // results (fp32 rows per split) below roughly twice the KV bytes they summarise.
     const long base_blocks = (long)batch * d->n_kv_heads * n_rtile;

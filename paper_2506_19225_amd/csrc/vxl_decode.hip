@@ -139,6 +139,110 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void decode_split_kernel(
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Step-mode kernel for at most 32 stacked query rows (e.g. T = 1..4 at G = 7): the work is pure
+// streaming, so every WAVE owns its own 64-key tiles (tile = 4*(split*tpw + i) + wave) and its
+// own LDS tile pair, filled by direct global->LDS loads; there is no workgroup barrier in the
+// loop.  The four waves' running (max, sum, O) are merged through LDS in wave order and the
+// workgroup writes one normalised partial + base-2 LSE per row.
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256, 1) void decode_wave_kernel(
+    const uint16_t* __restrict__ Qd, const uint16_t* __restrict__ Kmix, const uint16_t* __restrict__ Vmix,
+    const int32_t* __restrict__ mix_len, float* __restrict__ part_o, float* __restrict__ part_lse, int T_q,
+    int n_q_heads, int n_kv_heads, int group, int l_cap, int tiles_per_wave, float scale) {
+    constexpr int TILE_ELEMS = kKeyTile * D;                   // one unpadded tile
+    constexpr int RED_ROW = D + 4;                             // floats per row of the merge area
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    uint16_t* Kw = lds + wave * 2 * TILE_ELEMS;                // this wave's K tile, then its V tile
+    uint16_t* Vw = Kw + TILE_ELEMS;
+    const int split = blockIdx.x, n_split = gridDim.x, g = blockIdx.y, b = blockIdx.z;
+    const int n_rows = group * T_q;                            // <= 32
+    const int len = min(max(mix_len[b], 0), l_cap);
+    const int n_tiles = (len + kKeyTile - 1) / kKeyTile;
+    const size_t part_base = (((size_t)b * n_kv_heads + g) * n_split + split) * (size_t)n_rows;
+
+    bf16x8 qreg[1][D / 16];
+    {
+        const int rho = min(l32, n_rows - 1);
+        const int t = rho / group, hg = rho % group;
+        const uint4* src = (const uint4*)(Qd + (((size_t)b * T_q + t) * n_q_heads + g * group + hg) * D);
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) qreg[0][ks] = __builtin_bit_cast(bf16x8, src[ks * 2 + hi]);
+    }
+    f32x16 o[1][D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) o[0][db] = zero16();
+    float m_run = -INFINITY, l_run = 0.f;
+    const float c2 = scale * kLog2e;
+    const char* kbase = (const char*)(Kmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
+    const char* vbase = (const char*)(Vmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
+
+    for (int i = 0; i < tiles_per_wave; ++i) {
+        const int tile = (split * tiles_per_wave + i) * 4 + wave;
+        if (tile >= n_tiles) break;
+        const int key0 = tile * kKeyTile;
+        const int rlim = min(kKeyTile - 1, len - 1 - key0);
+        dma_tile_wave<D>(kbase + (size_t)key0 * (D * 2), vbase + (size_t)key0 * (D * 2), Kw, Vw, lane, rlim);
+        __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): the tile is in LDS
+        __builtin_amdgcn_wave_barrier();
+        f32x16 s[1][2];
+        qk_tile<D, 1, D>(Kw, qreg, l32, hi, s);
+        if (rlim < kKeyTile - 1) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[0][kb][r] = acc_key(kb, r, hi) <= rlim ? s[0][kb][r] : -INFINITY;
+        }
+        bf16x8 pb[1][2][2];
+        softmax_tile<D / 32>(s[0], c2, m_run, l_run, o[0], pb[0]);
+        pv_tile<D, 1, D>(Vw, pb, lane, o);
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // ---- merge the four waves (their tile buffers are free now) ----
+    float* red = (float*)(lds + wave * 2 * TILE_ELEMS);        // [32][RED_ROW] + stats behind it
+    float* stats = red + 32 * RED_ROW;                         // [32][2]: reference logit, sum
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (l32 < n_rows) {
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                float4 v;
+                v.x = o[0][db][rq * 4 + 0]; v.y = o[0][db][rq * 4 + 1];
+                v.z = o[0][db][rq * 4 + 2]; v.w = o[0][db][rq * 4 + 3];
+                *(float4*)(red + l32 * RED_ROW + db * 32 + rq * 8 + hi * 4) = v;
+            }
+        if (hi == 0) { stats[l32 * 2] = m_run; stats[l32 * 2 + 1] = l_tot; }
+    }
+    __syncthreads();
+    constexpr int WSTRIDE = 2 * TILE_ELEMS / 2;                // floats between the waves' areas
+    const float* red0 = (const float*)lds;
+    for (int e = tid; e < n_rows * D; e += 256) {
+        const int row = e / D, dd = e % D;
+        float mw[4], lw[4], M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float* st = red0 + w * WSTRIDE + 32 * RED_ROW;
+            mw[w] = st[row * 2]; lw[w] = st[row * 2 + 1];
+            M = fmaxf(M, mw[w]);
+        }
+        float acc = 0.f, L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float f = mw[w] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mw[w] - M) * c2);
+            L = fmaf(f, lw[w], L);
+            acc = fmaf(f, red0[w * WSTRIDE + row * RED_ROW + dd], acc);
+        }
+        const bool empty = M == -INFINITY;
+        part_o[(part_base + row) * D + dd] = empty ? 0.f : acc / L;
+        if (dd == 0) part_lse[part_base + row] = empty ? -INFINITY : M * c2 + __builtin_amdgcn_logf(L);
+    }
+}
+
 __device__ __forceinline__ uint16_t f32_to_bf16(float v) {
     uint32_t b = __float_as_uint(v);
     if ((b & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
@@ -235,10 +339,42 @@ static vxl_status run_decode(const vxl_attn_desc* d, float scale, const void* Qd
     return VXL_OK;
 }
 
+template <int D>
+static vxl_status run_decode_wave(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
+                                  const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len, void* O,
+                                  float* LSE, void* ws, hipStream_t s) {
+    const DecodePlan p = decode_plan(d, batch, T, l_cap);
+    float* part_o = (float*)((char*)ws + p.part_o);
+    float* part_lse = (float*)((char*)ws + p.part_ml);
+    const int group = d->n_q_heads / d->n_kv_heads;
+    const int n_rows = group * T;
+    constexpr int lds_bytes = 4 * 2 * kKeyTile * D * 2;
+    static_assert(32 * (D + 4) * 4 + 32 * 2 * 4 <= 2 * kKeyTile * D * 2, "merge area must fit a wave's tiles");
+    static bool attr_done = false;
+    if (!attr_done) {
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_wave_kernel<D>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((decode_wave_kernel<D>), dim3(p.n_split, d->n_kv_heads, batch), dim3(256), lds_bytes, s,
+                       (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix, mix_len, part_o,
+                       part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap, p.split_len / (4 * kKeyTile), scale);
+    VXL_HIP_TRY(hipGetLastError());
+    const size_t merge_lds = (size_t)(((p.n_split + 3) & ~3) + 256 / (D / 4) * D) * sizeof(float);
+    hipLaunchKernelGGL((decode_merge_kernel<D>), dim3(n_rows, d->n_kv_heads, batch), dim3(256), merge_lds, s,
+                       part_o, part_lse, (uint16_t*)O, LSE, T, d->n_q_heads, d->n_kv_heads, group, p.n_split);
+    VXL_HIP_TRY(hipGetLastError());
+    return VXL_OK;
+}
+
 vxl_status launch_decode_bf16(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
                               const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len, void* O,
                               float* LSE, void* ws, hipStream_t s) {
     const int n_rows = (d->n_q_heads / d->n_kv_heads) * T;
+    if (n_rows <= kRowBlock)
+        return d->head_dim == 128
+                   ? run_decode_wave<128>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s)
+                   : run_decode_wave<64>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s);
     const bool big = n_rows > 128;
     if (d->head_dim == 128)
         return big ? run_decode<128, 2>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s)

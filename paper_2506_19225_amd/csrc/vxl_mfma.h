@@ -87,6 +87,7 @@ struct TileRegs {
     }
 };
 
+constexpr int kKeyTileRows = 64;                    // keys per tile (same as kKeyTile)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -167,17 +168,63 @@ __device__ __forceinline__ void softmax_tile(f32x16 (&s)[2], float c2, float& m_
     l_run += sum0 + sum1;
 }
 
+// Element offset of 16-byte piece `piece` of row `row` in an UNPADDED V tile (row stride D).
+// The 64-byte chunks of a row are XOR-ed with the row's index inside a group of four 256-byte
+// lines, so the four rows a half-wave touches in one transposing read fall into distinct banks.
+template <int D>
+__device__ __forceinline__ int v_tile_off(int row, int piece) {
+    constexpr int CPR = D * 2 / 64;                   // 64-byte chunks per row
+    constexpr int RPL = D == 128 ? 1 : 2;             // rows per 256-byte line
+    return row * D + ((((piece >> 2) ^ ((row / RPL) & (CPR - 1))) << 2 | (piece & 3)) << 3);
+}
+
 // A operand of the second product for the 16-key step (kb, j) and the 32-wide d block db, read
-// transposed from a row-major V tile (64 keys x D, row stride VROW elements) in LDS.
-template <int VROW>
+// transposed from a row-major V tile in LDS: row stride VROW elements when VROW > D (padded
+// layout), or the unpadded swizzled layout of v_tile_off when VROW == D.
+template <int D, int VROW>
 __device__ __forceinline__ bf16x8 load_vt_operand(const uint16_t* vt, int kb, int j, int db, int lane) {
     const int hi = lane >> 5, dhalf = (lane >> 4) & 1, s = lane & 15;
-    const uint16_t* p = vt + (kb * 32 + j * 16 + 4 * hi + (s >> 2)) * VROW + db * 32 + dhalf * 16 + 4 * (s & 3);
+    const int row = kb * 32 + j * 16 + 4 * hi + (s >> 2);
+    const uint16_t* p;
+    if constexpr (VROW == D) {
+        constexpr int CPR = D * 2 / 64, RPL = D == 128 ? 1 : 2;
+        p = vt + row * D + ((db ^ ((row / RPL) & (CPR - 1))) << 5) + dhalf * 16 + 4 * (s & 3);
+    } else {
+        p = vt + row * VROW + db * 32 + dhalf * 16 + 4 * (s & 3);
+    }
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
-    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * VROW));
+    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * VROW));   // row + 8: same swizzle
     const s16x8 both = __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, both);
+}
+
+// Direct global -> LDS copy of one 64-key K tile and V tile by ONE wave (global_load_lds_dwordx4:
+// lane i's 16 bytes land at the LDS base + 16*i, so one instruction fills 1 KiB of consecutive
+// LDS and the swizzles are applied on the global side: a lane fetches the piece that belongs at
+// its LDS position).  kt / vt are the unpadded swizzled tiles (k_tile_off / v_tile_off); rows
+// beyond rlim are clamped to it.  Completion is tracked by vmcnt.
+template <int D>
+__device__ __forceinline__ void dma_tile_wave(const char* kb, const char* vb, uint16_t* kt, uint16_t* vt,
+                                              int lane, int rlim) {
+    constexpr int PPR = D / 8;                        // 16-byte pieces per row
+    constexpr int RPI = 64 / PPR;                     // rows per instruction (1 KiB)
+    typedef const __attribute__((address_space(1))) void* gptr;
+    typedef __attribute__((address_space(3))) void* lptr;
+    const int r_in = lane / PPR, pp = lane % PPR;
+#pragma unroll
+    for (int i = 0; i < kKeyTileRows / RPI; ++i) {
+        const int row = i * RPI + r_in;
+        const int src_row = min(row, rlim);
+        // logical piece that lives at physical position pp of this row
+        const int kp = pp ^ ((row / (16 / PPR)) & (PPR - 1));
+        constexpr int CPR = D * 2 / 64, RPL = D == 128 ? 1 : 2;
+        const int vp = (((pp >> 2) ^ ((row / RPL) & (CPR - 1))) << 2) | (pp & 3);
+        __builtin_amdgcn_global_load_lds((gptr)(kb + (size_t)src_row * (D * 2) + kp * 16),
+                                         (lptr)(kt + i * RPI * D), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr)(vb + (size_t)src_row * (D * 2) + vp * 16),
+                                         (lptr)(vt + i * RPI * D), 16, 0, 0);
+    }
 }
 
 // O^T[qb][db] += V^T . P^T over the 64 keys of the tile.
@@ -190,7 +237,7 @@ __device__ __forceinline__ void pv_tile(const uint16_t* vt, const bf16x8 (&pb)[Q
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int db = 0; db < D / 32; ++db) {
-                const bf16x8 a = load_vt_operand<VROW>(vt, kb, j, db, lane);
+                const bf16x8 a = load_vt_operand<D, VROW>(vt, kb, j, db, lane);
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb)
                     o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb][kb][j], o[qb][db], 0, 0, 0);
