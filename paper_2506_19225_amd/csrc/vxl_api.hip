@@ -58,15 +58,18 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
     const int n_rtile = (rows + row_tile - 1) / row_tile;
     const int tiles = (l_cap + kKeyTile - 1) / kKeyTile;
     if (rows <= kRowBlock) {
-        // Step mode: every wave of a workgroup owns whole tiles; one workgroup per compute unit
-        // (its four tile pairs fill the LDS), tiles spread evenly over at most ~256 workgroups.
+        // Step mode: every wave of an 8-wave workgroup owns whole 32-key tiles; one workgroup per
+        // compute unit (its tile pairs fill the LDS), tiles spread evenly over at most ~256
+        // workgroups.
+        constexpr int kWaves = 8, kTile = 32;
+        const int tiles32 = (l_cap + kTile - 1) / kTile;
         const long units = (long)batch * d->n_kv_heads;
         const long max_split = std::max<long>(1, 256 / units);
-        long n_split = std::min<long>((tiles + 3) / 4, max_split);
-        const int tpw = (int)((tiles + 4 * n_split - 1) / (4 * n_split));
-        n_split = (tiles + 4 * tpw - 1) / (4 * tpw);
+        long n_split = std::min<long>((tiles32 + kWaves - 1) / kWaves, max_split);
+        const int tpw = (int)((tiles32 + kWaves * n_split - 1) / (kWaves * n_split));
+        n_split = (tiles32 + kWaves * tpw - 1) / (kWaves * tpw);
         p.n_split = (int)n_split;
-        p.split_len = 4 * tpw * kKeyTile;
+        p.split_len = kWaves * tpw * kTile;
         size_t off = 0;
         p.part_o = off;
         off += align_up((size_t)batch * d->n_kv_heads * p.n_split * rows * d->head_dim * sizeof(float), 256);

@@ -141,19 +141,25 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void decode_split_kernel(
 
 // ------------------------------------------------------------------------------------------
 // Step-mode kernel for at most 32 stacked query rows (e.g. T = 1..4 at G = 7): the work is pure
-// streaming, so every WAVE owns its own 64-key tiles (tile = 4*(split*tpw + i) + wave) and its
+// streaming, so every WAVE owns its own 32-key tiles (tile = NW*(split*tpw + i) + wave) and its
 // own LDS tile pair, filled by direct global->LDS loads; there is no workgroup barrier in the
-// loop.  The four waves' running (max, sum, O) are merged through LDS in wave order and the
-// workgroup writes one normalised partial + base-2 LSE per row.
+// loop.  Eight waves per workgroup (two per SIMD) overlap one wave's loads with another's
+// arithmetic and keep 128 KiB of loads in flight per compute unit.  The waves' running
+// (reference, sum, O) are merged through LDS in wave order and the workgroup writes one
+// normalised partial + base-2 LSE per row.
 // ------------------------------------------------------------------------------------------
+constexpr int kStepWaves = 8;       // waves per workgroup of the step-mode kernel
+constexpr int kStepTile = 32;       // keys per wave tile
+
 template <int D>
-__global__ __launch_bounds__(256, 1) void decode_wave_kernel(
+__global__ __launch_bounds__(64 * kStepWaves, 2) void decode_wave_kernel(
     const uint16_t* __restrict__ Qd, const uint16_t* __restrict__ Kmix, const uint16_t* __restrict__ Vmix,
     const int32_t* __restrict__ mix_len, float* __restrict__ part_o, float* __restrict__ part_lse, int T_q,
     int n_q_heads, int n_kv_heads, int group, int l_cap, int tiles_per_wave, float scale) {
-    constexpr int TILE_ELEMS = kKeyTile * D;                   // one unpadded tile
-    constexpr int RED_ROW = D + 4;                             // floats per row of the merge area
+    constexpr int NW = kStepWaves, TK = kStepTile;
+    constexpr int TILE_ELEMS = TK * D;                         // one unpadded tile
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+    __shared__ float stats[NW][32][2];                         // per wave and row: reference logit, sum
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     uint16_t* Kw = lds + wave * 2 * TILE_ELEMS;                // this wave's K tile, then its V tile
@@ -161,7 +167,7 @@ __global__ __launch_bounds__(256, 1) void decode_wave_kernel(
     const int split = blockIdx.x, n_split = gridDim.x, g = blockIdx.y, b = blockIdx.z;
     const int n_rows = group * T_q;                            // <= 32
     const int len = min(max(mix_len[b], 0), l_cap);
-    const int n_tiles = (len + kKeyTile - 1) / kKeyTile;
+    const int n_tiles = (len + TK - 1) / TK;
     const size_t part_base = (((size_t)b * n_kv_heads + g) * n_split + split) * (size_t)n_rows;
 
     bf16x8 qreg[1][D / 16];
@@ -181,30 +187,28 @@ __global__ __launch_bounds__(256, 1) void decode_wave_kernel(
     const char* vbase = (const char*)(Vmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
 
     for (int i = 0; i < tiles_per_wave; ++i) {
-        const int tile = (split * tiles_per_wave + i) * 4 + wave;
+        const int tile = (split * tiles_per_wave + i) * NW + wave;
         if (tile >= n_tiles) break;
-        const int key0 = tile * kKeyTile;
-        const int rlim = min(kKeyTile - 1, len - 1 - key0);
-        dma_tile_wave<D>(kbase + (size_t)key0 * (D * 2), vbase + (size_t)key0 * (D * 2), Kw, Vw, lane, rlim);
+        const int key0 = tile * TK;
+        const int rlim = min(TK - 1, len - 1 - key0);
+        dma_tile_wave<D, TK>(kbase + (size_t)key0 * (D * 2), vbase + (size_t)key0 * (D * 2), Kw, Vw, lane, rlim);
         __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): the tile is in LDS
         __builtin_amdgcn_wave_barrier();
-        f32x16 s[1][2];
-        qk_tile<D, 1, D>(Kw, qreg, l32, hi, s);
-        if (rlim < kKeyTile - 1) {
+        f32x16 s[1][1];
+        qk_tile<D, 1, D, 1>(Kw, qreg, l32, hi, s);
+        if (rlim < TK - 1) {
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[0][kb][r] = acc_key(kb, r, hi) <= rlim ? s[0][kb][r] : -INFINITY;
+            for (int r = 0; r < 16; ++r) s[0][0][r] = acc_key(0, r, hi) <= rlim ? s[0][0][r] : -INFINITY;
         }
-        bf16x8 pb[1][2][2];
-        softmax_tile<D / 32>(s[0], c2, m_run, l_run, o[0], pb[0]);
-        pv_tile<D, 1, D>(Vw, pb, lane, o);
+        bf16x8 pb[1][1][2];
+        softmax_tile<D / 32, 1>(s[0], c2, m_run, l_run, o[0], pb[0]);
+        pv_tile<D, 1, D, 1>(Vw, pb, lane, o);
         __builtin_amdgcn_wave_barrier();
     }
 
-    // ---- merge the four waves (their tile buffers are free now) ----
-    float* red = (float*)(lds + wave * 2 * TILE_ELEMS);        // [32][RED_ROW] + stats behind it
-    float* stats = red + 32 * RED_ROW;                         // [32][2]: reference logit, sum
+    // ---- merge the waves (their tile buffers are free now): area [32 rows][D] floats per wave ----
+    static_assert(32 * D * 4 <= 2 * TILE_ELEMS * 2, "merge area must fit a wave's tile pair");
+    float* red = (float*)(lds + wave * 2 * TILE_ELEMS);
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     if (l32 < n_rows) {
 #pragma unroll
@@ -214,28 +218,25 @@ __global__ __launch_bounds__(256, 1) void decode_wave_kernel(
                 float4 v;
                 v.x = o[0][db][rq * 4 + 0]; v.y = o[0][db][rq * 4 + 1];
                 v.z = o[0][db][rq * 4 + 2]; v.w = o[0][db][rq * 4 + 3];
-                *(float4*)(red + l32 * RED_ROW + db * 32 + rq * 8 + hi * 4) = v;
+                *(float4*)(red + l32 * D + db * 32 + rq * 8 + hi * 4) = v;
             }
-        if (hi == 0) { stats[l32 * 2] = m_run; stats[l32 * 2 + 1] = l_tot; }
+        if (hi == 0) { stats[wave][l32][0] = m_run; stats[wave][l32][1] = l_tot; }
     }
     __syncthreads();
     constexpr int WSTRIDE = 2 * TILE_ELEMS / 2;                // floats between the waves' areas
     const float* red0 = (const float*)lds;
-    for (int e = tid; e < n_rows * D; e += 256) {
+    for (int e = tid; e < n_rows * D; e += 64 * NW) {
         const int row = e / D, dd = e % D;
-        float mw[4], lw[4], M = -INFINITY;
+        float M = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const float* st = red0 + w * WSTRIDE + 32 * RED_ROW;
-            mw[w] = st[row * 2]; lw[w] = st[row * 2 + 1];
-            M = fmaxf(M, mw[w]);
-        }
+        for (int w = 0; w < NW; ++w) M = fmaxf(M, stats[w][row][0]);
         float acc = 0.f, L = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const float f = mw[w] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mw[w] - M) * c2);
-            L = fmaf(f, lw[w], L);
-            acc = fmaf(f, red0[w * WSTRIDE + row * RED_ROW + dd], acc);
+        for (int w = 0; w < NW; ++w) {
+            const float mw = stats[w][row][0];
+            const float f = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mw - M) * c2);
+            L = fmaf(f, stats[w][row][1], L);
+            acc = fmaf(f, mw == -INFINITY ? 0.f : red0[w * WSTRIDE + row * D + dd], acc);
         }
         const bool empty = M == -INFINITY;
         part_o[(part_base + row) * D + dd] = empty ? 0.f : acc / L;
@@ -348,17 +349,17 @@ static vxl_status run_decode_wave(const vxl_attn_desc* d, float scale, const voi
     float* part_lse = (float*)((char*)ws + p.part_ml);
     const int group = d->n_q_heads / d->n_kv_heads;
     const int n_rows = group * T;
-    constexpr int lds_bytes = 4 * 2 * kKeyTile * D * 2;
-    static_assert(32 * (D + 4) * 4 + 32 * 2 * 4 <= 2 * kKeyTile * D * 2, "merge area must fit a wave's tiles");
+    constexpr int lds_bytes = kStepWaves * 2 * kStepTile * D * 2;
     static bool attr_done = false;
     if (!attr_done) {
         VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_wave_kernel<D>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
         attr_done = true;
     }
-    hipLaunchKernelGGL((decode_wave_kernel<D>), dim3(p.n_split, d->n_kv_heads, batch), dim3(256), lds_bytes, s,
-                       (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix, mix_len, part_o,
-                       part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap, p.split_len / (4 * kKeyTile), scale);
+    hipLaunchKernelGGL((decode_wave_kernel<D>), dim3(p.n_split, d->n_kv_heads, batch), dim3(64 * kStepWaves),
+                       lds_bytes, s, (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix, mix_len,
+                       part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap,
+                       p.split_len / (kStepWaves * kStepTile), scale);
     VXL_HIP_TRY(hipGetLastError());
     const size_t merge_lds = (size_t)(((p.n_split + 3) & ~3) + 256 / (D / 4) * D) * sizeof(float);
     hipLaunchKernelGGL((decode_merge_kernel<D>), dim3(n_rows, d->n_kv_heads, batch), dim3(256), merge_lds, s,

@@ -104,17 +104,17 @@ __device__ __forceinline__ constexpr int acc_key(int kb, int r, int hi) {
 }
 
 // S^T[qb][kb] = K tile (64 keys, row-major in LDS, pieces placed by k_tile_off) times Q^T.
-template <int D, int QB, int KROW>
+template <int D, int QB, int KROW, int KB = 2>
 __device__ __forceinline__ void qk_tile(const uint16_t* kt, const bf16x8 (&qreg)[QB][D / 16], int l32,
-                                        int hi, f32x16 (&s)[QB][2]) {
+                                        int hi, f32x16 (&s)[QB][KB]) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) s[qb][kb] = zero16();
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < KB; ++kb) {
             const bf16x8 a = *(const bf16x8*)(kt + k_tile_off<D>(kb * 32 + l32, ks * 2 + hi));
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
@@ -129,13 +129,13 @@ __device__ __forceinline__ void qk_tile(const uint16_t* kt, const bf16x8 (&qreg)
 // wave-uniform decision: until then the probabilities stay below 2^8, which fp32 and bf16
 // represent with unchanged relative precision, and the final division by l_run is the same.
 // The sum is taken over the bf16-rounded probabilities (the weights the second product uses).
-template <int DB>
-__device__ __forceinline__ void softmax_tile(f32x16 (&s)[2], float c2, float& m_run, float& l_run,
-                                             f32x16 (&o)[DB], bf16x8 (&pb)[2][2]) {
+template <int DB, int KB = 2>
+__device__ __forceinline__ void softmax_tile(f32x16 (&s)[KB], float c2, float& m_run, float& l_run,
+                                             f32x16 (&o)[DB], bf16x8 (&pb)[KB][2]) {
     typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
     float mx = s[0][0];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
@@ -154,13 +154,13 @@ __device__ __forceinline__ void softmax_tile(f32x16 (&s)[2], float c2, float& m_
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
     float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
             bf16x2 pr;
             pr[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[kb][r], c2, -mc));
             pr[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[kb][r + 1], c2, -mc));
-            if (kb == 0) sum0 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum0, false);
+            if (((kb * 8 + r / 2) & 1) == 0) sum0 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum0, false);
             else sum1 = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum1, false);
             pb[kb][r >> 3][r & 7] = pr[0];
             pb[kb][r >> 3][(r & 7) + 1] = pr[1];
@@ -199,12 +199,12 @@ __device__ __forceinline__ bf16x8 load_vt_operand(const uint16_t* vt, int kb, in
     return __builtin_bit_cast(bf16x8, both);
 }
 
-// Direct global -> LDS copy of one 64-key K tile and V tile by ONE wave (global_load_lds_dwordx4:
+// Direct global -> LDS copy of one ROWS-key K tile and V tile by ONE wave (global_load_lds_dwordx4:
 // lane i's 16 bytes land at the LDS base + 16*i, so one instruction fills 1 KiB of consecutive
 // LDS and the swizzles are applied on the global side: a lane fetches the piece that belongs at
 // its LDS position).  kt / vt are the unpadded swizzled tiles (k_tile_off / v_tile_off); rows
 // beyond rlim are clamped to it.  Completion is tracked by vmcnt.
-template <int D>
+template <int D, int ROWS = 64>
 __device__ __forceinline__ void dma_tile_wave(const char* kb, const char* vb, uint16_t* kt, uint16_t* vt,
                                               int lane, int rlim) {
     constexpr int PPR = D / 8;                        // 16-byte pieces per row
@@ -213,7 +213,7 @@ __device__ __forceinline__ void dma_tile_wave(const char* kb, const char* vb, ui
     typedef __attribute__((address_space(3))) void* lptr;
     const int r_in = lane / PPR, pp = lane % PPR;
 #pragma unroll
-    for (int i = 0; i < kKeyTileRows / RPI; ++i) {
+    for (int i = 0; i < ROWS / RPI; ++i) {
         const int row = i * RPI + r_in;
         const int src_row = min(row, rlim);
         // logical piece that lives at physical position pp of this row
@@ -228,11 +228,11 @@ __device__ __forceinline__ void dma_tile_wave(const char* kb, const char* vb, ui
 }
 
 // O^T[qb][db] += V^T . P^T over the 64 keys of the tile.
-template <int D, int QB, int VROW>
-__device__ __forceinline__ void pv_tile(const uint16_t* vt, const bf16x8 (&pb)[QB][2][2], int lane,
+template <int D, int QB, int VROW, int KB = 2>
+__device__ __forceinline__ void pv_tile(const uint16_t* vt, const bf16x8 (&pb)[QB][KB][2], int lane,
                                         f32x16 (&o)[QB][D / 32]) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll

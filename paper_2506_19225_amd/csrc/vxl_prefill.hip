@@ -244,6 +244,182 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Main kernel, streaming variant: 8 waves = 256 query rows per workgroup (one workgroup per
+// compute unit, two waves per SIMD), K/V tiles brought in by direct global->LDS loads into a ring
+// of NS stages, NS-1 tiles ahead of the arithmetic.  Against the 4-wave kernel this halves the
+// tile traffic, the barriers and the LDS fills per FLOP, takes the staging out of the VALU/VGPR
+// budget, and hides the memory latency behind several tiles of arithmetic.
+//
+// The loads are issued from inline assembly: the compiler cannot see them, so it neither orders
+// them against the LDS reads of other stages nor counts them in its own vmcnt bookkeeping; the
+// kernel does both by hand (every wave issues the same number of loads per tile, and waits with
+// vmcnt = loads still allowed in flight).  No compiler-visible global load is outstanding while
+// the ring runs: the query registers are forced complete before the first ring load.
+// ------------------------------------------------------------------------------------------
+template <int D, int NS>
+struct PrefillDmaCfg {
+    static constexpr int WAVES = 8;
+    static constexpr int BM = 32 * WAVES;
+    static constexpr int TILE = kKeyTile * D;                 // elements of one unpadded K (or V) tile
+    static constexpr int STAGE = 2 * TILE;                    // K tile then V tile
+    static constexpr int LDS_BYTES = NS * STAGE * 2;
+    static constexpr int PPR = D / 8;                         // 16-byte pieces per row
+    static constexpr int RPI = 64 / PPR;                      // rows per load instruction (1 KiB)
+    static constexpr int NI = kKeyTile / RPI;                 // instructions per tile per matrix
+    static constexpr int IPW = NI / WAVES;                    // ... per wave
+    static constexpr int GROUP = 2 * IPW;                     // loads per wave per tile (K and V)
+};
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
+}
+
+// 16 bytes per lane from (uniform base + per-lane offset) to LDS offset lds_off + 16*lane.
+__device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t lds_off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_off), "v"(off), "s"(base) : "memory");
+}
+
+template <int D, int NS>
+__global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
+    const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+    const uint16_t* __restrict__ Kctx, const uint16_t* __restrict__ Vctx, uint16_t* __restrict__ O,
+    float* __restrict__ LSE, const Segment* __restrict__ segs, const WorkItem* __restrict__ work,
+    int n_tokens, int n_q_heads, int group, int ctx_rows_pad, float scale, int n_items, int xpg) {
+    using C = PrefillDmaCfg<D, NS>;
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
+
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int item, h;
+    if (xpg > 0) {
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int j = slot * xpg + xcd % xpg;
+        if (j >= n_items * group) return;
+        item = j / group;
+        h = (xcd / xpg) * group + j % group;
+    } else {
+        item = blockIdx.x / n_q_heads;
+        h = blockIdx.x % n_q_heads;
+    }
+    item = __builtin_amdgcn_readfirstlane(item);
+    h = __builtin_amdgcn_readfirstlane(h);
+    const int g = h / group;
+    const WorkItem wi = work[item];
+    const Segment sg = segs[wi.seg];
+    const int m0 = wi.m_tile * C::BM;
+    const int wrow0 = m0 + wave * 32;
+    const int n_ctx_t = (sg.ctx_len + kKeyTile - 1) / kKeyTile;
+    const int last_row = min(m0 + C::BM, sg.q_len) - 1;
+    const int n_t = n_ctx_t + last_row / kKeyTile + 1;
+
+    bf16x8 qreg[1][D / 16];
+    {
+        const int row = sg.q_start + min(wrow0 + l32, sg.q_len - 1);
+        const uint4* src = (const uint4*)(Q + ((size_t)h * n_tokens + row) * D);
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) qreg[0][ks] = __builtin_bit_cast(bf16x8, src[ks * 2 + hi]);
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) {                 // loaded before the ring starts
+            typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+            asm volatile("" :: "v"(__builtin_bit_cast(u32x4, qreg[0][ks])));
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    const char* kctx_g = (const char*)(Kctx + (size_t)g * ctx_rows_pad * D);
+    const char* vctx_g = (const char*)(Vctx + (size_t)g * ctx_rows_pad * D);
+    const char* kown = (const char*)(K + ((size_t)g * n_tokens + sg.q_start) * D);
+    const char* vown = (const char*)(V + ((size_t)g * n_tokens + sg.q_start) * D);
+    const int r_in = lane / C::PPR, pp = lane % C::PPR;
+
+    // Tile t -> stage t % NS.  Every wave issues GROUP loads: instruction slots wave, wave + 8, ...
+    auto issue = [&](int t) {
+        const bool ctx = t < n_ctx_t;
+        const int row0 = ctx ? t * kKeyTile : (t - n_ctx_t) * kKeyTile;
+        const int rlim = ctx ? kKeyTile - 1 : min(kKeyTile - 1, sg.q_len - 1 - row0);
+        const char* kb = (ctx ? kctx_g : kown) + (size_t)row0 * (D * 2);
+        const char* vb = (ctx ? vctx_g : vown) + (size_t)row0 * (D * 2);
+        const uint32_t st = lds_base + (uint32_t)(t % NS) * (C::STAGE * 2);
+#pragma unroll
+        for (int i = 0; i < C::IPW; ++i) {
+            const int slot = wave + i * C::WAVES;
+            const int row = slot * C::RPI + r_in;
+            const uint32_t roff = (uint32_t)min(row, rlim) * (D * 2);
+            const int kp = pp ^ ((row / (16 / C::PPR)) & (C::PPR - 1));
+            constexpr int CPR = D * 2 / 64, RPL = D == 128 ? 1 : 2;
+            const int vp = (((pp >> 2) ^ ((row / RPL) & (CPR - 1))) << 2) | (pp & 3);
+            dma16(kb, roff + kp * 16, st + slot * 1024);
+            dma16(vb, roff + vp * 16, st + C::TILE * 2 + slot * 1024);
+        }
+    };
+
+    f32x16 o[1][D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) o[0][db] = zero16();
+    float m_run = -INFINITY, l_run = 0.f;
+    const float c2 = scale * kLog2e;
+
+#pragma unroll
+    // Prologue: NS-1 tiles ahead.  Tile indices beyond the last are clamped to it, so that every
+    // wave always issues the same number of loads; a clamped issue rewrites the last tile's own
+    // stage with the same bytes, which is harmless.
+    for (int t = 0; t < NS - 1; ++t) issue(min(t, n_t - 1));
+
+    for (int ti = 0; ti < n_t; ++ti) {
+        wait_vmcnt<C::GROUP * (NS - 2)>();                    // this wave's part of tile ti has landed
+        __builtin_amdgcn_s_barrier();                         // ... and everyone's; stage (ti-1)%NS is free
+        {
+            issue(min(ti + NS - 1, n_t - 1));
+        }
+        const bool is_ctx = ti < n_ctx_t;
+        const int key0 = is_ctx ? ti * kKeyTile : (ti - n_ctx_t) * kKeyTile;
+        const bool skip = !is_ctx && key0 > wrow0 + 31;
+        if (!skip) {
+            const uint16_t* kt = lds + (ti % NS) * C::STAGE;
+            const uint16_t* vt = kt + C::TILE;
+            f32x16 s[1][2];
+            qk_tile<D, 1, D>(kt, qreg, l32, hi, s);
+            const bool need_mask = is_ctx ? (key0 + kKeyTile > sg.ctx_len) : (key0 + kKeyTile - 1 > wrow0);
+            if (need_mask) {
+                const int lim = is_ctx ? sg.ctx_len - key0 - 1 : wrow0 + l32 - key0;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        s[0][kb][r] = acc_key(kb, r, hi) <= lim ? s[0][kb][r] : -INFINITY;
+            }
+            bf16x8 pb[1][2][2];
+            softmax_tile<D / 32>(s[0], c2, m_run, l_run, o[0], pb[0]);
+            pv_tile<D, 1, D>(vt, pb, lane, o);
+        }
+    }
+    wait_vmcnt<0>();                                          // drain the refills before the wave ends
+
+    {
+        const int q_off = wrow0 + l32;
+        const float l_tot = l_run + __shfl_xor(l_run, 32);
+        if (q_off < sg.q_len) {
+            const float inv = 1.f / l_tot;
+            const size_t tok = (size_t)h * n_tokens + sg.q_start + q_off;
+            uint16_t* orow = O + tok * D;
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    bf16x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = (__bf16)(o[0][db][rq * 4 + e] * inv);
+                    *(bf16x4*)(orow + db * 32 + rq * 8 + hi * 4) = v;
+                }
+            if (LSE && hi == 0) LSE[tok] = m_run * scale + logf(l_tot);
+        }
+    }
+}
+
 template <typename F>
 vxl_status enable_big_lds(F kernel, int bytes) {
     VXL_HIP_TRY(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
@@ -260,7 +436,7 @@ extern "C" void vxl_debug_flags(int flags) { g_prefill_dbg = flags; }
 // vxl_chunk_prefill calls run the instrumented instance of the kernel (D = 128, one row block).
 extern "C" void vxl_debug_prefill_profile(void* buf) { g_prof_buf = (unsigned long long*)buf; }
 static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
-extern "C" void vxl_debug_prefill_rows_per_wave(int blocks) { g_prefill_qb = blocks == 2 ? 2 : 1; }
+extern "C" void vxl_debug_prefill_rows_per_wave(int blocks) { g_prefill_qb = (blocks == 2 || blocks == 3) ? blocks : 1; }
 // Measurement hook: when both events are set, every vxl_chunk_prefill records them on its stream
 // immediately before and after the main attention kernel (the pre-pass is outside the bracket).
 extern "C" void vxl_debug_prefill_events(void* start, void* stop) {
@@ -318,8 +494,47 @@ static vxl_status run_prefill(const vxl_layout* L, const vxl_attn_desc* d, float
     return VXL_OK;
 }
 
+template <int D, int NS>
+static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Q,
+                                  const void* K, const void* V, void* O, float* LSE, void* ws, hipStream_t s) {
+    using C = PrefillDmaCfg<D, NS>;
+    const PrefillWorkspace w = prefill_workspace(L, d);
+    uint16_t* kctx = (uint16_t*)((char*)ws + w.kctx);
+    uint16_t* vctx = (uint16_t*)((char*)ws + w.vctx);
+    const int n_rows_pad = L->n_ctx_tiles * kKeyTile;
+    if (L->n_ctx_tiles > 0) {
+        constexpr int rows = 256 / (D * 2 / 16);
+        hipLaunchKernelGGL((compact_kv_kernel<D>), dim3((n_rows_pad + rows - 1) / rows, d->n_kv_heads),
+                           dim3(256), 0, s, (const uint4*)K, (const uint4*)V, L->d_tile_src, (uint4*)kctx,
+                           (uint4*)vctx, n_rows_pad, L->n_tokens);
+        VXL_HIP_TRY(hipGetLastError());
+    }
+    static bool attr_done = false;
+    if (!attr_done) {
+        vxl_status st = enable_big_lds(prefill_dma_kernel<D, NS>, C::LDS_BYTES);
+        if (st != VXL_OK) return st;
+        attr_done = true;
+    }
+    const bool timed = g_ev_start && g_ev_stop;
+    if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_start, s));
+    const int group = d->n_q_heads / d->n_kv_heads;
+    const int xpg = (!(g_prefill_dbg & 2) && 8 % d->n_kv_heads == 0) ? 8 / d->n_kv_heads : 0;
+    const unsigned n_blocks = xpg ? 8u * (unsigned)((L->n_work[1] * group + xpg - 1) / xpg)
+                                  : (unsigned)L->n_work[1] * (unsigned)d->n_q_heads;
+    hipLaunchKernelGGL((prefill_dma_kernel<D, NS>), dim3(n_blocks), dim3(512), C::LDS_BYTES, s,
+                       (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V, kctx, vctx, (uint16_t*)O, LSE,
+                       L->d_segs, L->d_work[1], L->n_tokens, d->n_q_heads, group, n_rows_pad, scale,
+                       L->n_work[1], xpg);
+    VXL_HIP_TRY(hipGetLastError());
+    if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_stop, s));
+    return VXL_OK;
+}
+
 vxl_status launch_prefill_bf16(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Q,
                                const void* K, const void* V, void* O, float* LSE, void* ws, hipStream_t s) {
+    if (g_prefill_qb == 3)
+        return d->head_dim == 128 ? run_prefill_dma<128, 4>(L, d, scale, Q, K, V, O, LSE, ws, s)
+                                  : run_prefill_dma<64, 4>(L, d, scale, Q, K, V, O, LSE, ws, s);
     if (d->head_dim == 128)
         return g_prefill_qb == 2 ? run_prefill<128, 2>(L, d, scale, Q, K, V, O, LSE, ws, s)
                                  : run_prefill<128, 1>(L, d, scale, Q, K, V, O, LSE, ws, s);
