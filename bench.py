@@ -38,7 +38,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config1", choices=["config1", "config2", "config4"])
-    ap.add_argument("--rows-per-wave", type=int, default=0, help="debug: 1 or 2 32-row blocks per wave")
+    ap.add_argument("--prefill-variant", type=int, default=0,
+                    help="debug: 1 or 2 = the 4-wave register-staged kernel with 1 or 2 row blocks per wave")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the separate gather/decode measurements")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -93,8 +94,8 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     vxl.lib()
-    if args.rows_per_wave:
-        vxl.debug_prefill_rows_per_wave(args.rows_per_wave)
+    if args.prefill_variant:
+        vxl.debug_prefill_variant(args.prefill_variant)
 
     w = wl.WORKLOADS[args.workload]
     lay = wl.make_layout(w)
@@ -157,11 +158,12 @@ def main():
     achieved = eff_flops / (kernel_ms * 1e-3) / 1e12
     mixlen = int(mix_len.cpu()[0])
 
+    kernel_name = "prefill_mfma_kernel" if args.prefill_variant else "prefill_dma_kernel"
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.workload, {}).get("prefill_mfma_kernel")
+            traffic = json.load(open(tpath)).get(args.workload, {}).get(kernel_name)
         except Exception:
             traffic = None
 
@@ -175,7 +177,7 @@ def main():
                    "n_chunks": C, "q_heads": Hq, "kv_heads": Hkv, "head_dim": D, "decode_tokens": T,
                    "top_k": top_k, "mixed_kv_len": mixlen, "allowed_pairs": pairs,
                    "effective_flops": eff_flops},
-        "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel", "achieved": achieved,
+        "roofline": {"bound": "mfma", "kernel": kernel_name, "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "traffic": traffic, "kernel_ms": kernel_ms},
     }

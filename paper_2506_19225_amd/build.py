@@ -29,14 +29,46 @@ def _hipcc() -> str:
     return "hipcc"
 
 
+# Kernels that keep their own count of outstanding vector-memory operations (direct global-to-LDS
+# loads issued from inline assembly, waited for with hand-written vmcnt values): a register spill
+# would add scratch loads and stores to that count behind the kernel's back, so the build refuses
+# a compile in which one of them uses scratch memory.
+NO_SCRATCH = {"vxl_prefill.hip": ("prefill_dma_kernel",)}
+
+
+def _check_no_scratch(src: str, remarks: str) -> None:
+    name = None
+    for ln in remarks.splitlines():
+        if "remark: Function Name:" in ln:
+            name = ln.split("Function Name:")[1].split()[0]
+        elif "ScratchSize [bytes/lane]:" in ln and name and any(k in name for k in NO_SCRATCH[src]):
+            size = int(ln.split("ScratchSize [bytes/lane]:")[1].split()[0])
+            if size != 0:
+                raise RuntimeError(f"{src}: kernel {name} spills ({size} bytes of scratch per lane); "
+                                   "its hand-kept vmcnt bookkeeping needs a spill-free compile")
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    extra = ["-Rpass-analysis=kernel-resource-usage"] if src in NO_SCRATCH else []
+    cmd = [_hipcc(), *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(ln for ln in r.stderr.splitlines() if noise not in ln)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
+    if src in NO_SCRATCH:
+        _check_no_scratch(src, err)
+        keep, skip = [], 0                                   # drop the remarks (and their source echo)
+        for ln in err.splitlines():
+            if "[-Rpass-analysis=kernel-resource-usage]" in ln:
+                skip = 2
+            elif skip and (ln.lstrip().startswith("|") or "|" in ln[:8]):
+                skip -= 1
+            else:
+                skip = 0
+                keep.append(ln)
+        err = "\n".join(keep)
     if err.strip():
         sys.stderr.write(err + "\n")
     return obj

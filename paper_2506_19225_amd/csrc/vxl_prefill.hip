@@ -6,8 +6,11 @@
 //
 // Main kernel: one workgroup = one query-row tile of one query head of one segment (the prefix
 // or a chunk).  It walks 64-key tiles  history[0, ctx_len)  then  own segment[0, diagonal]  with
-// an online softmax; tiles are staged row-major in LDS (double buffered, next tile prefetched
-// into registers while the current one is consumed).  The arithmetic is in vxl_mfma.h.
+// an online softmax; the arithmetic is in vxl_mfma.h.  Two kernels do this:
+//   prefill_dma_kernel   (default)  256 rows and 8 waves per workgroup, tiles streamed into an LDS
+//                                   ring by direct global-to-LDS loads;
+//   prefill_mfma_kernel  (cross-check) 128 or 256 rows and 4 waves per workgroup, tiles staged
+//                                   through registers into a double buffer.
 #include <math.h>
 
 #include "vxl_internal.h"
@@ -254,8 +257,9 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
 // The loads are issued from inline assembly: the compiler cannot see them, so it neither orders
 // them against the LDS reads of other stages nor counts them in its own vmcnt bookkeeping; the
 // kernel does both by hand (every wave issues the same number of loads per tile, and waits with
-// vmcnt = loads still allowed in flight).  No compiler-visible global load is outstanding while
-// the ring runs: the query registers are forced complete before the first ring load.
+// vmcnt = loads still allowed in flight).  No compiler-visible vector memory operation may be
+// outstanding while the ring runs: the query registers are forced complete before the first ring
+// load, and the kernel must not spill (the build refuses a compile of it that uses scratch).
 // ------------------------------------------------------------------------------------------
 template <int D, int NS>
 struct PrefillDmaCfg {
@@ -428,7 +432,7 @@ vxl_status enable_big_lds(F kernel, int bytes) {
 
 }  // namespace
 
-static int g_prefill_qb = 1;
+static int g_prefill_variant = 0;
 static int g_prefill_dbg = 0;
 static unsigned long long* g_prof_buf = nullptr;
 extern "C" void vxl_debug_flags(int flags) { g_prefill_dbg = flags; }
@@ -436,7 +440,9 @@ extern "C" void vxl_debug_flags(int flags) { g_prefill_dbg = flags; }
 // vxl_chunk_prefill calls run the instrumented instance of the kernel (D = 128, one row block).
 extern "C" void vxl_debug_prefill_profile(void* buf) { g_prof_buf = (unsigned long long*)buf; }
 static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
-extern "C" void vxl_debug_prefill_rows_per_wave(int blocks) { g_prefill_qb = (blocks == 2 || blocks == 3) ? blocks : 1; }
+// Cross-check and measurement only: 0 = the streaming kernel (default); 1, 2 = the 4-wave
+// register-staged kernel with one or two 32-row blocks per wave.
+extern "C" void vxl_debug_prefill_variant(int v) { g_prefill_variant = (v == 1 || v == 2) ? v : 0; }
 // Measurement hook: when both events are set, every vxl_chunk_prefill records them on its stream
 // immediately before and after the main attention kernel (the pre-pass is outside the bracket).
 extern "C" void vxl_debug_prefill_events(void* start, void* stop) {
@@ -532,14 +538,14 @@ static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, f
 
 vxl_status launch_prefill_bf16(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Q,
                                const void* K, const void* V, void* O, float* LSE, void* ws, hipStream_t s) {
-    if (g_prefill_qb == 3)
+    if (g_prefill_variant == 0)
         return d->head_dim == 128 ? run_prefill_dma<128, 4>(L, d, scale, Q, K, V, O, LSE, ws, s)
                                   : run_prefill_dma<64, 4>(L, d, scale, Q, K, V, O, LSE, ws, s);
     if (d->head_dim == 128)
-        return g_prefill_qb == 2 ? run_prefill<128, 2>(L, d, scale, Q, K, V, O, LSE, ws, s)
-                                 : run_prefill<128, 1>(L, d, scale, Q, K, V, O, LSE, ws, s);
-    return g_prefill_qb == 2 ? run_prefill<64, 2>(L, d, scale, Q, K, V, O, LSE, ws, s)
-                             : run_prefill<64, 1>(L, d, scale, Q, K, V, O, LSE, ws, s);
+        return g_prefill_variant == 2 ? run_prefill<128, 2>(L, d, scale, Q, K, V, O, LSE, ws, s)
+                                      : run_prefill<128, 1>(L, d, scale, Q, K, V, O, LSE, ws, s);
+    return g_prefill_variant == 2 ? run_prefill<64, 2>(L, d, scale, Q, K, V, O, LSE, ws, s)
+                                  : run_prefill<64, 1>(L, d, scale, Q, K, V, O, LSE, ws, s);
 }
 
 }  // namespace vxl

@@ -70,7 +70,7 @@ def lib() -> C.CDLL:
     L.vxl_bilevel_decode.restype = C.c_int
     L.vxl_bilevel_decode.argtypes = [dp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     L.vxl_debug_force_simple.argtypes = [C.c_int]
-    L.vxl_debug_prefill_rows_per_wave.argtypes = [C.c_int]
+    L.vxl_debug_prefill_variant.argtypes = [C.c_int]
     L.vxl_debug_prefill_events.argtypes = [vp, vp]
     L.vxl_debug_flags.argtypes = [C.c_int]
     _lib = L
@@ -202,8 +202,10 @@ def debug_force_simple(on: bool) -> None:
     lib().vxl_debug_force_simple(int(bool(on)))
 
 
-def debug_prefill_rows_per_wave(blocks: int) -> None:
-    lib().vxl_debug_prefill_rows_per_wave(int(blocks))
+def debug_prefill_variant(variant: int) -> None:
+    """Cross-check and measurement only: 0 = the streaming kernel (default); 1, 2 = the 4-wave
+    register-staged kernel with one or two 32-row blocks per wave."""
+    lib().vxl_debug_prefill_variant(int(variant))
 
 
 def debug_prefill_events(start: Optional[torch.cuda.Event], stop: Optional[torch.cuda.Event]) -> None:
