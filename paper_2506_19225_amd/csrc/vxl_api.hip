@@ -46,6 +46,8 @@ PrefillWorkspace prefill_workspace(const vxl_layout* L, const vxl_attn_desc* d) 
     off += align_up((size_t)d->n_kv_heads * L->n_ctx_tiles * kKeyTile * d->head_dim * 2, 256);
     w.vctx = off;
     off += align_up((size_t)d->n_kv_heads * L->n_ctx_tiles * kKeyTile * d->head_dim * 2, 256);
+    w.queue = off;
+    off += 256;
     w.total = off;
     return w;
 }

@@ -73,6 +73,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct PrefillWorkspace {      // byte offsets into the caller's workspace (bf16 path)
     size_t kctx;               // [Hkv][n_ctx_tiles*64][D] compacted history keys
     size_t vctx;               // [Hkv][n_ctx_tiles*64][D] compacted history values
+    size_t queue;              // 8 int counters: next work index per queue of the persistent kernel
     size_t total;
 };
 PrefillWorkspace prefill_workspace(const vxl_layout* L, const vxl_attn_desc* d);

@@ -13,6 +13,8 @@
 //                                   through registers into a double buffer.
 #include <math.h>
 
+#include <algorithm>
+
 #include "vxl_internal.h"
 #include "vxl_mfma.h"
 
@@ -267,7 +269,7 @@ struct PrefillDmaCfg {
     static constexpr int BM = 32 * WAVES;
     static constexpr int TILE = kKeyTile * D;                 // elements of one unpadded K (or V) tile
     static constexpr int STAGE = 2 * TILE;                    // K tile then V tile
-    static constexpr int LDS_BYTES = NS * STAGE * 2;
+    static constexpr int LDS_BYTES = NS * STAGE * 2 + 16;     // the ring and the slot of the work index
     static constexpr int PPR = D / 8;                         // 16-byte pieces per row
     static constexpr int RPI = 64 / PPR;                      // rows per load instruction (1 KiB)
     static constexpr int NI = kKeyTile / RPI;                 // instructions per tile per matrix
@@ -286,31 +288,37 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t l
                  :: "s"(lds_off), "v"(off), "s"(base) : "memory");
 }
 
+// The kernel is persistent: the grid is one workgroup per compute unit, and every workgroup keeps
+// taking the next (work item, query head) pair of its queue from a counter in global memory until
+// the queue is empty.  The work list is sorted heaviest first, so this is greedy longest-first
+// scheduling without gaps between workgroups.  With xpg > 0 there is one queue per KV head group,
+// served by the xpg XCDs (blockIdx.x % 8, the order workgroups are dealt out in) whose L2 then
+// holds that group's K and V; otherwise a single queue.  The counters must be zero at launch.
 template <int D, int NS>
 __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     const uint16_t* __restrict__ Kctx, const uint16_t* __restrict__ Vctx, uint16_t* __restrict__ O,
     float* __restrict__ LSE, const Segment* __restrict__ segs, const WorkItem* __restrict__ work,
-    int n_tokens, int n_q_heads, int group, int ctx_rows_pad, float scale, int n_items, int xpg) {
+    int n_tokens, int n_q_heads, int group, int ctx_rows_pad, float scale, int n_items, int xpg,
+    int* __restrict__ queue) {
     using C = PrefillDmaCfg<D, NS>;
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
+    int* next_slot = (int*)(lds + NS * C::STAGE);
 
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    int item, h;
-    if (xpg > 0) {
-        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-        const int j = slot * xpg + xcd % xpg;
-        if (j >= n_items * group) return;
-        item = j / group;
-        h = (xcd / xpg) * group + j % group;
-    } else {
-        item = blockIdx.x / n_q_heads;
-        h = blockIdx.x % n_q_heads;
-    }
-    item = __builtin_amdgcn_readfirstlane(item);
-    h = __builtin_amdgcn_readfirstlane(h);
+    const int qid = xpg > 0 ? (int)(blockIdx.x & 7) / xpg : 0;            // this workgroup's queue
+    const int q_len_items = xpg > 0 ? n_items * group : n_items * n_q_heads;
+    const float c2 = scale * kLog2e;
+    const int r_in = lane / C::PPR, pp = lane % C::PPR;
+
+    if (tid == 0) next_slot[0] = atomicAdd(queue + qid, 1);
+    __syncthreads();
+    int j = __builtin_amdgcn_readfirstlane(next_slot[0]);
+  for (int par = 1; j < q_len_items; par ^= 1) {
+    const int item = xpg > 0 ? j / group : j / n_q_heads;
+    const int h = xpg > 0 ? qid * group + j % group : j % n_q_heads;
     const int g = h / group;
     const WorkItem wi = work[item];
     const Segment sg = segs[wi.seg];
@@ -320,25 +328,10 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     const int last_row = min(m0 + C::BM, sg.q_len) - 1;
     const int n_t = n_ctx_t + last_row / kKeyTile + 1;
 
-    bf16x8 qreg[1][D / 16];
-    {
-        const int row = sg.q_start + min(wrow0 + l32, sg.q_len - 1);
-        const uint4* src = (const uint4*)(Q + ((size_t)h * n_tokens + row) * D);
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) qreg[0][ks] = __builtin_bit_cast(bf16x8, src[ks * 2 + hi]);
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) {                 // loaded before the ring starts
-            typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-            asm volatile("" :: "v"(__builtin_bit_cast(u32x4, qreg[0][ks])));
-        }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-
     const char* kctx_g = (const char*)(Kctx + (size_t)g * ctx_rows_pad * D);
     const char* vctx_g = (const char*)(Vctx + (size_t)g * ctx_rows_pad * D);
     const char* kown = (const char*)(K + ((size_t)g * n_tokens + sg.q_start) * D);
     const char* vown = (const char*)(V + ((size_t)g * n_tokens + sg.q_start) * D);
-    const int r_in = lane / C::PPR, pp = lane % C::PPR;
 
     // Tile t -> stage t % NS.  Every wave issues GROUP loads: instruction slots wave, wave + 8, ...
     auto issue = [&](int t) {
@@ -365,13 +358,31 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) o[0][db] = zero16();
     float m_run = -INFINITY, l_run = 0.f;
-    const float c2 = scale * kLog2e;
 
 #pragma unroll
     // Prologue: NS-1 tiles ahead.  Tile indices beyond the last are clamped to it, so that every
     // wave always issues the same number of loads; a clamped issue rewrites the last tile's own
     // stage with the same bytes, which is harmless.
     for (int t = 0; t < NS - 1; ++t) issue(min(t, n_t - 1));
+
+    // The query rows are loaded after the ring has been started (both latencies then overlap) and
+    // forced complete here: the compiler's wait for them covers the older ring loads as well, and
+    // from here on no load it knows of is outstanding.
+    bf16x8 qreg[1][D / 16];
+    {
+        const int row = sg.q_start + min(wrow0 + l32, sg.q_len - 1);
+        const uint4* src = (const uint4*)(Q + ((size_t)h * n_tokens + row) * D);
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) qreg[0][ks] = __builtin_bit_cast(bf16x8, src[ks * 2 + hi]);
+        // the index of the item after this one is fetched in the same wait and read when this item is done
+        if (tid == 0) next_slot[par] = atomicAdd(queue + qid, 1);
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) {
+            typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+            asm volatile("" :: "v"(__builtin_bit_cast(u32x4, qreg[0][ks])));
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
 
     for (int ti = 0; ti < n_t; ++ti) {
         wait_vmcnt<C::GROUP * (NS - 2)>();                    // this wave's part of tile ti has landed
@@ -422,6 +433,15 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
             if (LSE && hi == 0) LSE[tok] = m_run * scale + logf(l_tot);
         }
     }
+    __syncthreads();                    // every wave is done with this item's tiles; next_slot[par] is written
+    j = __builtin_amdgcn_readfirstlane(next_slot[par]);
+  }
+}
+
+// Zeroes the queue counters of the persistent kernel (a kernel, not a memset: the call may be
+// captured into a graph).
+__global__ void reset_queue_kernel(int* queue) {
+    if (threadIdx.x < 8) queue[threadIdx.x] = 0;
 }
 
 template <typename F>
@@ -507,7 +527,10 @@ static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, f
     const PrefillWorkspace w = prefill_workspace(L, d);
     uint16_t* kctx = (uint16_t*)((char*)ws + w.kctx);
     uint16_t* vctx = (uint16_t*)((char*)ws + w.vctx);
+    int* queue = (int*)((char*)ws + w.queue);
     const int n_rows_pad = L->n_ctx_tiles * kKeyTile;
+    hipLaunchKernelGGL(reset_queue_kernel, dim3(1), dim3(64), 0, s, queue);
+    VXL_HIP_TRY(hipGetLastError());
     if (L->n_ctx_tiles > 0) {
         constexpr int rows = 256 / (D * 2 / 16);
         hipLaunchKernelGGL((compact_kv_kernel<D>), dim3((n_rows_pad + rows - 1) / rows, d->n_kv_heads),
@@ -521,16 +544,24 @@ static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, f
         if (st != VXL_OK) return st;
         attr_done = true;
     }
+    static int n_cus = 0;                                     // one persistent workgroup per compute unit
+    if (n_cus == 0) {
+        int dev = 0;
+        VXL_HIP_TRY(hipGetDevice(&dev));
+        VXL_HIP_TRY(hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
+        if (n_cus < 8) n_cus = 8;
+    }
     const bool timed = g_ev_start && g_ev_stop;
     if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_start, s));
     const int group = d->n_q_heads / d->n_kv_heads;
     const int xpg = (!(g_prefill_dbg & 2) && 8 % d->n_kv_heads == 0) ? 8 / d->n_kv_heads : 0;
-    const unsigned n_blocks = xpg ? 8u * (unsigned)((L->n_work[1] * group + xpg - 1) / xpg)
-                                  : (unsigned)L->n_work[1] * (unsigned)d->n_q_heads;
+    const long long n_pairs = (long long)L->n_work[1] * d->n_q_heads;
+    // no more workgroups than pairs (rounded up to whole rounds over the 8 XCDs when queues are per XCD group)
+    const unsigned n_blocks = (unsigned)std::min<long long>(n_cus / 8 * 8, xpg ? (n_pairs + 7) / 8 * 8 : n_pairs);
     hipLaunchKernelGGL((prefill_dma_kernel<D, NS>), dim3(n_blocks), dim3(512), C::LDS_BYTES, s,
                        (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V, kctx, vctx, (uint16_t*)O, LSE,
                        L->d_segs, L->d_work[1], L->n_tokens, d->n_q_heads, group, n_rows_pad, scale,
-                       L->n_work[1], xpg);
+                       L->n_work[1], xpg, queue);
     VXL_HIP_TRY(hipGetLastError());
     if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_stop, s));
     return VXL_OK;
