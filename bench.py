@@ -184,9 +184,40 @@ def main():
 
     if not args.no_extras:
         result["bilevel"] = measure_bilevel(torch, vxl, w, gl, desc, dk, dv, dqd, mask, l_cap, mixlen)
+        # the same calls at the shapes on which the bandwidth-bound claim is made: config1's mixed KV
+        # (8 MB) is a launch-latency case, these two move 49 MB and 1.08 GB per decode call
+        result["bilevel_large"] = {
+            "config2": bilevel_case(torch, vxl, wl, "config2", wl.WORKLOADS["config2"].k),
+            "config4_k_all": bilevel_case(torch, vxl, wl, "config4", 1 << 30),
+        }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, lay, q, k, v)
     print(json.dumps(result))
+
+
+def bilevel_case(torch, vxl, wl, name, top_k):
+    """Gather / decode measurements on the layout and shapes of another workload.  K, V and the
+    queries are seeded device-side normals (the values do not matter to these kernels); the dense
+    chunks are the first top_k ones."""
+    w = wl.WORKLOADS[name]
+    lay = wl.make_layout(w)
+    gl = vxl.Layout(lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx)
+    desc = vxl.make_desc(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
+    gen = torch.Generator(device="cuda").manual_seed(w.seed)
+    shape_kv = (w.n_kv_heads, lay.n_tokens, w.head_dim)
+    dk = (torch.randn(shape_kv, device="cuda", generator=gen) * 0.088).to(torch.bfloat16)
+    dv = (torch.randn(shape_kv, device="cuda", generator=gen) * 0.088).to(torch.bfloat16)
+    dqd = (torch.randn((w.B, w.T, w.n_q_heads, w.head_dim), device="cuda", generator=gen) * 0.088).to(torch.bfloat16)
+    kk = min(top_k, lay.n_chunks)
+    mask = torch.zeros((w.B, lay.n_chunks), dtype=torch.uint8, device="cuda")
+    mask[:, :kk] = 1
+    l_cap = gl.mixed_kv_capacity(kk)
+    mixlen = int(lay.n_prefix + sum(int(lay.chunk_bounds[c + 1] - lay.chunk_bounds[c]) if c < kk
+                                    else int(lay.sparse_offsets[c + 1] - lay.sparse_offsets[c])
+                                    for c in range(lay.n_chunks)))
+    res = measure_bilevel(torch, vxl, w, gl, desc, dk, dv, dqd, mask, l_cap, mixlen)
+    res.update({"batch": w.B, "decode_tokens": w.T, "mixed_kv_len": mixlen, "dense_chunks": kk})
+    return res
 
 
 def measure_bilevel(torch, vxl, w, gl, desc, dk, dv, dqd, mask, l_cap, mixlen):

@@ -33,7 +33,7 @@ def _hipcc() -> str:
 # loads issued from inline assembly, waited for with hand-written vmcnt values): a register spill
 # would add scratch loads and stores to that count behind the kernel's back, so the build refuses
 # a compile in which one of them uses scratch memory.
-NO_SCRATCH = {"vxl_prefill.hip": ("prefill_dma_kernel",)}
+NO_SCRATCH = {"vxl_prefill.hip": ("prefill_dma_kernel",), "vxl_decode.hip": ("decode_ring_kernel",)}
 
 
 def _check_no_scratch(src: str, remarks: str) -> None:

@@ -80,10 +80,12 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
         p.total = off;
         return p;
     }
-    // Split the keys until about two workgroups per compute unit exist, but keep the partial
-    // results (fp32 rows per split) below roughly twice the KV bytes they summarise.
+    // Split the keys until every compute unit has its workgroups (one of the 8-wave ring kernel,
+    // two of the 4-wave kernel), but keep the partial results (fp32 rows per split) below roughly
+    // twice the KV bytes they summarise.
     const long base_blocks = (long)batch * d->n_kv_heads * n_rtile;
-    long want = (512 + base_blocks - 1) / base_blocks;
+    const long target = rows > 128 ? 256 : 512;
+    long want = (target + base_blocks - 1) / base_blocks;
     const long cap = std::max<long>(1, 2L * l_cap / rows);
     want = std::max<long>(1, std::min<long>(std::min<long>(want, cap), tiles));
     const int tiles_per = (int)((tiles + want - 1) / want);

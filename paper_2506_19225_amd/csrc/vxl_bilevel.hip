@@ -92,23 +92,41 @@ __global__ __launch_bounds__(256) void score_topk_kernel(
     const int group = n_q_heads / n_kv_heads;
     const T* qb = Qd + (size_t)b * T_q * n_q_heads * D;
     // mean query of every kv head.  Step 1: every thread owns 16-byte columns of the [T, Hq*D]
-    // query matrix and sums them over the tokens (independent 16-byte loads, token order).
+    // query matrix, two at a time, and sums them over the tokens in token order; the loads of 16
+    // tokens of both columns are independent and in flight together.
     constexpr int EPC = 16 / (int)sizeof(T);                  // elements per 16-byte piece
     const int row_pieces = n_q_heads * D / EPC;
-    for (int p = tid; p < row_pieces; p += 256) {
-        float acc[EPC];
+    for (int p0 = tid; p0 < row_pieces; p0 += 512) {
+        const int p1 = p0 + 256 < row_pieces ? p0 + 256 : p0;      // second column (or the first again)
+        float acc0[EPC], acc1[EPC];
 #pragma unroll
-        for (int i = 0; i < EPC; ++i) acc[i] = 0.f;
-        const uint4* src = (const uint4*)qb + p;
-#pragma unroll 8
-        for (int t = 0; t < T_q; ++t) {
-            const uint4 v = src[(size_t)t * row_pieces];
-            const T* e = (const T*)&v;
+        for (int i = 0; i < EPC; ++i) acc0[i] = acc1[i] = 0.f;
+        for (int t0 = 0; t0 < T_q; t0 += 16) {
+            uint4 v0[16], v1[16];
 #pragma unroll
-            for (int i = 0; i < EPC; ++i) acc[i] += ld(e + i);
+            for (int u = 0; u < 16; ++u) {
+                const int t = t0 + u < T_q ? t0 + u : T_q - 1;     // clamped rows are not added below
+                v0[u] = ((const uint4*)qb)[(size_t)t * row_pieces + p0];
+                v1[u] = ((const uint4*)qb)[(size_t)t * row_pieces + p1];
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                if (t0 + u < T_q) {
+                    const T* e0 = (const T*)&v0[u];
+                    const T* e1 = (const T*)&v1[u];
+#pragma unroll
+                    for (int i = 0; i < EPC; ++i) {
+                        acc0[i] += ld(e0 + i);
+                        acc1[i] += ld(e1 + i);
+                    }
+                }
+            }
         }
 #pragma unroll
-        for (int i = 0; i < EPC; ++i) hsum[p * EPC + i] = acc[i];
+        for (int i = 0; i < EPC; ++i) {
+            hsum[p0 * EPC + i] = acc0[i];
+            if (p1 != p0) hsum[p1 * EPC + i] = acc1[i];
+        }
     }
     __syncthreads();
     // Step 2: add the heads of a group in head order.
@@ -119,30 +137,50 @@ __global__ __launch_bounds__(256) void score_topk_kernel(
         qbar[e] = a / (float)(T_q * group);
     }
     __syncthreads();
-    // one thread per chunk: dot over (g, d) in that order (independent 16-byte loads of kbar)
-    for (int c = tid; c < n_sort; c += 256) {
-        float a = -INFINITY;
-        if (c < n_chunks) {
-            float acc = 0.f;
-            for (int g = 0; g < n_kv_heads; ++g) {
-                const float4* kb = (const float4*)(kbar + ((size_t)g * n_chunks + c) * D);
-                const float* qg = qbar + g * D;
-                float pg = 0.f;
+    // Scores: 8 consecutive lanes share a chunk; lane `part` takes the part-th eighth of the
+    // flattened (kv head, d) index range, and the eight partial dot products are added in a fixed
+    // tree.  Every thread works on two chunks at a time so that their loads overlap.
+    {
+        const int part = tid & 7, cl = tid >> 3;              // 32 chunk slots per pass and half
+        const int slice = n_kv_heads * D / 8;                 // elements per part (a multiple of 4)
+        for (int base = 0; base < n_sort; base += 64) {
+            float pg[2] = {0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int c = base + u * 32 + cl;
+                if (c < n_chunks) {
+                    float a0 = 0.f;
 #pragma unroll 8
-                for (int x = 0; x < D / 4; ++x) {
-                    const float4 kv = kb[x];
-                    pg = fmaf(qg[4 * x + 0], kv.x, pg);
-                    pg = fmaf(qg[4 * x + 1], kv.y, pg);
-                    pg = fmaf(qg[4 * x + 2], kv.z, pg);
-                    pg = fmaf(qg[4 * x + 3], kv.w, pg);
+                    for (int x = 0; x < slice; x += 4) {
+                        const int e = part * slice + x, g = e / D, dd = e % D;
+                        const float4 kv = *(const float4*)(kbar + ((size_t)g * n_chunks + c) * D + dd);
+                        const float* qg = qbar + e;
+                        a0 = fmaf(qg[0], kv.x, a0);
+                        a0 = fmaf(qg[1], kv.y, a0);
+                        a0 = fmaf(qg[2], kv.z, a0);
+                        a0 = fmaf(qg[3], kv.w, a0);
+                    }
+                    pg[u] = a0;
                 }
-                acc += pg;
             }
-            a = acc * (scale / (float)n_kv_heads);
-            if (scores) scores[(size_t)b * n_chunks + c] = a;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                float a0 = pg[u];
+                a0 += __shfl_xor(a0, 1);
+                a0 += __shfl_xor(a0, 2);
+                a0 += __shfl_xor(a0, 4);
+                const int c = base + u * 32 + cl;
+                if (part == 0 && c < n_sort) {
+                    float a = -INFINITY;
+                    if (c < n_chunks) {
+                        a = a0 * (scale / (float)n_kv_heads);
+                        if (scores) scores[(size_t)b * n_chunks + c] = a;
+                    }
+                    s_val[c] = a;
+                    s_idx[c] = c < n_chunks ? c : 0x7fffffff;
+                }
+            }
         }
-        s_val[c] = a;
-        s_idx[c] = c < n_chunks ? c : 0x7fffffff;
     }
     __syncthreads();
     // bitonic sort, best first

@@ -140,6 +140,150 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void decode_split_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
+// Batched kernel for more than 128 stacked query rows: 256 rows and 8 waves per workgroup (one row
+// block of 32 per wave, two waves per SIMD), the split's 64-key tiles streamed into a ring of NS
+// LDS stages by direct global->LDS loads, NS-1 tiles ahead of the arithmetic -- the structure of
+// the streaming pre-filling kernel, without its causal part.  The loads are issued from inline
+// assembly and counted by hand (every wave issues the same number per tile and waits with
+// vmcnt = loads still allowed in flight), so the kernel must not spill, and the query registers
+// are forced complete before the first ring load.  Same partials as decode_split_kernel.
+// ------------------------------------------------------------------------------------------
+template <int D, int NS>
+struct DecodeRingCfg {
+    static constexpr int WAVES = 8;
+    static constexpr int RT = 32 * WAVES;                     // query rows per workgroup
+    static constexpr int TILE = kKeyTile * D;                 // elements of one unpadded K (or V) tile
+    static constexpr int STAGE = 2 * TILE;                    // K tile then V tile
+    static constexpr int LDS_BYTES = NS * STAGE * 2;
+    static constexpr int PPR = D / 8;                         // 16-byte pieces per row
+    static constexpr int RPI = 64 / PPR;                      // rows per load instruction (1 KiB)
+    static constexpr int NI = kKeyTile / RPI;                 // instructions per tile per matrix
+    static constexpr int IPW = NI / WAVES;                    // ... per wave
+    static constexpr int GROUP = 2 * IPW;                     // loads per wave per tile (K and V)
+};
+
+template <int D, int NS>
+__global__ __launch_bounds__(512, 2) void decode_ring_kernel(
+    const uint16_t* __restrict__ Qd, const uint16_t* __restrict__ Kmix, const uint16_t* __restrict__ Vmix,
+    const int32_t* __restrict__ mix_len, float* __restrict__ part_o, float* __restrict__ part_lse, int T_q,
+    int n_q_heads, int n_kv_heads, int group, int l_cap, int n_rtile, int split_len, float scale) {
+    using C = DecodeRingCfg<D, NS>;
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
+
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int split = blockIdx.x, n_split = gridDim.x;
+    const int g = blockIdx.y % n_kv_heads, rt = blockIdx.y / n_kv_heads;
+    const int b = blockIdx.z;
+    const int n_rows = group * T_q;
+    const int len = __builtin_amdgcn_readfirstlane(min(max(mix_len[b], 0), l_cap));
+    const int k_lo = split * split_len;
+    const int k_hi = min(k_lo + split_len, len);
+    const int wrow0 = rt * C::RT + wave * 32;
+    const size_t part_base = (((size_t)b * n_kv_heads + g) * n_split + split) * (size_t)n_rows;
+
+    if (k_lo >= k_hi) {                            // empty split: only its weight (zero) is recorded
+        for (int r = rt * C::RT + tid; r < min(n_rows, (rt + 1) * C::RT); r += 512)
+            part_lse[part_base + r] = -INFINITY;
+        return;
+    }
+    const int n_t = (k_hi - k_lo + kKeyTile - 1) / kKeyTile;
+    const char* kbase = (const char*)(Kmix + (((size_t)b * n_kv_heads + g) * (size_t)l_cap + k_lo) * D);
+    const char* vbase = (const char*)(Vmix + (((size_t)b * n_kv_heads + g) * (size_t)l_cap + k_lo) * D);
+    const int r_in = lane / C::PPR, pp = lane % C::PPR;
+
+    // Tile t -> stage t % NS.  Every wave issues GROUP loads: instruction slots wave, wave + 8, ...
+    // Rows past the end of the split are clamped to its last row (scores masked, V finite).
+    auto issue = [&](int t) {
+        const int row0 = t * kKeyTile;
+        const int rlim = min(kKeyTile - 1, k_hi - k_lo - 1 - row0);
+        const char* kb = kbase + (size_t)row0 * (D * 2);
+        const char* vb = vbase + (size_t)row0 * (D * 2);
+        const uint32_t st = lds_base + (uint32_t)(t % NS) * (C::STAGE * 2);
+#pragma unroll
+        for (int i = 0; i < C::IPW; ++i) {
+            const int slot = wave + i * C::WAVES;
+            const int row = slot * C::RPI + r_in;
+            const uint32_t roff = (uint32_t)min(row, rlim) * (D * 2);
+            const int kp = pp ^ ((row / (16 / C::PPR)) & (C::PPR - 1));
+            constexpr int CPR = D * 2 / 64, RPL = D == 128 ? 1 : 2;
+            const int vp = (((pp >> 2) ^ ((row / RPL) & (CPR - 1))) << 2) | (pp & 3);
+            dma16(kb, roff + kp * 16, st + slot * 1024);
+            dma16(vb, roff + vp * 16, st + C::TILE * 2 + slot * 1024);
+        }
+    };
+#pragma unroll
+    for (int t = 0; t < NS - 1; ++t) issue(min(t, n_t - 1));
+
+    // Query rows: loaded after the ring has been started (the latencies overlap) and forced
+    // complete here; from here on no load the compiler knows of is outstanding.
+    bf16x8 qreg[1][D / 16];
+    {
+        const int rho = min(wrow0 + l32, n_rows - 1);
+        const int t = rho / group, hg = rho % group;
+        const uint4* src = (const uint4*)(Qd + (((size_t)b * T_q + t) * n_q_heads + g * group + hg) * D);
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) qreg[0][ks] = __builtin_bit_cast(bf16x8, src[ks * 2 + hi]);
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) {
+            typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+            asm volatile("" :: "v"(__builtin_bit_cast(u32x4, qreg[0][ks])));
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    f32x16 o[1][D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) o[0][db] = zero16();
+    float m_run = -INFINITY, l_run = 0.f;
+    const float c2 = scale * kLog2e;
+    const bool wave_active = wrow0 < n_rows;       // waves without rows only help with the loads
+
+    for (int ti = 0; ti < n_t; ++ti) {
+        wait_vmcnt<C::GROUP * (NS - 2)>();                    // this wave's part of tile ti has landed
+        __builtin_amdgcn_s_barrier();                         // ... and everyone's; stage (ti-1)%NS is free
+        issue(min(ti + NS - 1, n_t - 1));
+        if (wave_active) {
+            const uint16_t* kt = lds + (ti % NS) * C::STAGE;
+            const int key0 = k_lo + ti * kKeyTile;
+            f32x16 s[1][2];
+            qk_tile<D, 1, D>(kt, qreg, l32, hi, s);
+            if (key0 + kKeyTile > k_hi) {
+                const int lim = k_hi - key0 - 1;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s[0][kb][r] = acc_key(kb, r, hi) <= lim ? s[0][kb][r] : -INFINITY;
+            }
+            bf16x8 pb[1][2][2];
+            softmax_tile<D / 32>(s[0], c2, m_run, l_run, o[0], pb[0]);
+            pv_tile<D, 1, D>(kt + C::TILE, pb, lane, o);
+        }
+    }
+    wait_vmcnt<0>();                                          // drain the refills before the wave ends
+
+    if (!wave_active) return;
+    const int rho = wrow0 + l32;
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (rho >= n_rows) return;
+    const float inv = 1.f / l_tot;
+    float* orow = part_o + (part_base + rho) * D;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+            float4 v;
+            v.x = o[0][db][rq * 4 + 0] * inv;
+            v.y = o[0][db][rq * 4 + 1] * inv;
+            v.z = o[0][db][rq * 4 + 2] * inv;
+            v.w = o[0][db][rq * 4 + 3] * inv;
+            *(float4*)(orow + db * 32 + rq * 8 + hi * 4) = v;
+        }
+    if (hi == 0) part_lse[part_base + rho] = m_run * c2 + __builtin_amdgcn_logf(l_tot);
+}
+
+// ------------------------------------------------------------------------------------------
 // Step-mode kernel for at most 32 stacked query rows (e.g. T = 1..4 at G = 7): the work is pure
 // streaming, so every WAVE owns its own 32-key tiles (tile = NW*(split*tpw + i) + wave) and its
 // own LDS tile pair, filled by direct global->LDS loads; there is no workgroup barrier in the
@@ -341,6 +485,35 @@ static vxl_status run_decode(const vxl_attn_desc* d, float scale, const void* Qd
 }
 
 template <int D>
+static vxl_status run_decode_ring(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
+                                  const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len, void* O,
+                                  float* LSE, void* ws, hipStream_t s) {
+    using C = DecodeRingCfg<D, 4>;
+    const DecodePlan p = decode_plan(d, batch, T, l_cap);
+    float* part_o = (float*)((char*)ws + p.part_o);
+    float* part_lse = (float*)((char*)ws + p.part_ml);
+    const int group = d->n_q_heads / d->n_kv_heads;
+    const int n_rows = group * T;
+    const int n_rtile = (n_rows + C::RT - 1) / C::RT;
+    static bool attr_done = false;
+    if (!attr_done) {
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_ring_kernel<D, 4>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((decode_ring_kernel<D, 4>), dim3(p.n_split, n_rtile * d->n_kv_heads, batch), dim3(512),
+                       C::LDS_BYTES, s, (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix,
+                       mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap, n_rtile,
+                       p.split_len, scale);
+    VXL_HIP_TRY(hipGetLastError());
+    const size_t merge_lds = (size_t)(((p.n_split + 3) & ~3) + 256 / (D / 4) * D) * sizeof(float);
+    hipLaunchKernelGGL((decode_merge_kernel<D>), dim3(n_rows, d->n_kv_heads, batch), dim3(256), merge_lds, s,
+                       part_o, part_lse, (uint16_t*)O, LSE, T, d->n_q_heads, d->n_kv_heads, group, p.n_split);
+    VXL_HIP_TRY(hipGetLastError());
+    return VXL_OK;
+}
+
+template <int D>
 static vxl_status run_decode_wave(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
                                   const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len, void* O,
                                   float* LSE, void* ws, hipStream_t s) {
@@ -378,9 +551,9 @@ vxl_status launch_decode_bf16(const vxl_attn_desc* d, float scale, const void* Q
                    : run_decode_wave<64>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s);
     const bool big = n_rows > 128;
     if (d->head_dim == 128)
-        return big ? run_decode<128, 2>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s)
+        return big ? run_decode_ring<128>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s)
                    : run_decode<128, 1>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s);
-    return big ? run_decode<64, 2>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s)
+    return big ? run_decode_ring<64>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s)
                : run_decode<64, 1>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s);
 }
 

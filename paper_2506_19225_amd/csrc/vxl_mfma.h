@@ -227,6 +227,20 @@ __device__ __forceinline__ void dma_tile_wave(const char* kb, const char* vb, ui
     }
 }
 
+// Pieces of a hand-kept ring of direct global -> LDS loads (kernels that count vmcnt themselves).
+// wait_vmcnt<N>: wait until at most N vector-memory operations of this wave are outstanding.
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
+}
+// 16 bytes per lane from (uniform base + per-lane offset) to LDS byte offset lds_off + 16*lane.
+// Issued from inline assembly so that the compiler neither counts it nor orders LDS reads of
+// other ring stages behind it.
+__device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t lds_off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_off), "v"(off), "s"(base) : "memory");
+}
+
 // O^T[qb][db] += V^T . P^T over the 64 keys of the tile.
 template <int D, int QB, int VROW, int KB = 2>
 __device__ __forceinline__ void pv_tile(const uint16_t* vt, const bf16x8 (&pb)[QB][KB][2], int lane,

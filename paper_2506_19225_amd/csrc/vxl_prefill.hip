@@ -277,17 +277,6 @@ struct PrefillDmaCfg {
     static constexpr int GROUP = 2 * IPW;                     // loads per wave per tile (K and V)
 };
 
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    static_assert(N >= 0 && N < 64, "vmcnt range");
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
-}
-
-// 16 bytes per lane from (uniform base + per-lane offset) to LDS offset lds_off + 16*lane.
-__device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t lds_off) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_off), "v"(off), "s"(base) : "memory");
-}
-
 // The kernel is persistent: the grid is one workgroup per compute unit, and every workgroup keeps
 // taking the next (work item, query head) pair of its queue from a counter in global memory until
 // the queue is empty.  The work list is sorted heaviest first, so this is greedy longest-first
