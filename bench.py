@@ -35,8 +35,8 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="config1", choices=["config1", "config2", "config4"])
     ap.add_argument("--prefill-variant", type=int, default=0,
                     help="debug: 1 or 2 = the 4-wave register-staged kernel with 1 or 2 row blocks per wave")

@@ -348,21 +348,24 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     for (int db = 0; db < D / 32; ++db) o[0][db] = zero16();
     float m_run = -INFINITY, l_run = 0.f;
 
+    // The ring runs AHEAD tiles in front of the arithmetic.  Tile indices beyond the last are
+    // clamped to it, so that every wave always issues the same number of loads; a clamped issue
+    // rewrites the last tile's own stage with the same bytes, which is harmless.
+    constexpr int AHEAD = NS - 1;
 #pragma unroll
-    // Prologue: NS-1 tiles ahead.  Tile indices beyond the last are clamped to it, so that every
-    // wave always issues the same number of loads; a clamped issue rewrites the last tile's own
-    // stage with the same bytes, which is harmless.
-    for (int t = 0; t < NS - 1; ++t) issue(min(t, n_t - 1));
+    for (int t = 0; t < AHEAD; ++t) issue(min(t, n_t - 1));
 
     // The query rows are loaded after the ring has been started (both latencies then overlap) and
     // forced complete here: the compiler's wait for them covers the older ring loads as well, and
     // from here on no load it knows of is outstanding.
     bf16x8 qreg[1][D / 16];
     {
-        const int row = sg.q_start + min(wrow0 + l32, sg.q_len - 1);
-        const uint4* src = (const uint4*)(Q + ((size_t)h * n_tokens + row) * D);
+        // uniform base + 32-bit lane offset: the address stays out of the vector registers
+        const char* qbase = (const char*)(Q + ((size_t)h * n_tokens + sg.q_start) * D);
+        const uint32_t qoff = (uint32_t)min(wrow0 + l32, sg.q_len - 1) * (D * 2) + hi * 16;
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) qreg[0][ks] = __builtin_bit_cast(bf16x8, src[ks * 2 + hi]);
+        for (int ks = 0; ks < D / 16; ++ks)
+            qreg[0][ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qbase + qoff + ks * 32));
         // the index of the item after this one is fetched in the same wait and read when this item is done
         if (tid == 0) next_slot[par] = atomicAdd(queue + qid, 1);
 #pragma unroll
@@ -374,14 +377,12 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     __builtin_amdgcn_sched_barrier(0);
 
     for (int ti = 0; ti < n_t; ++ti) {
-        wait_vmcnt<C::GROUP * (NS - 2)>();                    // this wave's part of tile ti has landed
+        wait_vmcnt<C::GROUP * (AHEAD - 1)>();                 // this wave's part of tile ti has landed
         __builtin_amdgcn_s_barrier();                         // ... and everyone's; stage (ti-1)%NS is free
-        {
-            issue(min(ti + NS - 1, n_t - 1));
-        }
+        issue(min(ti + AHEAD, n_t - 1));
         const bool is_ctx = ti < n_ctx_t;
         const int key0 = is_ctx ? ti * kKeyTile : (ti - n_ctx_t) * kKeyTile;
-        const bool skip = !is_ctx && key0 > wrow0 + 31;
+        const bool skip = !is_ctx && key0 > wrow0 + 31;       // the tile lies above this wave's rows
         if (!skip) {
             const uint16_t* kt = lds + (ti % NS) * C::STAGE;
             const uint16_t* vt = kt + C::TILE;
@@ -408,8 +409,9 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
         const float l_tot = l_run + __shfl_xor(l_run, 32);
         if (q_off < sg.q_len) {
             const float inv = 1.f / l_tot;
-            const size_t tok = (size_t)h * n_tokens + sg.q_start + q_off;
-            uint16_t* orow = O + tok * D;
+            // uniform bases + 32-bit lane offsets, as for the query loads
+            char* obase = (char*)(O + ((size_t)h * n_tokens + sg.q_start) * D);
+            const uint32_t ooff = (uint32_t)q_off * (D * 2) + hi * 8;
 #pragma unroll
             for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -417,9 +419,9 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
                     bf16x4 v;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = (__bf16)(o[0][db][rq * 4 + e] * inv);
-                    *(bf16x4*)(orow + db * 32 + rq * 8 + hi * 4) = v;
+                    *(bf16x4*)(obase + ooff + (db * 32 + rq * 8) * 2) = v;
                 }
-            if (LSE && hi == 0) LSE[tok] = m_run * scale + logf(l_tot);
+            if (LSE && hi == 0) (LSE + (size_t)h * n_tokens + sg.q_start)[q_off] = m_run * scale + logf(l_tot);
         }
     }
     __syncthreads();                    // every wave is done with this item's tiles; next_slot[par] is written
