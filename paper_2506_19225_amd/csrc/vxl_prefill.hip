@@ -26,13 +26,16 @@ __device__ __forceinline__ uint4 zero4() { return make_uint4(0u, 0u, 0u, 0u); }
 
 // ------------------------------------------------------------------------------------------
 // Pre-pass: Kctx[g, r, :] = K[g, tile_src[r], :], same for V (zero rows where tile_src is -1).
+// Its first workgroup also zeroes the work-queue counters of the persistent main kernel (when
+// `queue` is given), which saves that kernel's callers a launch of their own.
 // ------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void compact_kv_kernel(const uint4* __restrict__ K, const uint4* __restrict__ V,
                                                          const int32_t* __restrict__ tile_src,
                                                          uint4* __restrict__ Kctx, uint4* __restrict__ Vctx,
-                                                         int n_rows_pad, int n_tokens) {
+                                                         int n_rows_pad, int n_tokens, int* __restrict__ queue) {
     constexpr int LPR = D * 2 / 16, ROWS = 256 / LPR;
+    if (queue && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 8) queue[threadIdx.x] = 0;
     const int r = blockIdx.x * ROWS + threadIdx.x / LPR, part = threadIdx.x % LPR, g = blockIdx.y;
     if (r >= n_rows_pad) return;
     const int src = tile_src[r];
@@ -473,7 +476,7 @@ static vxl_status run_prefill(const vxl_layout* L, const vxl_attn_desc* d, float
         constexpr int rows = 256 / (D * 2 / 16);
         hipLaunchKernelGGL((compact_kv_kernel<D>), dim3((n_rows_pad + rows - 1) / rows, d->n_kv_heads),
                            dim3(256), 0, s, (const uint4*)K, (const uint4*)V, L->d_tile_src, (uint4*)kctx,
-                           (uint4*)vctx, n_rows_pad, L->n_tokens);
+                           (uint4*)vctx, n_rows_pad, L->n_tokens, (int*)nullptr);
         VXL_HIP_TRY(hipGetLastError());
     }
     static bool attr_done = false;
@@ -520,15 +523,15 @@ static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, f
     uint16_t* vctx = (uint16_t*)((char*)ws + w.vctx);
     int* queue = (int*)((char*)ws + w.queue);
     const int n_rows_pad = L->n_ctx_tiles * kKeyTile;
-    hipLaunchKernelGGL(reset_queue_kernel, dim3(1), dim3(64), 0, s, queue);
-    VXL_HIP_TRY(hipGetLastError());
     if (L->n_ctx_tiles > 0) {
         constexpr int rows = 256 / (D * 2 / 16);
         hipLaunchKernelGGL((compact_kv_kernel<D>), dim3((n_rows_pad + rows - 1) / rows, d->n_kv_heads),
                            dim3(256), 0, s, (const uint4*)K, (const uint4*)V, L->d_tile_src, (uint4*)kctx,
-                           (uint4*)vctx, n_rows_pad, L->n_tokens);
-        VXL_HIP_TRY(hipGetLastError());
+                           (uint4*)vctx, n_rows_pad, L->n_tokens, queue);
+    } else {
+        hipLaunchKernelGGL(reset_queue_kernel, dim3(1), dim3(64), 0, s, queue);
     }
+    VXL_HIP_TRY(hipGetLastError());
     static bool attr_done = false;
     if (!attr_done) {
         vxl_status st = enable_big_lds(prefill_dma_kernel<D, NS>, C::LDS_BYTES);
