@@ -135,3 +135,32 @@ def test_config3_layers(layer):
         _, k0, _ = wl.make_qkv(w, lay, layer=0, with_q=False)
         _, mask0 = oracle.select_topk(oracle.chunk_scores(wl.make_decode_queries(w, 0), k0, lay.chunk_bounds), w.k)
         chain_and_check(w, lay, gl, k, v, dk, dv, qd, w.k, mask_from=mask0)
+
+
+def test_maximum_chunk_count():
+    """The largest chunk count the library accepts (the LDS sort runs at its full 4096 slots, the
+    gather scan loops 16 times): thousands of chunks of 1..3 tokens, some without kept tokens;
+    pre-filling on the same layout (4097 small segments) checked on every row."""
+    rng = np.random.default_rng(91)
+    c_n = vxl.MAX_CHUNKS
+    lens = rng.integers(1, 4, size=c_n)
+    kept, s = [], 5
+    for ln in lens:
+        kept.append(np.array([s], dtype=np.int64) if ln >= 2 else np.zeros(0, np.int64))
+        s += int(ln)
+    lay = wl.layout_from_lists(5, [int(x) for x in lens], kept)
+    w = wl.tiny_workload("bf16", 4, 2, 64, T=2, B=2, k=100, seed=91, value_scale=0.5)
+    q, k, v = wl.make_qkv(w, lay)
+    gl = make_layout(lay)
+    desc = desc_of(w)
+    dq, dk, dv = (vxl.to_device(x, w.dtype) for x in (q, k, v))
+    out = torch.full_like(dq, float("nan"))
+    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_PREFILL, gl, desc))
+    vxl.chunk_prefill(gl, desc, dq, dk, dv, out, None, ws)
+    torch.cuda.synchronize()
+    rows = np.arange(lay.n_tokens)[::7]
+    want = oracle.prefill_blk(q, k, v, *lay_args(lay), rows=rows)
+    assert_close(vxl.to_host(out)[:, rows], want, "bf16", what="4096-chunk prefill")
+    qd = wl.make_decode_queries(w)
+    for top_k in (100, c_n):
+        chain_and_check(w, lay, gl, k, v, dk, dv, qd, top_k)

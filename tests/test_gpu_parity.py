@@ -274,7 +274,8 @@ def test_decode_config0_fp32_and_tiny_bf16():
     want, wlse = oracle.decode_lse(qd, wk, wv, wlen)
     assert_close(got, want, "f32", head_axis=2, what="config0 decode")
     assert np.abs(lse - wlse).max() < 1e-4
-    for t_q, bsz, d in ((1, 2, 128), (5, 3, 64), (40, 1, 128)):
+    # stacked rows 7 (wave kernel), 35 (split kernel), 280 and 210 (ring kernel, both head dims)
+    for t_q, bsz, d in ((1, 2, 128), (5, 3, 64), (40, 1, 128), (30, 2, 64)):
         w = wl.tiny_workload("bf16", 14, 2, d, T=t_q, B=bsz, k=2, seed=72 + t_q)
         lay = wl.random_layout(rng, 17, 9, 5, 120)
         _, k, v = wl.make_qkv(w, lay, with_q=False)
