@@ -12,6 +12,8 @@ with the allowed set A(i) of `sets.allowed_mask`.  Two forms that must agree:
   prefill_blk  per chunk, the explicit list of visible key ids (prefix, kept ids of earlier
                chunks, own chunk) and an explicit score block with the intra-chunk causal mask.
 
+`window` > 0 adds the dense look-back range of the sliding chunk window (see sets.allowed_mask).
+
 Inputs are float arrays in the caller's storage precision; all arithmetic is float64.
 """
 import numpy as np
@@ -28,7 +30,7 @@ def _softmax_rows(s):
 
 
 def prefill_def(q, k, v, n_prefix, chunk_bounds, sparse_idx, scale=None, rows=None,
-                row_block=512, return_lse=False, return_probs=False):
+                row_block=512, return_lse=False, return_probs=False, window=0):
     """O[Hq, len(rows), D] (float64) straight from the set definition.
 
     q [Hq, N, D]; k, v [Hkv, N, D]; rows = query token ids to evaluate (default all).
@@ -47,7 +49,7 @@ def prefill_def(q, k, v, n_prefix, chunk_bounds, sparse_idx, scale=None, rows=No
     v64 = np.asarray(v, dtype=np.float64)
     for r0 in range(0, len(rows), row_block):
         rr = rows[r0:r0 + row_block]
-        mask = allowed_mask(rr, n_prefix, chunk_bounds, sparse_idx)
+        mask = allowed_mask(rr, n_prefix, chunk_bounds, sparse_idx, window)
         for h in range(hq):
             g = h // grp
             s = scale * (np.asarray(q[h, rr], dtype=np.float64) @ k64[g].T)
@@ -66,7 +68,7 @@ def prefill_def(q, k, v, n_prefix, chunk_bounds, sparse_idx, scale=None, rows=No
 
 
 def prefill_blk(q, k, v, n_prefix, chunk_bounds, sparse_offsets, sparse_idx, scale=None,
-                rows=None, heads=None, return_lse=False):
+                rows=None, heads=None, return_lse=False, window=0):
     """Same result as prefill_def, organised chunk by chunk (usable at long sequence lengths).
 
     rows  = query token ids to evaluate (default all), any order; heads = query heads
@@ -87,7 +89,7 @@ def prefill_blk(q, k, v, n_prefix, chunk_bounds, sparse_offsets, sparse_idx, sca
         sel = np.nonzero(seg_of == c)[0]
         rr = rows[sel]
         lo, hi = (0, n_prefix) if c < 0 else (int(b[c]), int(b[c + 1]))
-        hist = allowed_keys(int(c), n_prefix, chunk_bounds, sparse_offsets, sparse_idx)
+        hist = allowed_keys(int(c), n_prefix, chunk_bounds, sparse_offsets, sparse_idx, window)
         own = np.arange(lo, hi, dtype=np.int64)
         keys = np.concatenate([hist, own])
         # history keys are all visible; own-chunk key j is visible to query i iff j <= i

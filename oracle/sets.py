@@ -7,7 +7,13 @@ in CSR form (sparse_offsets[C+1], sparse_idx[S_total]).
 import numpy as np
 
 
-def allowed_mask(rows, n_prefix, chunk_bounds, sparse_idx):
+def window_start(c, n_prefix, chunk_bounds, window):
+    """First token id of the dense look-back range of chunk c: the `window` tokens before the
+    chunk, never reaching into the prefix (which is visible anyway)."""
+    return max(int(n_prefix), int(chunk_bounds[c]) - int(window))
+
+
+def allowed_mask(rows, n_prefix, chunk_bounds, sparse_idx, window=0):
     """Boolean [len(rows), N]: entry (r, j) says whether query token rows[r] may attend to key j.
 
     Pre-filling figure caption + text: the chunk being processed attends to itself, to the
@@ -15,6 +21,11 @@ def allowed_mask(rows, n_prefix, chunk_bounds, sparse_idx):
     prefix) attention is causal.  As a set, for query i in chunk c:
         A(i) = [0, P)  u  (S_0 u ... u S_{c-1})  u  [b_c, i]
     and A(i) = [0, i] for a prefix token.
+
+    window > 0 (same paragraph: the chunk to process is placed by a sliding window with a step
+    size, so that it also sees the overlapping part of the preceding chunk in full detail):
+    chunk c additionally sees every token of [max(P, b_c - window), b_c), i.e.
+        A(i) = [0, P)  u  (S_0 u ... u S_{c-1})  u  [max(P, b_c - window), i].
     """
     b = np.asarray(chunk_bounds, dtype=np.int64)
     assert int(b[0]) == int(n_prefix)
@@ -30,28 +41,43 @@ def allowed_mask(rows, n_prefix, chunk_bounds, sparse_idx):
     same_segment = (cj == ci)
     in_prefix = (j < n_prefix)
     kept_earlier = kept[None, :] & (cj < ci)
-    return (j <= i) & (same_segment | in_prefix | kept_earlier)
+    # start of the dense look-back range of every query row (N = none, for prefix rows)
+    lo = np.array([window_start(c, n_prefix, b, window) if c >= 0 else n for c in chunk_of[rows]],
+                  dtype=np.int64)[:, None]
+    looked_back = (j >= lo) & (ci >= 0)
+    return (j <= i) & (same_segment | in_prefix | kept_earlier | looked_back)
 
 
-def allowed_keys(c, n_prefix, chunk_bounds, sparse_offsets, sparse_idx):
-    """Key ids visible to chunk c before its own tokens: prefix, then kept ids of chunks < c.
+def allowed_keys(c, n_prefix, chunk_bounds, sparse_offsets, sparse_idx, window=0):
+    """Key ids visible to every token of chunk c before its own tokens, ascending: the prefix,
+    the kept ids of chunks < c that lie before the look-back range, then the look-back range.
     c = -1 denotes the prefix itself (nothing precedes it)."""
     if c < 0:
         return np.zeros(0, dtype=np.int64)
+    lo = window_start(c, n_prefix, chunk_bounds, window)
     hist = np.asarray(sparse_idx, dtype=np.int64)[: int(sparse_offsets[c])]
-    return np.concatenate([np.arange(n_prefix, dtype=np.int64), hist])
+    hist = hist[hist < lo]
+    return np.concatenate([np.arange(n_prefix, dtype=np.int64), hist,
+                           np.arange(lo, int(chunk_bounds[c]), dtype=np.int64)])
 
 
-def allowed_pair_count(n_prefix, chunk_bounds, sparse_offsets):
+def allowed_pair_count(n_prefix, chunk_bounds, sparse_offsets, sparse_idx=None, window=0):
     """Number of (query, key) pairs the pre-filling mask allows, in closed form:
-    P(P+1)/2 + sum_c [ len_c (P + off_c) + len_c (len_c + 1) / 2 ]."""
+    P(P+1)/2 + sum_c [ len_c (P + off_c) + len_c (len_c + 1) / 2 ]  without a window; with one,
+    off_c counts only the kept ids before the look-back range and its length is added."""
     b = np.asarray(chunk_bounds, dtype=np.int64)
     off = np.asarray(sparse_offsets, dtype=np.int64)
     p = int(n_prefix)
     total = p * (p + 1) // 2
     for c in range(len(b) - 1):
         ln = int(b[c + 1] - b[c])
-        total += ln * (p + int(off[c])) + ln * (ln + 1) // 2
+        hist = int(off[c])
+        back = 0
+        if window > 0:
+            lo = window_start(c, p, b, window)
+            back = int(b[c]) - lo
+            hist = int(np.count_nonzero(np.asarray(sparse_idx, dtype=np.int64)[: int(off[c])] < lo))
+        total += ln * (p + hist + back) + ln * (ln + 1) // 2
     return total
 
 

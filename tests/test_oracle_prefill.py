@@ -252,3 +252,87 @@ def test_config0_def_and_blk_agree():
     a = oracle.prefill_def(q, k, v, lay.n_prefix, lay.chunk_bounds, lay.sparse_idx)
     b = oracle.prefill_blk(q, k, v, lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx)
     assert np.abs(a - b).max() < 1e-12
+
+
+# ------------------------------------------------------------------ sliding chunk window
+def test_window_mask_matches_hand_written_fixture():
+    want = np.loadtxt(os.path.join(GOLDEN, "prefill_mask_window_small.txt"), comments="#").astype(bool)
+    lay = small_layout()
+    got = oracle.allowed_mask(np.arange(lay.n_tokens), lay.n_prefix, lay.chunk_bounds, lay.sparse_idx, window=2)
+    assert np.array_equal(got, want)
+    assert got.sum() == 60 == oracle.allowed_pair_count(lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets,
+                                                        lay.sparse_idx, window=2)
+
+
+def test_window_mask_against_set_enumeration():
+    """The vectorised mask against plain Python sets built token by token from the definition."""
+    rng = np.random.default_rng(61)
+    for _ in range(25):
+        lay = wl.random_layout(rng, int(rng.integers(0, 5)), int(rng.integers(1, 6)), 1, 9)
+        window = int(rng.integers(0, 14))
+        b, p = [int(x) for x in lay.chunk_bounds], lay.n_prefix
+        kept_by_chunk = [set(int(t) for t in lay.sparse_idx[lay.sparse_offsets[c]:lay.sparse_offsets[c + 1]])
+                         for c in range(lay.n_chunks)]
+        want = np.zeros((lay.n_tokens, lay.n_tokens), dtype=bool)
+        for i in range(lay.n_tokens):
+            if i < p:
+                allowed = set(range(i + 1))
+            else:
+                c = max(cc for cc in range(lay.n_chunks) if b[cc] <= i)
+                allowed = set(range(p))
+                for cc in range(c):
+                    allowed |= kept_by_chunk[cc]
+                allowed |= set(range(max(p, b[c] - window), i + 1))
+            want[i, sorted(allowed)] = True
+        got = oracle.allowed_mask(np.arange(lay.n_tokens), p, lay.chunk_bounds, lay.sparse_idx, window=window)
+        assert np.array_equal(got, want)
+        assert got.sum() == oracle.allowed_pair_count(p, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx,
+                                                      window=window)
+        if window == 0:
+            assert np.array_equal(got, oracle.allowed_mask(np.arange(lay.n_tokens), p, lay.chunk_bounds,
+                                                           lay.sparse_idx))
+
+
+def test_window_covering_everything_is_dense_causal():
+    rng = np.random.default_rng(62)
+    lay = wl.random_layout(rng, 3, 5, 2, 9)
+    n = lay.n_tokens
+    q, k, v = rand_qkv(rng, 4, 2, n, 16)
+    want = sdpa_causal(q, k, v)
+    got = oracle.prefill_def(q, k, v, lay.n_prefix, lay.chunk_bounds, lay.sparse_idx, window=n)
+    blk = oracle.prefill_blk(q, k, v, lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx, window=n)
+    assert np.abs(got - want).max() < 1e-12
+    assert np.abs(blk - want).max() < 1e-12
+
+
+def test_window_without_history_is_banded_attention():
+    """No prefix, nothing kept: token i of chunk c sees exactly [b_c - window, i]; compared with
+    a row-by-row evaluation that shares nothing with the oracle's matrix code."""
+    rng = np.random.default_rng(63)
+    lens, window, d = [5, 7, 4, 6], 3, 8
+    lay = wl.layout_from_lists(0, lens, [np.zeros(0, np.int32)] * len(lens))
+    n = lay.n_tokens
+    q, k, v = rand_qkv(rng, 2, 1, n, d)
+    got = oracle.prefill_blk(q, k, v, 0, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx, window=window)
+    starts = np.cumsum([0] + lens)
+    for h in range(2):
+        for i in range(n):
+            c = int(np.searchsorted(starts, i, side="right") - 1)
+            lo = max(0, int(starts[c]) - window)
+            w_ = [math.exp(float(np.dot(q[h, i].astype(np.float64), k[0, j].astype(np.float64))) / math.sqrt(d))
+                  for j in range(lo, i + 1)]
+            o = sum(wj * v[0, j].astype(np.float64) for wj, j in zip(w_, range(lo, i + 1))) / sum(w_)
+            assert np.abs(got[h, i] - o).max() < 1e-12
+
+
+def test_window_def_and_blk_agree():
+    rng = np.random.default_rng(64)
+    for _ in range(6):
+        lay = wl.random_layout(rng, int(rng.integers(0, 4)), int(rng.integers(2, 6)), 2, 12)
+        window = int(rng.integers(1, 10))
+        q, k, v = rand_qkv(rng, 4, 2, lay.n_tokens, 8)
+        a, la = oracle.prefill_def(q, k, v, lay.n_prefix, lay.chunk_bounds, lay.sparse_idx, return_lse=True,
+                                   window=window)
+        b, lb = oracle.prefill_blk(q, k, v, lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx,
+                                   return_lse=True, window=window)
+        assert np.abs(a - b).max() < 1e-12 and np.abs(la - lb).max() < 1e-12
