@@ -87,6 +87,19 @@ typedef void* vxl_stream;               /* a hipStream_t */
 vxl_status vxl_layout_create(int32_t n_tokens, int32_t n_prefix, int32_t n_chunks,
                              const int32_t* chunk_bounds, const int32_t* sparse_offsets,
                              const int32_t* sparse_idx, vxl_stream stream, vxl_layout** out);
+/* The same with the sliding chunk window of "Chunk-based Pre-filling" (the chunk to process is
+ * placed by a window that advances by a step smaller than its size, so it overlaps the end of
+ * the preceding chunk and sees that part in full detail; the chunks of this interface are the
+ * window's steps): the `window` >= 0 tokens right before chunk c, clipped at the end of the
+ * prefix, are visible to every token of chunk c as dense rows, in addition to the prefix and
+ * the kept tokens of earlier chunks; a kept token inside that range is seen once.
+ * window == 0 is vxl_layout_create.  Only vxl_chunk_prefill reads the window; scoring, gather
+ * and decode depend on the bounds and the kept lists alone.
+ * Errors: as vxl_layout_create; VXL_ERR_INVALID_ARG for window < 0. */
+vxl_status vxl_layout_create_windowed(int32_t n_tokens, int32_t n_prefix, int32_t n_chunks,
+                                      const int32_t* chunk_bounds, const int32_t* sparse_offsets,
+                                      const int32_t* sparse_idx, int32_t window, vxl_stream stream,
+                                      vxl_layout** out);
 vxl_status vxl_layout_destroy(vxl_layout* layout);
 
 /* Bytes of workspace the given hot call needs (0 on invalid arguments).  batch, n_q_tokens

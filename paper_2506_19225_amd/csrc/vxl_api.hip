@@ -128,9 +128,17 @@ void vxl_debug_force_simple(int on) { g_force_simple = on; }
 vxl_status vxl_layout_create(int32_t n_tokens, int32_t n_prefix, int32_t n_chunks,
                              const int32_t* chunk_bounds, const int32_t* sparse_offsets,
                              const int32_t* sparse_idx, vxl_stream stream, vxl_layout** out) {
+    return vxl_layout_create_windowed(n_tokens, n_prefix, n_chunks, chunk_bounds, sparse_offsets, sparse_idx,
+                                      0, stream, out);
+}
+
+vxl_status vxl_layout_create_windowed(int32_t n_tokens, int32_t n_prefix, int32_t n_chunks,
+                                      const int32_t* chunk_bounds, const int32_t* sparse_offsets,
+                                      const int32_t* sparse_idx, int32_t window, vxl_stream stream,
+                                      vxl_layout** out) {
     if (!out) return VXL_ERR_INVALID_ARG;
     *out = nullptr;
-    if (n_tokens <= 0 || n_prefix < 0 || n_chunks < 0 || !chunk_bounds || !sparse_offsets)
+    if (n_tokens <= 0 || n_prefix < 0 || n_chunks < 0 || window < 0 || !chunk_bounds || !sparse_offsets)
         return VXL_ERR_INVALID_ARG;
     if (n_chunks > VXL_MAX_CHUNKS) return VXL_ERR_UNSUPPORTED;
     if (chunk_bounds[0] != n_prefix || chunk_bounds[n_chunks] != n_tokens || sparse_offsets[0] != 0)
@@ -154,6 +162,7 @@ vxl_status vxl_layout_create(int32_t n_tokens, int32_t n_prefix, int32_t n_chunk
     vxl_layout* L = new (std::nothrow) vxl_layout();
     if (!L) return VXL_ERR_INVALID_ARG;
     L->n_tokens = n_tokens; L->n_prefix = n_prefix; L->n_chunks = n_chunks; L->s_total = s_total;
+    L->window = window;
     L->bounds.assign(chunk_bounds, chunk_bounds + n_chunks + 1);
     L->soff.assign(sparse_offsets, sparse_offsets + n_chunks + 1);
     if (s_total) L->sidx.assign(sparse_idx, sparse_idx + s_total);
@@ -162,15 +171,21 @@ vxl_status vxl_layout_create(int32_t n_tokens, int32_t n_prefix, int32_t n_chunk
     int32_t tile_base = 0;
     int64_t pairs = (int64_t)n_prefix * (n_prefix + 1) / 2;
     if (n_prefix > 0) {
-        L->segs.push_back({0, n_prefix, 0, tile_base});
+        L->segs.push_back({0, n_prefix, 0, tile_base, 0});
         tile_base += (n_prefix + kKeyTile - 1) / kKeyTile;
     }
     for (int c = 0; c < n_chunks; ++c) {
         const int32_t len = chunk_bounds[c + 1] - chunk_bounds[c];
-        const int32_t ctx = n_prefix + sparse_offsets[c];
-        L->segs.push_back({chunk_bounds[c], len, ctx, tile_base});
+        // dense look-back range [lo, b_c); kept tokens inside it are seen through it, not twice
+        const int32_t back = (int32_t)std::min<int64_t>(window, chunk_bounds[c] - n_prefix);
+        const int32_t lo = chunk_bounds[c] - back;
+        const int32_t* kept_begin = L->sidx.data();
+        const int32_t* kept_end = kept_begin + sparse_offsets[c];
+        const int32_t n_kept_before = (int32_t)(std::lower_bound(kept_begin, kept_end, lo) - kept_begin);
+        const int32_t ctx = n_prefix + n_kept_before;
+        L->segs.push_back({chunk_bounds[c], len, ctx, tile_base, back});
         tile_base += (len + kKeyTile - 1) / kKeyTile;
-        pairs += (int64_t)len * ctx + (int64_t)len * (len + 1) / 2;
+        pairs += (int64_t)len * (ctx + back) + (int64_t)len * (len + 1) / 2;
     }
     L->pair_count = pairs;
     L->n_seg = (int32_t)L->segs.size();
@@ -196,7 +211,7 @@ vxl_status vxl_layout_create(int32_t n_tokens, int32_t n_prefix, int32_t n_chunk
             const int mt = (sg.q_len + bm - 1) / bm;
             for (int m = 0; m < mt; ++m) {
                 const int last = std::min(sg.q_len, (m + 1) * bm) - 1;
-                const int64_t cost = (sg.ctx_len + kKeyTile - 1) / kKeyTile + last / kKeyTile + 1;
+                const int64_t cost = (sg.ctx_len + kKeyTile - 1) / kKeyTile + (last + sg.back) / kKeyTile + 1;
                 items.push_back({cost, {s, m}});
             }
         }

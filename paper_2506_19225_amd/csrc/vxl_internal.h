@@ -14,12 +14,16 @@ constexpr int kKeyTile = 64;      // keys per K/V tile of the matrix-core kernel
 constexpr int kRowBlock = 32;     // query rows per MFMA block (one 32x32 tile side)
 
 // One pre-filling segment: the prefix (if any) or a chunk.  Queries of a segment attend to the
-// first ctx_len rows of the compacted history buffer and, causally, to their own segment.
+// first ctx_len rows of the compacted history buffer, to the `back` tokens right before the
+// segment (the sliding chunk window's dense look-back range; 0 without a window) and, causally,
+// to their own segment: row r of the segment sees the dense rows [q_start - back, q_start + r].
 struct Segment {
     int32_t q_start;    // first token id
     int32_t q_len;      // tokens in the segment
-    int32_t ctx_len;    // visible history rows: 0 for the prefix, P + sparse_offsets[c] for chunk c
+    int32_t ctx_len;    // visible history rows: 0 for the prefix; for chunk c, P + the number of
+                        // kept tokens of earlier chunks that lie before the look-back range
     int32_t tile_base;  // index of the segment's first own-V tile among the own tiles
+    int32_t back;       // dense look-back rows: min(window, b_c - P)
 };
 
 struct WorkItem {
@@ -30,7 +34,7 @@ struct WorkItem {
 }  // namespace vxl
 
 struct vxl_layout {
-    int32_t n_tokens = 0, n_prefix = 0, n_chunks = 0, s_total = 0;
+    int32_t n_tokens = 0, n_prefix = 0, n_chunks = 0, s_total = 0, window = 0;
     std::vector<int32_t> bounds, soff, sidx;          // host copies
     int device = 0;
 

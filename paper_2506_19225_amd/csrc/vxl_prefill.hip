@@ -99,7 +99,7 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
 
     const int n_ctx_t = (sg.ctx_len + kKeyTile - 1) / kKeyTile;
     const int last_row = min(m0 + C::BM, sg.q_len) - 1;
-    const int n_t = n_ctx_t + last_row / kKeyTile + 1;
+    const int n_t = n_ctx_t + (last_row + sg.back) / kKeyTile + 1;      // own keys start `back` rows early
 
     // ---- this wave's queries, in B-operand layout: lane (l32, hi) holds 8 consecutive d ----
     bf16x8 qreg[QB][D / 16];
@@ -126,8 +126,8 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
     // in the segment itself (rows clamped to the segment end: clamped rows are masked by causality).
     const uint16_t* kctx_g = Kctx + (size_t)g * ctx_rows_pad * D;
     const uint16_t* vctx_g = Vctx + (size_t)g * ctx_rows_pad * D;
-    const uint16_t* kown = K + ((size_t)g * n_tokens + sg.q_start) * D;
-    const uint16_t* vown = V + ((size_t)g * n_tokens + sg.q_start) * D;
+    const uint16_t* kown = K + ((size_t)g * n_tokens + sg.q_start - sg.back) * D;
+    const uint16_t* vown = V + ((size_t)g * n_tokens + sg.q_start - sg.back) * D;
     const int ld_r = tid / (D / 8), ld_part = tid % (D / 8);        // this thread's row / 16-byte piece
     constexpr int ROWS_PER_PASS = 256 / (D / 8);
     // Prefetch registers as named scalars (LD = 4 pairs for D = 128, 2 for D = 64): they must stay
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
         const bool ctx_ = t_ < n_ctx_t;                                                             \
         const int row0_ = ctx_ ? t_ * kKeyTile : (t_ - n_ctx_t) * kKeyTile;                         \
         /* rows of the tile beyond the segment end are clamped to its last row */                   \
-        const int rlim_ = ctx_ ? kKeyTile - 1 : min(kKeyTile - 1, sg.q_len - 1 - row0_);            \
+        const int rlim_ = ctx_ ? kKeyTile - 1 : min(kKeyTile - 1, sg.back + sg.q_len - 1 - row0_);  \
         const char* kb_ = (const char*)(ctx_ ? kctx_g : kown) + (size_t)row0_ * (D * 2);            \
         const char* vb_ = (const char*)(ctx_ ? vctx_g : vown) + (size_t)row0_ * (D * 2);            \
         VXL_FETCH1(0, kr0, vr0);                                                                    \
@@ -187,18 +187,18 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
         const bool is_ctx = ti < n_ctx_t;
         const int key0 = is_ctx ? ti * kKeyTile : (ti - n_ctx_t) * kKeyTile;   // tile start in its space
         // own tiles entirely above this wave's rows contribute nothing
-        const bool skip = !is_ctx && key0 > wrow0 + 32 * QB - 1;
+        const bool skip = !is_ctx && key0 > wrow0 + sg.back + 32 * QB - 1;
         if (!skip) {
             f32x16 s[QB][2];
             qk_tile<D, QB, C::KROW>(Ks + buf * C::K_ELEMS, qreg, l32, hi, s);
             if (PROF) { __builtin_amdgcn_sched_barrier(0); asm volatile("s_nop 0" :: "v"(s[0][0][15]), "v"(s[0][1][15])); t1 = tick(); }
             // ---- mask (ragged last history tile, causal own tiles) ----
-            const bool need_mask = is_ctx ? (key0 + kKeyTile > sg.ctx_len) : (key0 + kKeyTile - 1 > wrow0);
+            const bool need_mask = is_ctx ? (key0 + kKeyTile > sg.ctx_len) : (key0 + kKeyTile - 1 > wrow0 + sg.back);
             if (need_mask) {
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb) {
                     // tile-relative key kt is visible iff kt <= lim
-                    const int lim = is_ctx ? sg.ctx_len - key0 - 1 : wrow0 + qb * 32 + l32 - key0;
+                    const int lim = is_ctx ? sg.ctx_len - key0 - 1 : wrow0 + sg.back + qb * 32 + l32 - key0;
 #pragma unroll
                     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -318,18 +318,18 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     const int wrow0 = m0 + wave * 32;
     const int n_ctx_t = (sg.ctx_len + kKeyTile - 1) / kKeyTile;
     const int last_row = min(m0 + C::BM, sg.q_len) - 1;
-    const int n_t = n_ctx_t + last_row / kKeyTile + 1;
+    const int n_t = n_ctx_t + (last_row + sg.back) / kKeyTile + 1;      // own keys start `back` rows early
 
     const char* kctx_g = (const char*)(Kctx + (size_t)g * ctx_rows_pad * D);
     const char* vctx_g = (const char*)(Vctx + (size_t)g * ctx_rows_pad * D);
-    const char* kown = (const char*)(K + ((size_t)g * n_tokens + sg.q_start) * D);
-    const char* vown = (const char*)(V + ((size_t)g * n_tokens + sg.q_start) * D);
+    const char* kown = (const char*)(K + ((size_t)g * n_tokens + sg.q_start - sg.back) * D);
+    const char* vown = (const char*)(V + ((size_t)g * n_tokens + sg.q_start - sg.back) * D);
 
     // Tile t -> stage t % NS.  Every wave issues GROUP loads: instruction slots wave, wave + 8, ...
     auto issue = [&](int t) {
         const bool ctx = t < n_ctx_t;
         const int row0 = ctx ? t * kKeyTile : (t - n_ctx_t) * kKeyTile;
-        const int rlim = ctx ? kKeyTile - 1 : min(kKeyTile - 1, sg.q_len - 1 - row0);
+        const int rlim = ctx ? kKeyTile - 1 : min(kKeyTile - 1, sg.back + sg.q_len - 1 - row0);
         const char* kb = (ctx ? kctx_g : kown) + (size_t)row0 * (D * 2);
         const char* vb = (ctx ? vctx_g : vown) + (size_t)row0 * (D * 2);
         const uint32_t st = lds_base + (uint32_t)(t % NS) * (C::STAGE * 2);
@@ -385,15 +385,15 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
         issue(min(ti + AHEAD, n_t - 1));
         const bool is_ctx = ti < n_ctx_t;
         const int key0 = is_ctx ? ti * kKeyTile : (ti - n_ctx_t) * kKeyTile;
-        const bool skip = !is_ctx && key0 > wrow0 + 31;       // the tile lies above this wave's rows
+        const bool skip = !is_ctx && key0 > wrow0 + sg.back + 31;   // the tile lies above this wave's rows
         if (!skip) {
             const uint16_t* kt = lds + (ti % NS) * C::STAGE;
             const uint16_t* vt = kt + C::TILE;
             f32x16 s[1][2];
             qk_tile<D, 1, D>(kt, qreg, l32, hi, s);
-            const bool need_mask = is_ctx ? (key0 + kKeyTile > sg.ctx_len) : (key0 + kKeyTile - 1 > wrow0);
+            const bool need_mask = is_ctx ? (key0 + kKeyTile > sg.ctx_len) : (key0 + kKeyTile - 1 > wrow0 + sg.back);
             if (need_mask) {
-                const int lim = is_ctx ? sg.ctx_len - key0 - 1 : wrow0 + l32 - key0;
+                const int lim = is_ctx ? sg.ctx_len - key0 - 1 : wrow0 + sg.back + l32 - key0;
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll

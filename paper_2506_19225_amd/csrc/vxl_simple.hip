@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256) void prefill_simple_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ LSE, const int32_t* __restrict__ bounds, const int32_t* __restrict__ soff,
     const int32_t* __restrict__ sidx, int n_tokens, int n_prefix, int n_chunks, int group,
-    float scale) {
+    float scale, int window) {
     __shared__ float q_lds[4][D];
     const int wave = threadIdx.x >> 6;
     const int i = blockIdx.x * 4 + wave;
@@ -95,8 +95,15 @@ __global__ __launch_bounds__(256) void prefill_simple_kernel(
             const int mid = (lo + hi) >> 1;
             if (bounds[mid] <= i) lo = mid; else hi = mid;
         }
-        own_start = bounds[lo];
-        n_hist = n_prefix + soff[lo];
+        // dense range starts `window` tokens before the chunk (not inside the prefix); kept tokens
+        // of earlier chunks count as history only if they lie before that range
+        own_start = max(n_prefix, bounds[lo] - window);
+        int a = 0, b = soff[lo];            // first kept index (of the earlier chunks) >= own_start
+        while (a < b) {
+            const int mid = (a + b) >> 1;
+            if (sidx[mid] < own_start) a = mid + 1; else b = mid;
+        }
+        n_hist = n_prefix + a;
     }
     const int n_keys = n_hist + (i - own_start + 1);
     auto key = [=](int slot) -> size_t {
@@ -148,7 +155,7 @@ vxl_status launch_prefill_simple(const vxl_layout* L, const vxl_attn_desc* d, fl
 #define VXL_LAUNCH(T, D)                                                                          \
     hipLaunchKernelGGL((prefill_simple_kernel<T, D>), grid, block, 0, s, (const T*)Q, (const T*)K, \
                        (const T*)V, (T*)O, LSE, L->d_bounds, L->d_soff, L->d_sidx, L->n_tokens,   \
-                       L->n_prefix, L->n_chunks, group, scale)
+                       L->n_prefix, L->n_chunks, group, scale, L->window)
     if (d->dtype == VXL_F32) { if (d->head_dim == 64) VXL_LAUNCH(float, 64); else VXL_LAUNCH(float, 128); }
     else { if (d->head_dim == 64) VXL_LAUNCH(uint16_t, 64); else VXL_LAUNCH(uint16_t, 128); }
 #undef VXL_LAUNCH

@@ -53,6 +53,8 @@ def lib() -> C.CDLL:
     L.vxl_last_error.restype = C.c_char_p
     L.vxl_layout_create.restype = C.c_int
     L.vxl_layout_create.argtypes = [i32, i32, i32, vp, vp, vp, vp, C.POINTER(vp)]
+    L.vxl_layout_create_windowed.restype = C.c_int
+    L.vxl_layout_create_windowed.argtypes = [i32, i32, i32, vp, vp, vp, i32, vp, C.POINTER(vp)]
     L.vxl_layout_destroy.restype = C.c_int
     L.vxl_layout_destroy.argtypes = [vp]
     L.vxl_workspace_bytes.restype = sz
@@ -110,10 +112,10 @@ def torch_dtype(desc: AttnDesc):
 
 
 class Layout:
-    """Owns a vxl_layout handle (vxl_layout_create / vxl_layout_destroy)."""
+    """Owns a vxl_layout handle (vxl_layout_create[_windowed] / vxl_layout_destroy)."""
 
     def __init__(self, n_prefix: int, chunk_bounds, sparse_offsets, sparse_idx, stream=None,
-                 n_tokens: Optional[int] = None):
+                 n_tokens: Optional[int] = None, window: int = 0):
         self.bounds = np.ascontiguousarray(chunk_bounds, dtype=np.int32)
         self.soff = np.ascontiguousarray(sparse_offsets, dtype=np.int32)
         self.sidx = np.ascontiguousarray(sparse_idx, dtype=np.int32)
@@ -121,9 +123,16 @@ class Layout:
         self.n_chunks = len(self.bounds) - 1
         self.n_tokens = int(self.bounds[-1]) if n_tokens is None else int(n_tokens)
         handle = C.c_void_p()
-        st = lib().vxl_layout_create(
-            self.n_tokens, self.n_prefix, self.n_chunks, self.bounds.ctypes.data, self.soff.ctypes.data,
-            self.sidx.ctypes.data if self.sidx.size else None, _stream(stream), C.byref(handle))
+        self.window = int(window)
+        if self.window == 0:
+            st = lib().vxl_layout_create(
+                self.n_tokens, self.n_prefix, self.n_chunks, self.bounds.ctypes.data, self.soff.ctypes.data,
+                self.sidx.ctypes.data if self.sidx.size else None, _stream(stream), C.byref(handle))
+        else:
+            st = lib().vxl_layout_create_windowed(
+                self.n_tokens, self.n_prefix, self.n_chunks, self.bounds.ctypes.data, self.soff.ctypes.data,
+                self.sidx.ctypes.data if self.sidx.size else None, self.window, _stream(stream),
+                C.byref(handle))
         _check(st, "vxl_layout_create")
         self.handle = handle
 

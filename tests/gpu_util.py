@@ -28,8 +28,8 @@ def assert_close(got, want, dtype, head_axis=0, what=""):
     assert rel.max() <= TOL_BF16_REL, f"{what}: rel Frobenius err {rel.max():.3e} (per head {rel})"
 
 
-def make_layout(lay: wl.Layout) -> vxl.Layout:
-    return vxl.Layout(lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx)
+def make_layout(lay: wl.Layout, window: int = 0) -> vxl.Layout:
+    return vxl.Layout(lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx, window=window)
 
 
 def desc_of(w: wl.Workload, scale: float = 0.0):

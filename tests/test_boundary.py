@@ -65,6 +65,16 @@ def test_layout_create_rejects_null_and_oversized():
     assert st == vxl.VXL_ERR_UNSUPPORTED
 
 
+def test_windowed_layout_rejects_negative_window():
+    b = np.asarray([2, 6, 10], np.int32)
+    o = np.asarray([0, 1, 2], np.int32)
+    i = np.asarray([2, 6], np.int32)
+    h = C.c_void_p()
+    st = vxl.lib().vxl_layout_create_windowed(10, 2, 2, b.ctypes.data, o.ctypes.data, i.ctypes.data, -1, None,
+                                              C.byref(h))
+    assert st == vxl.VXL_ERR_INVALID_ARG and not h.value
+
+
 def test_hot_calls_reject_bad_descriptors_before_launch():
     lib = vxl.lib()
     fake = C.c_void_p(0x1000)          # never dereferenced: validation fails first

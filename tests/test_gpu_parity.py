@@ -172,6 +172,58 @@ def test_prefill_locality_and_determinism_bit_exact():
     assert not changed[:170].any() and not changed[280:].any()
 
 
+# --------------------------------------------------------------------------------- sliding chunk window
+WINDOW_CASES = [
+    # (dtype, Hq, Hkv, D, P, n_chunks, len_lo, len_hi, window, seed)
+    ("f32", 2, 1, 64, 3, 4, 5, 60, 7, 110),
+    ("bf16", 4, 2, 128, 0, 4, 20, 90, 33, 111),
+    ("bf16", 6, 2, 64, 9, 5, 30, 150, 64, 112),
+    ("bf16", 4, 1, 128, 70, 4, 100, 300, 130, 113),        # look-back longer than two key tiles
+    ("bf16", 2, 2, 128, 5, 6, 40, 200, 100000, 114),       # window covers everything: dense causal
+]
+
+
+@pytest.mark.parametrize("case", WINDOW_CASES, ids=lambda c: f"{c[0]}-d{c[3]}-p{c[4]}-w{c[8]}")
+@pytest.mark.parametrize("qb", [0, 1, 2])
+def test_prefill_sliding_window(case, qb):
+    dtype, hq, hkv, d, p, nc, lo, hi, window, seed = case
+    if dtype == "f32" and qb != 0:
+        pytest.skip("kernel variants only exist for the matrix-core path")
+    rng = np.random.default_rng(seed)
+    lay = wl.random_layout(rng, p, nc, lo, hi)
+    w = wl.tiny_workload(dtype, hq, hkv, d, T=1, B=1, k=1, seed=seed)
+    q, k, v = wl.make_qkv(w, lay)
+    gl = make_layout(lay, window=window)
+    assert gl.pair_count() == oracle.allowed_pair_count(lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets,
+                                                        lay.sparse_idx, window=window)
+    vxl.debug_prefill_variant(qb)
+    try:
+        got, lse = gpu_prefill(w, lay, q, k, v, want_lse=True, gl=gl)
+    finally:
+        vxl.debug_prefill_variant(0)
+    want, wlse = oracle_prefill(q, k, v, lay, return_lse=True, window=window)
+    assert_close(got, want, dtype, what=f"windowed prefill {case}")
+    assert np.abs(lse - wlse).max() < (1e-4 if dtype == "f32" else 2e-2)
+    if dtype == "bf16" and qb == 0:                       # the vector kernel walks the same sets on its own
+        vxl.debug_force_simple(True)
+        try:
+            alt = gpu_prefill(w, lay, q, k, v, gl=gl)
+        finally:
+            vxl.debug_force_simple(False)
+        assert_close(alt, want, dtype, what=f"windowed prefill, vector kernel {case}")
+
+
+def test_prefill_window_config1_sampled_rows():
+    """config1 with a look-back of one frame group (64 tokens): full size, sampled rows."""
+    w = wl.WORKLOADS["config1"]
+    lay = wl.make_layout(w)
+    q, k, v = wl.make_qkv(w, lay)
+    got = gpu_prefill(w, lay, q, k, v, gl=make_layout(lay, window=64))
+    rows = sample_rows(lay, np.random.default_rng(0))
+    want = oracle_prefill(q, k, v, lay, rows=rows, window=64)
+    assert_close(got[:, rows], want, "bf16", what="config1 windowed prefill")
+
+
 # --------------------------------------------------------------------------------- score / top-k
 def check_topk(w, lay, qd, k, top_k):
     idx, mask, scores = gpu_score_topk(w, lay, qd, k, top_k)
