@@ -399,3 +399,70 @@ def test_all_dense_decode_equals_prefill_free_full_attention():
     full_v = np.broadcast_to(v[None], (2,) + v.shape)
     want = oracle.decode_mixed(qd, full_k, full_v, [lay.n_tokens] * 2)
     assert_close(got, want, "bf16", head_axis=2, what="all-dense decode")
+
+
+# --------------------------------------------------------------------------------- streams and graphs
+def _whole_path(w, lay, gl, desc, dq, dk, dv, dqd, bufs):
+    out, idx, mask, kmix, vmix, mix_len, od, ws = bufs
+    vxl.chunk_prefill(gl, desc, dq, dk, dv, out, None, ws[0])
+    vxl.chunk_score_topk(gl, desc, dqd, dk, w.k, idx, mask, workspace=ws[1])
+    vxl.gather_bilevel_kv(gl, desc, dk, dv, mask, kmix, vmix, mix_len, None, ws[2])
+    vxl.bilevel_decode(desc, dqd, kmix, vmix, mix_len, od, None, ws[3])
+
+
+def test_whole_path_on_a_side_stream_and_in_a_replayed_graph():
+    """The four calls never allocate or synchronise, so they run on any stream and can be captured
+    into a HIP graph.  Every replay (with eager work and synchronisations in between, and with
+    the persistent kernel's work queue reset inside the graph) must reproduce the eager result
+    bit for bit."""
+    w = wl.tiny_workload("bf16", 14, 2, 128, T=8, B=2, k=2, seed=95, value_scale=0.4)
+    rng = np.random.default_rng(95)
+    lay = wl.random_layout(rng, 40, 7, 60, 400)
+    q, k, v = wl.make_qkv(w, lay)
+    qd = wl.make_decode_queries(w)
+    gl = make_layout(lay)
+    desc = desc_of(w)
+    dq, dk, dv, dqd = (vxl.to_device(x, w.dtype) for x in (q, k, v, qd))
+    l_cap = gl.mixed_kv_capacity(w.k)
+
+    def buffers():
+        return (torch.full_like(dq, float("nan")),
+                torch.zeros((w.B, w.k), dtype=torch.int32, device="cuda"),
+                torch.zeros((w.B, lay.n_chunks), dtype=torch.uint8, device="cuda"),
+                torch.zeros((w.B, w.n_kv_heads, l_cap, w.head_dim), dtype=dk.dtype, device="cuda"),
+                torch.zeros((w.B, w.n_kv_heads, l_cap, w.head_dim), dtype=dk.dtype, device="cuda"),
+                torch.zeros((w.B,), dtype=torch.int32, device="cuda"),
+                torch.full_like(dqd, float("nan")),
+                [vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_PREFILL, gl, desc)),
+                 vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_SCORE_TOPK, gl, desc, w.B, w.T)),
+                 vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_GATHER, gl, desc, w.B)),
+                 vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_DECODE, None, desc, w.B, w.T, l_cap))])
+
+    eager = buffers()
+    _whole_path(w, lay, gl, desc, dq, dk, dv, dqd, eager)
+    torch.cuda.synchronize()
+    want = oracle_prefill(q, k, v, lay)
+    assert_close(vxl.to_host(eager[0]), want, "bf16", what="eager prefill")
+
+    side = torch.cuda.Stream()
+    on_side = buffers()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        _whole_path(w, lay, gl, desc, dq, dk, dv, dqd, on_side)
+    side.synchronize()
+    for a, b in zip(eager[:7], on_side[:7]):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+    captured = buffers()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        _whole_path(w, lay, gl, desc, dq, dk, dv, dqd, captured)
+    for rep in range(3):
+        for t in (captured[0], captured[6]):
+            t.fill_(float("nan"))                          # eager work between the replays
+        captured[4].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(eager[:7], captured[:7]):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), f"replay {rep} differs"
