@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void decode_split_kernel(
 // ------------------------------------------------------------------------------------------
 // Batched kernel for more than 128 stacked query rows: 256 rows and 8 waves per workgroup (one row
 // block of 32 per wave, two waves per SIMD), the split's 64-key tiles streamed into a ring of NS
-// LDS stages by direct global->LDS loads, NS-1 tiles ahead of the arithmetic -- the structure of
+// LDS stages by direct global->LDS loads, two tiles ahead of the arithmetic -- the structure of
 // the streaming pre-filling kernel, without its causal part.  The loads are issued from inline
 // assembly and counted by hand (every wave issues the same number per tile and waits with
 // vmcnt = loads still allowed in flight), so the kernel must not spill, and the query registers
@@ -213,8 +213,12 @@ __global__ __launch_bounds__(512, 2) void decode_ring_kernel(
             dma16(vb, roff + vp * 16, st + C::TILE * 2 + slot * 1024);
         }
     };
+    // Two groups of TPB stages: one is consumed while the other is refilled, one workgroup barrier
+    // per TPB tiles.
+    constexpr int TPB = 2;
+    static_assert(NS == 2 * TPB, "two groups of TPB stages");
 #pragma unroll
-    for (int t = 0; t < NS - 1; ++t) issue(min(t, n_t - 1));
+    for (int t = 0; t < TPB; ++t) issue(min(t, n_t - 1));
 
     // Query rows: loaded after the ring has been started (the latencies overlap) and forced
     // complete here; from here on no load the compiler knows of is outstanding.
@@ -240,26 +244,30 @@ __global__ __launch_bounds__(512, 2) void decode_ring_kernel(
     const float c2 = scale * kLog2e;
     const bool wave_active = wrow0 < n_rows;       // waves without rows only help with the loads
 
-    for (int ti = 0; ti < n_t; ++ti) {
-        wait_vmcnt<C::GROUP * (NS - 2)>();                    // this wave's part of tile ti has landed
-        __builtin_amdgcn_s_barrier();                         // ... and everyone's; stage (ti-1)%NS is free
-        issue(min(ti + NS - 1, n_t - 1));
-        if (wave_active) {
-            const uint16_t* kt = lds + (ti % NS) * C::STAGE;
-            const int key0 = k_lo + ti * kKeyTile;
-            f32x16 s[1][2];
-            qk_tile<D, 1, D>(kt, qreg, l32, hi, s);
-            if (key0 + kKeyTile > k_hi) {
-                const int lim = k_hi - key0 - 1;
+    auto process = [&](int ti) {
+        if (!wave_active) return;
+        const uint16_t* kt = lds + (ti % NS) * C::STAGE;
+        const int key0 = k_lo + ti * kKeyTile;
+        f32x16 s[1][2];
+        qk_tile<D, 1, D>(kt, qreg, l32, hi, s);
+        if (key0 + kKeyTile > k_hi) {
+            const int lim = k_hi - key0 - 1;
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) s[0][kb][r] = acc_key(kb, r, hi) <= lim ? s[0][kb][r] : -INFINITY;
-            }
-            bf16x8 pb[1][2][2];
-            softmax_tile<D / 32>(s[0], c2, m_run, l_run, o[0], pb[0]);
-            pv_tile<D, 1, D>(kt + C::TILE, pb, lane, o);
+                for (int r = 0; r < 16; ++r) s[0][kb][r] = acc_key(kb, r, hi) <= lim ? s[0][kb][r] : -INFINITY;
         }
+        bf16x8 pb[1][2][2];
+        softmax_tile<D / 32>(s[0], c2, m_run, l_run, o[0], pb[0]);
+        pv_tile<D, 1, D>(kt + C::TILE, pb, lane, o);
+    };
+    for (int t0 = 0; t0 < n_t; t0 += TPB) {
+        wait_vmcnt<0>();                                      // this wave's parts of tiles t0, t0+1 have landed
+        __builtin_amdgcn_s_barrier();                         // ... and everyone's; the other group is free
+        issue(min(t0 + TPB, n_t - 1));
+        process(t0);
+        issue(min(t0 + TPB + 1, n_t - 1));
+        if (t0 + 1 < n_t) process(t0 + 1);
     }
     wait_vmcnt<0>();                                          // drain the refills before the wave ends
 

@@ -255,7 +255,7 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
 // ------------------------------------------------------------------------------------------
 // Main kernel, streaming variant: 8 waves = 256 query rows per workgroup (one workgroup per
 // compute unit, two waves per SIMD), K/V tiles brought in by direct global->LDS loads into a ring
-// of NS stages, NS-1 tiles ahead of the arithmetic.  Against the 4-wave kernel this halves the
+// of NS stages, two tiles ahead of the arithmetic.  Against the 4-wave kernel this halves the
 // tile traffic, the barriers and the LDS fills per FLOP, takes the staging out of the VALU/VGPR
 // budget, and hides the memory latency behind several tiles of arithmetic.
 //
@@ -351,12 +351,16 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     for (int db = 0; db < D / 32; ++db) o[0][db] = zero16();
     float m_run = -INFINITY, l_run = 0.f;
 
-    // The ring runs AHEAD tiles in front of the arithmetic.  Tile indices beyond the last are
-    // clamped to it, so that every wave always issues the same number of loads; a clamped issue
-    // rewrites the last tile's own stage with the same bytes, which is harmless.
-    constexpr int AHEAD = NS - 1;
+    // The ring is used as two groups of TPB stages: while the tiles of one group are consumed the
+    // other group is refilled, and the workgroup meets at ONE barrier per TPB tiles (fewer
+    // meetings let the waves drift apart, which is what overlaps one wave's vector work with
+    // another's matrix work).  Tile indices beyond the last are clamped to it, so that every wave
+    // always issues the same number of loads; a clamped issue rewrites the last tile's own stage
+    // with the same bytes, which is harmless.
+    constexpr int TPB = 2;                                    // tiles per workgroup barrier
+    static_assert(NS == 2 * TPB, "two groups of TPB stages");
 #pragma unroll
-    for (int t = 0; t < AHEAD; ++t) issue(min(t, n_t - 1));
+    for (int t = 0; t < TPB; ++t) issue(min(t, n_t - 1));
 
     // The query rows are loaded after the ring has been started (both latencies then overlap) and
     // forced complete here: the compiler's wait for them covers the older ring loads as well, and
@@ -379,10 +383,7 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     }
     __builtin_amdgcn_sched_barrier(0);
 
-    for (int ti = 0; ti < n_t; ++ti) {
-        wait_vmcnt<C::GROUP * (AHEAD - 1)>();                 // this wave's part of tile ti has landed
-        __builtin_amdgcn_s_barrier();                         // ... and everyone's; stage (ti-1)%NS is free
-        issue(min(ti + AHEAD, n_t - 1));
+    auto process = [&](int ti) {
         const bool is_ctx = ti < n_ctx_t;
         const int key0 = is_ctx ? ti * kKeyTile : (ti - n_ctx_t) * kKeyTile;
         const bool skip = !is_ctx && key0 > wrow0 + sg.back + 31;   // the tile lies above this wave's rows
@@ -404,6 +405,14 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
             softmax_tile<D / 32>(s[0], c2, m_run, l_run, o[0], pb[0]);
             pv_tile<D, 1, D>(vt, pb, lane, o);
         }
+    };
+    for (int t0 = 0; t0 < n_t; t0 += TPB) {
+        wait_vmcnt<0>();                                      // this wave's parts of tiles t0, t0+1 have landed
+        __builtin_amdgcn_s_barrier();                         // ... and everyone's; the other group is free
+        issue(min(t0 + TPB, n_t - 1));
+        process(t0);
+        issue(min(t0 + TPB + 1, n_t - 1));                    // the second refill between the two tiles
+        if (t0 + 1 < n_t) process(t0 + 1);
     }
     wait_vmcnt<0>();                                          // drain the refills before the wave ends
 
