@@ -34,6 +34,39 @@ def chunk_scores(qd, k, chunk_bounds, scale=None):
     return scale * np.einsum("bgd,gcd->bc", qbar, kbar) / hkv
 
 
+def chunk_scores_mass(qd, k, n_prefix, chunk_bounds, scale=None, row_block=64):
+    """score[B, C] float64: the second reading of the attention-score relevance oracle -- the
+    softmax attention MASS a query token puts on the dense keys of a chunk, averaged over the
+    query tokens and query heads:
+
+        p[b,t,h,j] = softmax over ALL tokens j (prefix and every chunk) of scale * Qd[b,t,h].K[g(h),j]
+        score[b,c] = mean over (t, h) of  sum_{j in chunk c} p[b,t,h,j]
+
+    The prefix takes part in the softmax but is not scored, so the scores of a query sum to
+    1 - (mean mass on the prefix).  qd [B, T, Hq, D]; k [Hkv, N, D]."""
+    bsz, t, hq, d = qd.shape
+    hkv = k.shape[0]
+    grp = hq // hkv
+    scale = 1.0 / np.sqrt(d) if scale is None else float(scale)
+    b = np.asarray(chunk_bounds, dtype=np.int64)
+    assert int(b[0]) == int(n_prefix)
+    c_n = len(b) - 1
+    k64 = np.asarray(k, dtype=np.float64)
+    out = np.zeros((bsz, c_n), dtype=np.float64)
+    for bi in range(bsz):
+        for h in range(hq):
+            kg = k64[h // grp]
+            for t0 in range(0, t, row_block):
+                q = np.asarray(qd[bi, t0:t0 + row_block, h], dtype=np.float64)      # [rows, D]
+                s = scale * (q @ kg.T)                                              # [rows, N]
+                s -= s.max(axis=1, keepdims=True)
+                p = np.exp(s)
+                p /= p.sum(axis=1, keepdims=True)
+                for c in range(c_n):
+                    out[bi, c] += p[:, b[c]:b[c + 1]].sum()
+    return out / (t * hq)
+
+
 def select_topk(scores, k, decide_dtype=np.float32):
     """(topk_idx [B, k'], dense_mask [B, C] uint8) with k' = min(k, C).
 

@@ -43,6 +43,74 @@ def test_score_is_mean_logit_by_brute_force():
             assert abs(sum(vals) / len(vals) - got[b, c]) < 1e-13
 
 
+def test_mass_score_by_brute_force():
+    """Attention-mass score against scalar loops with math.exp (nothing shared with the matrix code)."""
+    rng = np.random.default_rng(35)
+    lay = wl.random_layout(rng, 2, 4, 1, 6)
+    hq, hkv, d, t, bsz = 4, 2, 5, 3, 2
+    qd = rng.standard_normal((bsz, t, hq, d)).astype(np.float32)
+    k = rng.standard_normal((hkv, lay.n_tokens, d)).astype(np.float32)
+    got = oracle.chunk_scores_mass(qd, k, lay.n_prefix, lay.chunk_bounds)
+    want = np.zeros_like(got)
+    for b in range(bsz):
+        for tt in range(t):
+            for h in range(hq):
+                g = h // (hq // hkv)
+                e = [math.exp(sum(float(qd[b, tt, h, x]) * float(k[g, j, x]) for x in range(d)) / math.sqrt(d))
+                     for j in range(lay.n_tokens)]
+                z = sum(e)
+                for c in range(lay.n_chunks):
+                    want[b, c] += sum(e[lay.chunk_bounds[c]:lay.chunk_bounds[c + 1]]) / z
+    want /= t * hq
+    assert np.abs(got - want).max() < 1e-14
+
+
+def test_mass_score_closed_forms():
+    rng = np.random.default_rng(36)
+    lay = wl.random_layout(rng, 5, 6, 1, 9)
+    n = lay.n_tokens
+    lens = np.diff(lay.chunk_bounds)
+    qd = rng.standard_normal((2, 3, 4, 8)).astype(np.float32)
+    # identical keys everywhere: the attention is uniform, a chunk's mass is its share of the tokens
+    k = np.broadcast_to(rng.standard_normal((2, 1, 8)).astype(np.float32), (2, n, 8)).copy()
+    got = oracle.chunk_scores_mass(qd, k, lay.n_prefix, lay.chunk_bounds)
+    assert np.abs(got - lens[None, :] / n).max() < 1e-14
+    # the scores of a query and its mean prefix mass add up to one
+    k = rng.standard_normal((2, n, 8)).astype(np.float32)
+    got = oracle.chunk_scores_mass(qd, k, lay.n_prefix, lay.chunk_bounds)
+    no_prefix = oracle.chunk_scores_mass(qd, k[:, lay.n_prefix:], 0, lay.chunk_bounds - lay.n_prefix)
+    assert (got >= 0).all() and (got.sum(axis=1) < 1).all()
+    assert np.abs(no_prefix.sum(axis=1) - 1).max() < 1e-14
+    # scale 0: uniform again, whatever the keys
+    got = oracle.chunk_scores_mass(qd, k, lay.n_prefix, lay.chunk_bounds, scale=0.0)
+    assert np.abs(got - lens[None, :] / n).max() < 1e-14
+    # one key far above the others takes all the mass for its chunk
+    c, qd1 = 3, np.ones((1, 1, 2, 8), np.float32)
+    k1 = np.zeros((2, n, 8), np.float32)
+    k1[:, lay.chunk_bounds[c] + 1] = 40.0
+    got = oracle.chunk_scores_mass(qd1, k1, lay.n_prefix, lay.chunk_bounds)
+    assert abs(got[0, c] - 1) < 1e-12 and np.abs(np.delete(got[0], c)).max() < 1e-12
+
+
+def test_mass_score_small_logits_follow_the_mean_logit_score():
+    """For small logits exp(s) ~ 1 + s: mass_c ~ len_c/N * (1 + mean logit of c - mean logit overall),
+    i.e. per token the mass score orders chunks like the mean-logit score."""
+    rng = np.random.default_rng(37)
+    lay = wl.layout_from_lists(0, [6] * 5, [np.zeros(0, np.int32)] * 5)
+    qd = (rng.standard_normal((1, 2, 4, 8)) * 0.01).astype(np.float32)
+    k = (rng.standard_normal((2, 30, 8)) * 0.01).astype(np.float32)
+    mass = oracle.chunk_scores_mass(qd, k, 0, lay.chunk_bounds)
+    # first-order expansion evaluated with the explicit logit matrix
+    grp = 2
+    first = np.zeros(5)
+    for t in range(2):
+        for h in range(4):
+            s = (qd[0, t, h].astype(np.float64) @ k[h // grp].astype(np.float64).T) / math.sqrt(8)
+            first += np.array([(1 + s[6 * c:6 * c + 6] - s.mean()).sum() / 30 for c in range(5)])
+    first /= 8
+    assert np.abs(mass - first).max() < 1e-7
+
+
 def test_topk_exhaustive_enumeration():
     rng = np.random.default_rng(31)
     for trial in range(40):
