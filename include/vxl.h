@@ -54,7 +54,8 @@ typedef enum {
     VXL_OP_PREFILL = 0,
     VXL_OP_SCORE_TOPK = 1,
     VXL_OP_GATHER = 2,
-    VXL_OP_DECODE = 3
+    VXL_OP_DECODE = 3,
+    VXL_OP_SCORE_MASS = 4
 } vxl_op;
 
 typedef struct {
@@ -103,8 +104,8 @@ vxl_status vxl_layout_create_windowed(int32_t n_tokens, int32_t n_prefix, int32_
 vxl_status vxl_layout_destroy(vxl_layout* layout);
 
 /* Bytes of workspace the given hot call needs (0 on invalid arguments).  batch, n_q_tokens
- * and l_cap are read by the ops that take them (SCORE_TOPK, GATHER: batch; DECODE: batch,
- * n_q_tokens, l_cap); layout may be NULL for VXL_OP_DECODE. */
+ * and l_cap are read by the ops that take them (SCORE_TOPK, GATHER: batch; SCORE_MASS: batch,
+ * n_q_tokens; DECODE: batch, n_q_tokens, l_cap); layout may be NULL for VXL_OP_DECODE. */
 size_t vxl_workspace_bytes(vxl_op op, const vxl_layout* layout, const vxl_attn_desc* desc,
                            int32_t batch, int32_t n_q_tokens, int32_t l_cap);
 
@@ -152,6 +153,23 @@ vxl_status vxl_chunk_score_topk(const vxl_layout* layout, const vxl_attn_desc* d
                                 const void* K, int32_t k, float* kbar, int32_t kbar_ready,
                                 int32_t* topk_idx, uint8_t* dense_mask, float* scores,
                                 void* workspace, size_t workspace_bytes, vxl_stream stream);
+
+/*
+ * The same selection with the other reading of the attention-score relevance oracle
+ * ("Bi-level KVs Decoding" names the attention score mechanism without a formula): the softmax
+ * attention MASS on the chunk,
+ *   p[b,t,h,j]  = softmax over all tokens j (prefix and every chunk) of scale * Qd[b,t,h,:].K[g(h),j,:]
+ *   score[b,c]  = mean over (t, h) of sum over j in chunk c of p[b,t,h,j]
+ * The prefix takes part in the softmax but is not scored.  Unlike the mean-logit score this one
+ * is not normalised by the chunk length, and there is no per-chunk summary to cache: every call
+ * streams the dense keys once.  Arguments as vxl_chunk_score_topk (K is always read; workspace
+ * sized by VXL_OP_SCORE_MASS).  Scores are computed in fp32 with fixed summation orders.
+ */
+vxl_status vxl_chunk_score_topk_mass(const vxl_layout* layout, const vxl_attn_desc* desc,
+                                     const void* Qd, int32_t batch, int32_t n_q_tokens,
+                                     const void* K, int32_t k, int32_t* topk_idx,
+                                     uint8_t* dense_mask, float* scores, void* workspace,
+                                     size_t workspace_bytes, vxl_stream stream);
 
 /*
  * Reload and concatenate ("Bi-level KVs Decoding": dense KVs for the relevant chunks, sparse

@@ -221,6 +221,19 @@ vxl_status vxl_layout_create_windowed(int32_t n_tokens, int32_t n_prefix, int32_
         L->n_work[v] = (int32_t)work[v].size();
     }
 
+    // items of the attention-mass score: the prefix and every chunk in pieces of kMassPiece keys
+    std::vector<MassItem> mass_items;
+    std::vector<int32_t> mass_off(n_chunks + 1, 0);
+    for (int32_t lo = 0; lo < n_prefix; lo += kMassPiece)
+        mass_items.push_back({lo, std::min(lo + kMassPiece, n_prefix), -1});
+    for (int c = 0; c < n_chunks; ++c) {
+        mass_off[c] = (int32_t)mass_items.size();
+        for (int32_t lo = chunk_bounds[c]; lo < chunk_bounds[c + 1]; lo += kMassPiece)
+            mass_items.push_back({lo, std::min(lo + kMassPiece, chunk_bounds[c + 1]), c});
+    }
+    mass_off[n_chunks] = (int32_t)mass_items.size();
+    L->n_mass_items = (int32_t)mass_items.size();
+
     // one device blob
     size_t off = 0;
     auto place = [&](size_t bytes) { size_t o = off; off += align_up(std::max<size_t>(bytes, 4), 256); return o; };
@@ -230,6 +243,8 @@ vxl_status vxl_layout_create_windowed(int32_t n_tokens, int32_t n_prefix, int32_
     const size_t o_tsrc = place(tile_src.size() * 4);
     const size_t o_w0 = place(work[0].size() * sizeof(WorkItem));
     const size_t o_w1 = place(work[1].size() * sizeof(WorkItem));
+    const size_t o_mi = place(mass_items.size() * sizeof(MassItem));
+    const size_t o_mo = place(mass_off.size() * 4);
     L->blob_bytes = off;
     std::vector<char> host(off, 0);
     memcpy(host.data() + o_bounds, L->bounds.data(), (n_chunks + 1) * 4);
@@ -239,6 +254,8 @@ vxl_status vxl_layout_create_windowed(int32_t n_tokens, int32_t n_prefix, int32_
     memcpy(host.data() + o_tsrc, tile_src.data(), tile_src.size() * 4);
     if (!work[0].empty()) memcpy(host.data() + o_w0, work[0].data(), work[0].size() * sizeof(WorkItem));
     if (!work[1].empty()) memcpy(host.data() + o_w1, work[1].data(), work[1].size() * sizeof(WorkItem));
+    if (!mass_items.empty()) memcpy(host.data() + o_mi, mass_items.data(), mass_items.size() * sizeof(MassItem));
+    memcpy(host.data() + o_mo, mass_off.data(), mass_off.size() * 4);
 
     hipError_t e = hipGetDevice(&L->device);
     if (e == hipSuccess) e = hipMalloc(&L->d_blob, off);
@@ -258,6 +275,8 @@ vxl_status vxl_layout_create_windowed(int32_t n_tokens, int32_t n_prefix, int32_
     L->d_tile_src = (int32_t*)(base + o_tsrc);
     L->d_work[0] = (WorkItem*)(base + o_w0);
     L->d_work[1] = (WorkItem*)(base + o_w1);
+    L->d_mass_items = (MassItem*)(base + o_mi);
+    L->d_mass_off = (int32_t*)(base + o_mo);
     *out = L;
     return VXL_OK;
 }
@@ -304,6 +323,9 @@ size_t vxl_workspace_bytes(vxl_op op, const vxl_layout* L, const vxl_attn_desc* 
         case VXL_OP_DECODE:
             if (batch <= 0 || n_q_tokens <= 0 || l_cap <= 0) return 0;
             return std::max<size_t>(256, decode_plan(d, batch, n_q_tokens, l_cap).total);
+        case VXL_OP_SCORE_MASS:
+            if (!L || batch <= 0 || n_q_tokens <= 0) return 0;
+            return std::max<size_t>(256, mass_plan(L, d, batch, n_q_tokens).total);
     }
     return 0;
 }
@@ -353,6 +375,27 @@ vxl_status vxl_chunk_score_topk(const vxl_layout* L, const vxl_attn_desc* d, con
     }
     return launch_score_topk(L, d, resolve_scale(d), Qd, batch, n_q_tokens, kk, kb, topk_idx,
                              dense_mask, scores, (hipStream_t)stream);
+}
+
+vxl_status vxl_chunk_score_topk_mass(const vxl_layout* L, const vxl_attn_desc* d, const void* Qd,
+                                     int32_t batch, int32_t n_q_tokens, const void* K, int32_t k,
+                                     int32_t* topk_idx, uint8_t* dense_mask, float* scores,
+                                     void* workspace, size_t workspace_bytes, vxl_stream stream) {
+    vxl_status st;
+    if (!L) return VXL_ERR_INVALID_ARG;
+    if (!desc_ok(d, &st)) return st;
+    if (!Qd || !K || batch <= 0 || n_q_tokens <= 0 || k < 0 || !dense_mask) return VXL_ERR_INVALID_ARG;
+    if (!aligned16(Qd) || !aligned16(K)) return VXL_ERR_INVALID_ARG;
+    const int kk = std::min(k, L->n_chunks);
+    if (kk > 0 && !topk_idx) return VXL_ERR_INVALID_ARG;
+    if (L->n_chunks == 0) return VXL_OK;      // nothing to score, nothing to write
+    const MassPlan p = mass_plan(L, d, batch, n_q_tokens);
+    if (!workspace || workspace_bytes < p.total || !aligned16(workspace)) return VXL_ERR_WORKSPACE;
+    float* sc = scores ? scores : (float*)((char*)workspace + p.scores);
+    st = launch_score_mass(L, d, resolve_scale(d), Qd, batch, n_q_tokens, K, sc, workspace,
+                           g_force_simple != 0, (hipStream_t)stream);
+    if (st != VXL_OK) return st;
+    return launch_topk_from_scores(L, sc, batch, kk, topk_idx, dense_mask, (hipStream_t)stream);
 }
 
 vxl_status vxl_gather_bilevel_kv(const vxl_layout* L, const vxl_attn_desc* d, const void* K,

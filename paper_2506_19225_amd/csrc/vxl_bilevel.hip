@@ -78,6 +78,41 @@ __device__ __forceinline__ bool ranks_before(float sa, int ia, float sb, int ib)
     return sa > sb || (sa == sb && ia < ib);     // score descending, ties to the lower chunk id
 }
 
+// Bitonic sort of (score, chunk id) in LDS, best first (s_val / s_idx hold n_sort entries, a power
+// of two, padding = (-inf, INT_MAX)), then the ids of the k best and the membership mask of query b.
+// Called by all 256 threads of the block after a barrier.
+__device__ __forceinline__ void sort_select(float* s_val, int* s_idx, int n_sort, int n_chunks, int k, int b,
+                                            int32_t* __restrict__ topk_idx, uint8_t* __restrict__ dense_mask) {
+    const int tid = threadIdx.x;
+    // bitonic sort, best first
+    for (int size = 2; size <= n_sort; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int i = tid; i < n_sort / 2; i += 256) {
+                const int lo = 2 * i - (i & (stride - 1));
+                const int hi = lo + stride;
+                const bool up = ((lo & size) == 0);
+                const float va = s_val[lo], vb = s_val[hi];
+                const int ia = s_idx[lo], ib = s_idx[hi];
+                const bool a_first = ranks_before(va, ia, vb, ib);
+                if (a_first != up) { s_val[lo] = vb; s_val[hi] = va; s_idx[lo] = ib; s_idx[hi] = ia; }
+            }
+            __syncthreads();
+        }
+    }
+    // membership flags in LDS (the sorted scores are no longer needed), then one coalesced
+    // write of the mask
+    int* flag = (int*)s_val;
+    for (int c = tid; c < n_sort; c += 256) flag[c] = 0;
+    __syncthreads();
+    for (int i = tid; i < k; i += 256) {
+        const int c = s_idx[i];
+        topk_idx[(size_t)b * k + i] = c;
+        if (c < n_chunks) flag[c] = 1;       // (a NaN score could surface a padding slot)
+    }
+    __syncthreads();
+    for (int c = tid; c < n_chunks; c += 256) dense_mask[(size_t)b * n_chunks + c] = (uint8_t)flag[c];
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void score_topk_kernel(
     const T* __restrict__ Qd, const float* __restrict__ kbar, int T_q, int n_q_heads, int n_kv_heads,
@@ -183,33 +218,23 @@ __global__ __launch_bounds__(256) void score_topk_kernel(
         }
     }
     __syncthreads();
-    // bitonic sort, best first
-    for (int size = 2; size <= n_sort; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int i = tid; i < n_sort / 2; i += 256) {
-                const int lo = 2 * i - (i & (stride - 1));
-                const int hi = lo + stride;
-                const bool up = ((lo & size) == 0);
-                const float va = s_val[lo], vb = s_val[hi];
-                const int ia = s_idx[lo], ib = s_idx[hi];
-                const bool a_first = ranks_before(va, ia, vb, ib);
-                if (a_first != up) { s_val[lo] = vb; s_val[hi] = va; s_idx[lo] = ib; s_idx[hi] = ia; }
-            }
-            __syncthreads();
-        }
-    }
-    // membership flags in LDS (the sorted scores are no longer needed), then one coalesced
-    // write of the mask
-    int* flag = (int*)s_val;
-    for (int c = tid; c < n_sort; c += 256) flag[c] = 0;
-    __syncthreads();
-    for (int i = tid; i < k; i += 256) {
-        const int c = s_idx[i];
-        topk_idx[(size_t)b * k + i] = c;
-        if (c < n_chunks) flag[c] = 1;       // (a NaN score could surface a padding slot)
+    sort_select(s_val, s_idx, n_sort, n_chunks, k, b, topk_idx, dense_mask);
+}
+
+// Selection alone, from scores some other kernel has written: one block per query.
+__global__ __launch_bounds__(256) void topk_from_scores_kernel(const float* __restrict__ scores, int n_chunks,
+                                                               int k, int n_sort, int32_t* __restrict__ topk_idx,
+                                                               uint8_t* __restrict__ dense_mask) {
+    extern __shared__ unsigned char smem[];
+    float* s_val = (float*)smem;                              // [n_sort]
+    int* s_idx = (int*)(s_val + n_sort);                      // [n_sort]
+    const int b = blockIdx.x;
+    for (int c = threadIdx.x; c < n_sort; c += 256) {
+        s_val[c] = c < n_chunks ? scores[(size_t)b * n_chunks + c] : -INFINITY;
+        s_idx[c] = c < n_chunks ? c : 0x7fffffff;
     }
     __syncthreads();
-    for (int c = tid; c < n_chunks; c += 256) dense_mask[(size_t)b * n_chunks + c] = (uint8_t)flag[c];
+    sort_select(s_val, s_idx, n_sort, n_chunks, k, b, topk_idx, dense_mask);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -323,6 +348,16 @@ vxl_status launch_score_topk(const vxl_layout* L, const vxl_attn_desc* d, float 
     if (d->dtype == VXL_F32) { if (d->head_dim == 64) VXL_LAUNCH(float, 64); else VXL_LAUNCH(float, 128); }
     else { if (d->head_dim == 64) VXL_LAUNCH(uint16_t, 64); else VXL_LAUNCH(uint16_t, 128); }
 #undef VXL_LAUNCH
+    VXL_HIP_TRY(hipGetLastError());
+    return VXL_OK;
+}
+
+vxl_status launch_topk_from_scores(const vxl_layout* L, const float* scores, int batch, int k,
+                                   int32_t* topk_idx, uint8_t* dense_mask, hipStream_t s) {
+    int n_sort = 2;
+    while (n_sort < L->n_chunks) n_sort <<= 1;
+    hipLaunchKernelGGL(topk_from_scores_kernel, dim3(batch), dim3(256), (size_t)n_sort * 8, s, scores,
+                       L->n_chunks, k, n_sort, topk_idx, dense_mask);
     VXL_HIP_TRY(hipGetLastError());
     return VXL_OK;
 }

@@ -31,6 +31,14 @@ struct WorkItem {
     int32_t m_tile;     // query row tile inside the segment
 };
 
+// One item of the attention-mass score: a piece (at most kMassPiece keys) of the prefix or of a
+// chunk.  The prefix pieces come first, then the pieces of the chunks in chunk order.
+constexpr int kMassPiece = 1024;
+struct MassItem {
+    int32_t key_lo, key_hi;   // token range [key_lo, key_hi)
+    int32_t chunk;            // -1 for the prefix
+};
+
 }  // namespace vxl
 
 struct vxl_layout {
@@ -56,6 +64,10 @@ struct vxl_layout {
     vxl::WorkItem* d_work[2] = {nullptr, nullptr};   // heaviest-first items for 128 / 256 rows
     int32_t n_work[2] = {0, 0};
     int64_t pair_count = 0;
+    // attention-mass score: item table and, per chunk, its range of items
+    int32_t n_mass_items = 0;
+    vxl::MassItem* d_mass_items = nullptr;   // [n_mass_items]
+    int32_t* d_mass_off = nullptr;           // [C+1]: items of chunk c are [off[c], off[c+1])
 };
 
 namespace vxl {
@@ -95,6 +107,21 @@ vxl_status launch_chunk_summarize(const vxl_layout* L, const vxl_attn_desc* d, c
 vxl_status launch_score_topk(const vxl_layout* L, const vxl_attn_desc* d, float scale,
                              const void* Qd, int batch, int T, int k, const float* kbar,
                              int32_t* topk_idx, uint8_t* dense_mask, float* scores, hipStream_t s);
+vxl_status launch_topk_from_scores(const vxl_layout* L, const float* scores, int batch, int k,
+                                   int32_t* topk_idx, uint8_t* dense_mask, hipStream_t s);
+
+// attention-mass score
+struct MassPlan {              // byte offsets into the caller's workspace
+    size_t part_m, part_l;     // [B][Hkv][n_mass_items][G*T] per-item maximum (base 2) and sum
+    size_t row_m, row_il;      // [B][Hkv][G*T] per-row maximum and reciprocal of the total sum
+    size_t scores;             // [B][C] (used when the caller does not ask for the scores)
+    size_t total;
+};
+MassPlan mass_plan(const vxl_layout* L, const vxl_attn_desc* d, int batch, int T);
+vxl_status launch_score_mass(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Qd,
+                             int batch, int T, const void* K, float* scores, void* ws, bool force_simple,
+                             hipStream_t s);
+
 vxl_status launch_gather(const vxl_layout* L, const vxl_attn_desc* d, const void* K, const void* V,
                          const uint8_t* dense_mask, int batch, void* Kmix, void* Vmix, int l_cap,
                          int32_t* mix_len, int32_t* src_idx, int32_t* ws_offsets, hipStream_t s);

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG, "libvxl.so")
 
 VXL_OK, VXL_ERR_INVALID_ARG, VXL_ERR_UNSUPPORTED, VXL_ERR_WORKSPACE, VXL_ERR_HIP = range(5)
 VXL_F32, VXL_BF16 = 0, 1
-OP_PREFILL, OP_SCORE_TOPK, OP_GATHER, OP_DECODE = range(4)
+OP_PREFILL, OP_SCORE_TOPK, OP_GATHER, OP_DECODE, OP_SCORE_MASS = range(5)
 MAX_CHUNKS = 4096
 
 
@@ -67,6 +67,8 @@ def lib() -> C.CDLL:
     L.vxl_chunk_prefill.argtypes = [vp, dp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.vxl_chunk_score_topk.restype = C.c_int
     L.vxl_chunk_score_topk.argtypes = [vp, dp, vp, i32, i32, vp, i32, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.vxl_chunk_score_topk_mass.restype = C.c_int
+    L.vxl_chunk_score_topk_mass.argtypes = [vp, dp, vp, i32, i32, vp, i32, vp, vp, vp, vp, sz, vp]
     L.vxl_gather_bilevel_kv.restype = C.c_int
     L.vxl_gather_bilevel_kv.argtypes = [vp, dp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, sz, vp]
     L.vxl_bilevel_decode.restype = C.c_int
@@ -182,6 +184,16 @@ def chunk_score_topk(layout: Layout, desc: AttnDesc, qd, k, top_k: int, topk_idx
                                     _ptr(scores), _ptr(workspace),
                                     workspace.numel() if workspace is not None else 0, _stream(stream))
     _check(st, "vxl_chunk_score_topk")
+
+
+def chunk_score_topk_mass(layout: Layout, desc: AttnDesc, qd, k, top_k: int, topk_idx, dense_mask,
+                          scores=None, workspace=None, stream=None):
+    """vxl_chunk_score_topk_mass: arguments as chunk_score_topk, softmax attention-mass score."""
+    b, t = int(qd.shape[0]), int(qd.shape[1])
+    st = lib().vxl_chunk_score_topk_mass(layout.handle, C.byref(desc), _ptr(qd), b, t, _ptr(k), int(top_k),
+                                         _ptr(topk_idx), _ptr(dense_mask), _ptr(scores), _ptr(workspace),
+                                         workspace.numel() if workspace is not None else 0, _stream(stream))
+    _check(st, "vxl_chunk_score_topk_mass")
 
 
 def gather_bilevel_kv(layout: Layout, desc: AttnDesc, k, v, dense_mask, kmix, vmix, mix_len,

@@ -93,3 +93,19 @@ def gpu_decode(w, qd, kmix_dev, vmix_dev, mix_len_dev, scale=0.0, want_lse=False
     torch.cuda.synchronize()
     res = vxl.to_host(out)
     return (res, vxl.to_host(lse)) if want_lse else res
+
+
+def gpu_score_topk_mass(w, lay, qd, k, top_k, gl=None, scale=0.0):
+    """vxl_chunk_score_topk_mass -> (topk_idx, dense_mask, scores) as host arrays."""
+    gl = gl or make_layout(lay)
+    desc = desc_of(w, scale)
+    dqd, dk = vxl.to_device(qd, w.dtype), vxl.to_device(k, w.dtype)
+    bsz, c_n = qd.shape[0], lay.n_chunks
+    kk = min(top_k, c_n)
+    idx = torch.full((bsz, max(kk, 1)), -7, dtype=torch.int32, device="cuda")
+    mask = torch.full((bsz, max(c_n, 1)), 9, dtype=torch.uint8, device="cuda")
+    scores = torch.full((bsz, max(c_n, 1)), float("nan"), dtype=torch.float32, device="cuda")
+    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_SCORE_MASS, gl, desc, bsz, qd.shape[1]))
+    vxl.chunk_score_topk_mass(gl, desc, dqd, dk, top_k, idx, mask, scores, workspace=ws)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy()[:, :kk], mask.cpu().numpy()[:, :c_n], scores.cpu().numpy()[:, :c_n]
