@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libvxl.so")
 
-SOURCES = ["vxl_api.hip", "vxl_simple.hip", "vxl_bilevel.hip", "vxl_prefill.hip", "vxl_decode.hip", "vxl_mass.hip"]
+SOURCES = ["vxl_api.hip", "vxl_simple.hip", "vxl_bilevel.hip", "vxl_prefill.hip", "vxl_decode.hip", "vxl_mass.hip", "vxl_prefill_pipe.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=default",
@@ -35,6 +35,11 @@ def _hipcc() -> str:
 # a compile in which one of them uses scratch memory.
 NO_SCRATCH = {"vxl_prefill.hip": ("prefill_dma_kernel",), "vxl_decode.hip": ("decode_ring_kernel",)}
 
+# Per-file compiler options.  The software-pipelined pre-filling kernel runs one wave per SIMD with
+# more than 256 registers; its score products must land in ordinary vector registers (the vector
+# ALU reads them), its output accumulators are placed in the accumulation registers by hand.
+EXTRA_FLAGS = {"vxl_prefill_pipe.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
 
 def _check_no_scratch(src: str, remarks: str) -> None:
     name = None
@@ -51,6 +56,7 @@ def _check_no_scratch(src: str, remarks: str) -> None:
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     extra = ["-Rpass-analysis=kernel-resource-usage"] if src in NO_SCRATCH else []
+    extra += EXTRA_FLAGS.get(src, [])
     cmd = [_hipcc(), *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"

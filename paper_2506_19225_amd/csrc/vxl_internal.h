@@ -97,6 +97,10 @@ PrefillWorkspace prefill_workspace(const vxl_layout* L, const vxl_attn_desc* d);
 vxl_status launch_prefill_bf16(const vxl_layout* L, const vxl_attn_desc* d, float scale,
                                const void* Q, const void* K, const void* V, void* O, float* LSE,
                                void* ws, hipStream_t s);
+// main kernel of the software-pipelined form (4 waves x 64 rows); pre-pass done by the caller
+vxl_status launch_prefill_pipe_main(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Q,
+                                    const void* K, const void* V, const uint16_t* kctx, const uint16_t* vctx,
+                                    void* O, float* LSE, int* queue, hipStream_t s);
 vxl_status launch_prefill_simple(const vxl_layout* L, const vxl_attn_desc* d, float scale,
                                  const void* Q, const void* K, const void* V, void* O, float* LSE,
                                  hipStream_t s);

@@ -465,7 +465,8 @@ extern "C" void vxl_debug_prefill_profile(void* buf) { g_prof_buf = (unsigned lo
 static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 // Cross-check and measurement only: 0 = the streaming kernel (default); 1, 2 = the 4-wave
 // register-staged kernel with one or two 32-row blocks per wave.
-extern "C" void vxl_debug_prefill_variant(int v) { g_prefill_variant = (v == 1 || v == 2) ? v : 0; }
+// 3 = the software-pipelined 4-wave kernel with 64 rows per wave.
+extern "C" void vxl_debug_prefill_variant(int v) { g_prefill_variant = (v >= 1 && v <= 3) ? v : 0; }
 // Measurement hook: when both events are set, every vxl_chunk_prefill records them on its stream
 // immediately before and after the main attention kernel (the pre-pass is outside the bracket).
 extern "C" void vxl_debug_prefill_events(void* start, void* stop) {
@@ -556,6 +557,12 @@ static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, f
     }
     const bool timed = g_ev_start && g_ev_stop;
     if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_start, s));
+    if (g_prefill_variant == 3) {
+        const vxl_status st = launch_prefill_pipe_main(L, d, scale, Q, K, V, kctx, vctx, O, LSE, queue, s);
+        if (st != VXL_OK) return st;
+        if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_stop, s));
+        return VXL_OK;
+    }
     const int group = d->n_q_heads / d->n_kv_heads;
     const int xpg = (!(g_prefill_dbg & 2) && 8 % d->n_kv_heads == 0) ? 8 / d->n_kv_heads : 0;
     const long long n_pairs = (long long)L->n_work[1] * d->n_q_heads;
@@ -572,7 +579,7 @@ static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, f
 
 vxl_status launch_prefill_bf16(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Q,
                                const void* K, const void* V, void* O, float* LSE, void* ws, hipStream_t s) {
-    if (g_prefill_variant == 0)
+    if (g_prefill_variant == 0 || g_prefill_variant == 3)
         return d->head_dim == 128 ? run_prefill_dma<128, 4>(L, d, scale, Q, K, V, O, LSE, ws, s)
                                   : run_prefill_dma<64, 4>(L, d, scale, Q, K, V, O, LSE, ws, s);
     if (d->head_dim == 128)
