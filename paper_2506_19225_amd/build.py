@@ -33,7 +33,8 @@ def _hipcc() -> str:
 # loads issued from inline assembly, waited for with hand-written vmcnt values): a register spill
 # would add scratch loads and stores to that count behind the kernel's back, so the build refuses
 # a compile in which one of them uses scratch memory.
-NO_SCRATCH = {"vxl_prefill.hip": ("prefill_dma_kernel",), "vxl_decode.hip": ("decode_ring_kernel",)}
+NO_SCRATCH = {"vxl_prefill.hip": ("prefill_dma_kernel",), "vxl_decode.hip": ("decode_ring_kernel",),
+              "vxl_prefill_pipe.hip": ("prefill_pipe_kernel",)}
 
 # Per-file compiler options.  The software-pipelined pre-filling kernel runs one wave per SIMD with
 # more than 256 registers; its score products must land in ordinary vector registers (the vector
@@ -57,6 +58,8 @@ def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     extra = ["-Rpass-analysis=kernel-resource-usage"] if src in NO_SCRATCH else []
     extra += EXTRA_FLAGS.get(src, [])
+    if os.environ.get("VXL_PIPE_ABL") and src == "vxl_prefill_pipe.hip":     # measurement builds only
+        extra += ["-DVXL_PIPE_ABL=" + os.environ["VXL_PIPE_ABL"]]
     cmd = [_hipcc(), *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"

@@ -138,9 +138,12 @@ __device__ __forceinline__ void softmax_tile(f32x16 (&s)[KB], float c2, float& m
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    // The test is made on this lane's half of the keys (the two lanes of a row keep equal
+    // references, and the ballot covers both), so the common path has no cross-lane traffic; the
+    // row maximum is only formed when the reference is raised.
     const bool grow = (mx - m_run) * c2 > 8.f;              // also true for the first finite logit
     if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(m_run, mx);
         const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_run - m_new) * c2);
         l_run *= alpha;

@@ -42,6 +42,15 @@ namespace vxl {
 
 namespace {
 
+// Measurement builds only (VXL_PIPE_ABL in the environment of the build script): bit 0 leaves out
+// the exponentials, bit 1 the exponent / maximum / row-sum work, bit 2 the ring loads inside the
+// loop -- the results are then wrong, all accesses stay in bounds -- and bit 5 adds up the clock
+// ticks of the four phases and the barrier per wave and stores the totals behind the LSE array
+// (which the caller must then make 64 floats longer).
+#ifndef VXL_PIPE_ABL
+#define VXL_PIPE_ABL 0
+#endif
+
 template <int D>
 struct PipeCfg {
     static constexpr int WAVES = 4;
@@ -61,30 +70,29 @@ struct PipeCfg {
 typedef __attribute__((address_space(3))) const char* lds_cptr;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
-// The output accumulators live in the accumulation registers: their matrix instructions are
-// issued from inline assembly.  The compiler does not know these instructions' latency, so every
-// vector-ALU read of an accumulator is preceded by settle_acc (the rare rescale and the final
-// store; the matrix pipe itself orders dependent accumulations).
+// All matrix products go through the compiler's builtins (at one wave per SIMD their results are
+// placed in the accumulation registers; the vector ALU reads the scores from there).
 __device__ __forceinline__ void mfma_acc(f32x16& o, const bf16x8& a, const bf16x8& b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(o) : "v"(a), "v"(b));
+    o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, o, 0, 0, 0);
 }
-__device__ __forceinline__ void settle_acc(f32x16& o) {
-    asm volatile("s_nop 15\n\ts_nop 15" : "+a"(o));
-}
+__device__ __forceinline__ void settle_acc(f32x16&) {}
 
-// K operand of the 16-wide d step ks for the 32 keys kb*32.. of the tile at LDS byte address `tile`
-// (koff: this lane's byte offsets of its pieces in key block 0).
+// K operand of the 16-wide d step ks for the 32 keys kb*32.. of the tile at LDS byte offset `tile`.
+// koff: this lane's byte offset of its piece for ks = 0 in key block 0; the XOR swizzle of the
+// 16-byte pieces commutes with the d step (bits 5..), so the other steps are one XOR away, and
+// the key block and the tile only add multiples of 256.
 template <int D>
-__device__ __forceinline__ bf16x8 read_k(lds_cptr ring, uint32_t tile, const uint32_t (&koff)[D / 16], int kb,
-                                         int ks) {
-    return *(const __attribute__((address_space(3))) bf16x8*)(ring + (tile + koff[ks]) + kb * 32 * D * 2);
+__device__ __forceinline__ bf16x8 read_k(lds_cptr ring, uint32_t tile, uint32_t koff, int kb, int ks) {
+    return *(const __attribute__((address_space(3))) bf16x8*)(ring + ((tile + koff) ^ (uint32_t)(ks << 5)) +
+                                                               kb * 32 * D * 2);
 }
-// V^T operand (transposing LDS read) of the 16-key step (kb, j) and the 32-wide d block db.
+// V^T operand (transposing LDS read) of the 16-key step (kb, j) and the 32-wide d block db; voff:
+// this lane's byte offset for db = 0 in the first 16-key step (the swizzle of the 64-byte chunks
+// commutes with db in the same way).
 template <int D>
-__device__ __forceinline__ bf16x8 read_vt(lds_cptr ring, uint32_t tile, const uint32_t (&voff)[D / 32], int kb,
-                                          int j, int db) {
+__device__ __forceinline__ bf16x8 read_vt(lds_cptr ring, uint32_t tile, uint32_t voff, int kb, int j, int db) {
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-    lds_cptr p = ring + (tile + voff[db]) + (kb * 32 + j * 16) * D * 2;
+    lds_cptr p = ring + ((tile + voff) ^ (uint32_t)(db << 6)) + (kb * 32 + j * 16) * D * 2;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
     const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * D * 2));   // row + 8: same swizzle
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -111,19 +119,15 @@ __global__ __launch_bounds__(256, 1) void prefill_pipe_kernel(
     const float c2 = scale * kLog2e;
     const int r_in = lane / C::PPR, pp = lane % C::PPR;
 
-    // this lane's operand offsets (bytes) inside a stage: K pieces of key block 0, V^T pieces of
-    // the first 16-key step
-    uint32_t koff[KS], voff[DB];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) koff[ks] = (uint32_t)k_tile_off<D>(l32, ks * 2 + hi) * 2;
+    // this lane's operand offsets (bytes) inside a stage: its K piece of d step 0 in key block 0,
+    // its V^T piece of d block 0 in the first 16-key step
+    const uint32_t koff = (uint32_t)k_tile_off<D>(l32, hi) * 2;
+    uint32_t voff;
     {
         const int dhalf = (lane >> 4) & 1, sl = lane & 15;
         const int row = 4 * hi + (sl >> 2);
         constexpr int CPR = D * 2 / 64, RPL = D == 128 ? 1 : 2;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-            voff[db] = (uint32_t)(C::TILE + row * D + ((db ^ ((row / RPL) & (CPR - 1))) << 5) + dhalf * 16 +
-                                  4 * (sl & 3)) * 2;
+        voff = (uint32_t)(C::TILE + row * D + (((row / RPL) & (CPR - 1)) << 5) + dhalf * 16 + 4 * (sl & 3)) * 2;
     }
 
     if (tid == 0) next_slot[0] = atomicAdd(queue + qid, 1);
@@ -155,31 +159,48 @@ __global__ __launch_bounds__(256, 1) void prefill_pipe_kernel(
     const char* kown = (const char*)(K + ((size_t)g * n_tokens + sg.q_start - sg.back) * D);
     const char* vown = (const char*)(V + ((size_t)g * n_tokens + sg.q_start - sg.back) * D);
 
-    // Tile t -> stage t % NS.  Every wave issues 2*IPW loads: instruction slots wave, wave + 4, ...
-    auto issue = [&](int t) {
+    // Source of ring tile t (stage t % NS): pointers to its first K and V row, last valid row.
+    struct TileSrc { const char* kb; const char* vb; int rlim; uint32_t st; };
+    auto tile_src = [&](int t) -> TileSrc {
         const bool own = t >= n_full && t < n_full + n_own;
         const int row0 = own ? (t - n_full) * kKeyTile : min(t, n_full) * kKeyTile;
-        const int rlim = own ? min(kKeyTile - 1, sg.back + sg.q_len - 1 - row0) : kKeyTile - 1;
-        const char* kb = (own ? kown : kctx_g) + (size_t)row0 * (D * 2);
-        const char* vb = (own ? vown : vctx_g) + (size_t)row0 * (D * 2);
-        const uint32_t st = lds_base + (uint32_t)(t % NS) * (C::STAGE * 2);
-#pragma unroll
-        for (int i = 0; i < C::IPW; ++i) {
-            const int slot = wave + i * C::WAVES;
-            const int row = slot * C::RPI + r_in;
-            const uint32_t roff = (uint32_t)min(row, rlim) * (D * 2);
+        TileSrc ts;
+        ts.rlim = own ? min(kKeyTile - 1, sg.back + sg.q_len - 1 - row0) : kKeyTile - 1;
+        ts.kb = (own ? kown : kctx_g) + (size_t)row0 * (D * 2);
+        ts.vb = (own ? vown : vctx_g) + (size_t)row0 * (D * 2);
+        ts.st = lds_base + (uint32_t)(t % NS) * (C::STAGE * 2);
+        return ts;
+    };
+    // The i-th of the 2*IPW loads this wave contributes to a tile (instruction slots wave, wave + 4,
+    // ...; even i: K, odd i: V).  Rows beyond rlim are clamped to it.
+    auto issue_one = [&](const TileSrc& ts, int i) {
+        const int slot = wave + (i >> 1) * C::WAVES;
+        const int row = slot * C::RPI + r_in;
+        const uint32_t roff = (uint32_t)min(row, ts.rlim) * (D * 2);
+        if ((i & 1) == 0) {
             const int kp = pp ^ ((row / (16 / C::PPR)) & (C::PPR - 1));
+            dma16(ts.kb, roff + kp * 16, ts.st + slot * 1024);
+        } else {
             constexpr int CPR = D * 2 / 64, RPL = D == 128 ? 1 : 2;
             const int vp = (((pp >> 2) ^ ((row / RPL) & (CPR - 1))) << 2) | (pp & 3);
-            dma16(kb, roff + kp * 16, st + slot * 1024);
-            dma16(vb, roff + vp * 16, st + C::TILE * 2 + slot * 1024);
+            dma16(ts.vb, roff + vp * 16, ts.st + C::TILE * 2 + slot * 1024);
         }
     };
-    // top of step t: tile t+1 lands, everyone is done with tile t-2, tile t+2 is requested
-    auto step_top = [&](int t) {
-        wait_vmcnt<0>();
+    auto issue = [&](int t) {
+        const TileSrc ts = tile_src(t);
+#pragma unroll
+        for (int i = 0; i < 2 * C::IPW; ++i) issue_one(ts, i);
+    };
+    // The one workgroup barrier of step t: behind it tile t+1 is in LDS for everybody (every wave
+    // has waited for its own loads of it; only the loads of tile t+2, requested during this step,
+    // may still be in flight) and everybody is done with tile t-1's K and tile t-2 (so the stage of
+    // tile t-2 may be refilled with tile t+2 in step t+1... and is, at its start).  A pipelined
+    // wave places it before its last phase (the first to touch tile t+1), a sequential wave at
+    // the end of its step.
+    constexpr int NLD = 2 * C::IPW;                           // ring loads per wave and tile
+    auto step_barrier = [&]() {
+        wait_vmcnt<NLD>();
         __builtin_amdgcn_s_barrier();
-        issue(min(t + 2, n_t - 1));
     };
     auto stage_of = [&](int t) -> uint32_t { return (uint32_t)(t % NS) * (C::STAGE * 2); };
 
@@ -188,7 +209,9 @@ __global__ __launch_bounds__(256, 1) void prefill_pipe_kernel(
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
         for (int db = 0; db < DB; ++db) o[qb][db] = zero16();
-    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+    // running reference of a row in the exp2 domain (scaled logit * log2 e) and this lane's half
+    // of the running sum
+    float m2[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
 
     issue(0);
     issue(min(1, n_t - 1));
@@ -213,154 +236,242 @@ __global__ __launch_bounds__(256, 1) void prefill_pipe_kernel(
             for (int ks = 0; ks < KS; ++ks) {
                 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
                 asm volatile("" :: "v"(__builtin_bit_cast(u32x4, qreg[qb][ks])));
+                asm volatile("" : "+a"(qreg[qb][ks]));       // the queries stay in the accumulation registers
             }
     }
+    __builtin_amdgcn_s_barrier();                             // tiles 0 and 1 are in LDS for everybody
     __builtin_amdgcn_sched_barrier(0);
 
-    f32x16 s0[2], s1[2];                                      // scores of the two halves of a tile
-    bf16x8 p0[2][2], p1[2][2];                                // their probabilities, per row block and 16-key step
+    // s0 / s1: the two halves of a tile -- raw scores when a phase B has written them, exponents
+    // x = score*c2 - reference once a phase A has gone over them.  p0 / p1: their probabilities,
+    // per row block and 16-key step.
+    f32x16 s0[2], s1[2];
+    bf16x8 p0[2][2], p1[2][2];
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
-    // The rare raise of the running reference for both row blocks (exact: O and l are rescaled
-    // with it), taken when some lane of the wave sees a logit more than 2^8 above its reference.
-    auto raise = [&](const float (&mx)[2]) {
-        const bool grow = (mx[0] - m_run[0]) * c2 > 8.f || (mx[1] - m_run[1]) * c2 > 8.f;   // true for a first finite logit
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+    // A lane asks for a raise of the running reference when one of its own exponents exceeds 8
+    // (probabilities stay below 2^8, which fp32 and bf16 carry at unchanged relative precision) or
+    // when the row has no reference yet; the decision is wave-uniform (ballot), so the common path
+    // has no cross-lane traffic.  The raise itself is exact: O, l and the exponents at hand are
+    // moved to the new reference.
+    auto wants_raise = [&](const float (&mx)[2]) -> bool {
+        return mx[0] > 8.f || mx[1] > 8.f || (m2[0] == -INFINITY && mx[0] > -INFINITY) ||
+               (m2[1] == -INFINITY && mx[1] > -INFINITY);
+    };
+    auto raise = [&](const float (&mx)[2], f32x16 (&x)[2]) {
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < 2; ++qb) {
 #pragma unroll
-                for (int db = 0; db < DB; ++db) settle_acc(o[qb][db]);
-                const float m_new = fmaxf(m_run[qb], mx[qb]);
-                const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_run[qb] - m_new) * c2);
-                l_run[qb] *= alpha;
-                m_run[qb] = m_new;
+            for (int db = 0; db < DB; ++db) settle_acc(o[qb][db]);
+            const float row_mx = fmaxf(mx[qb], __shfl_xor(mx[qb], 32));
+            const float old_g = m2[qb] == -INFINITY ? 0.f : m2[qb];
+            const float m_new = fmaxf(m2[qb], old_g + row_mx);
+            const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m2[qb] - m_new);
+            const float shift = (m_new == -INFINITY ? 0.f : m_new) - old_g;
+            l_run[qb] *= alpha;
+            m2[qb] = m_new;
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
-            }
+                for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) x[qb][r] -= shift;
         }
     };
 
-    // Phase A: O += P(prev half) . V in NA slices of two matrix instructions, with the row maxima of
-    // s (both row blocks) spread over the slices; then the rare raise.  PV = false: maxima only.
-    auto phase_a = [&](auto pv_c, uint32_t tile, int kb, const bf16x8 (&p)[2][2], const f32x16 (&s)[2]) {
-        constexpr int NA = 2 * DB, VPS = 16 / NA;             // slices; score registers per slice and row block
-        float mx[2] = {s[0][0], s[1][0]};
-        bf16x8 a_cur, a_nxt;
-        if constexpr (decltype(pv_c)::value) a_cur = read_vt<D>(ring, tile, voff, kb, 0, 0);
+    // Operand queue of the pipelined phases: the operands of a phase's slices 0 and 1 are requested
+    // by the last two slices of the phase before it.
+    struct OpQ { bf16x8 c, n; };
+    constexpr int NA = 2 * DB;                                // slices of a phase A (2 or 4 matrix instruction pairs per 16-key step)
+    static_assert(NA == 2 * C::IPW, "one ring load per slice of a phase A");
+
+    // Phase A: O += P . V (32 keys kb*32.. of the tile at tv; P = p, whose row sums are added to l
+    // here) in 2*NA slices of ONE matrix instruction each: a wave issues in order, so two matrix
+    // instructions in a row would stall it for the length of the first, and the vector work is
+    // spread evenly between them instead.  Per slice: a share of s -> exponents x = s*c2 - reference
+    // with their lane maxima, a share of the row sums, and (DMA) one of this wave's ring loads of
+    // tile ts.  The last slices request the first operands of the phase B that follows (tile tk, key
+    // block kbk).  Then the raise of the reference: rare, except in the first half of an item
+    // (PV = false: no product is owed yet), where every row gets its reference.
+    auto phase_a = [&](auto pv_c, auto dma_c, uint32_t tv, int kb, const bf16x8 (&p)[2][2], f32x16 (&s)[2],
+                       OpQ& q, uint32_t tk, int kbk, const TileSrc& ts) {
+        constexpr bool PV = decltype(pv_c)::value, DMA = decltype(dma_c)::value;
+        constexpr int VPS = 16 / NA;                          // score registers per operand step and row block
+        float mx[2] = {-INFINITY, -INFINITY}, sum[2] = {0.f, 0.f};
+        const float nmc[2] = {m2[0] == -INFINITY ? 0.f : -m2[0], m2[1] == -INFINITY ? 0.f : -m2[1]};
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             const int jj = i / DB, db = i % DB;
-            if constexpr (decltype(pv_c)::value) {
-                if (i + 1 < NA) a_nxt = read_vt<D>(ring, tile, voff, kb, (i + 1) / DB, (i + 1) % DB);
-                mfma_acc(o[0][db], a_cur, p[0][jj]);
-                mfma_acc(o[1][db], a_cur, p[1][jj]);
-            }
+            bf16x8 nxt;
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
+            for (int qb = 0; qb < 2; ++qb) {
+                if (qb == 0) {
+                    if (i + 2 < NA) { if constexpr (PV) nxt = read_vt<D>(ring, tv, voff, kb, (i + 2) / DB, (i + 2) % DB); }
+                    else nxt = read_k<D>(ring, tk, koff, kbk, i + 2 - NA);
+                }
+                if constexpr (PV) mfma_acc(o[qb][db], q.c, p[qb][jj]);
+                if constexpr (DMA && !(VXL_PIPE_ABL & 4)) { if (qb == 1) issue_one(ts, i); }
+                if constexpr (!(VXL_PIPE_ABL & 2)) {
 #pragma unroll
-                for (int r = i * VPS; r < (i + 1) * VPS; ++r) mx[qb] = fmaxf(mx[qb], s[qb][r]);
-            if constexpr (decltype(pv_c)::value) {
+                    for (int r = i * VPS; r < (i + 1) * VPS; ++r) {
+                        s[qb][r] = fmaf(s[qb][r], c2, nmc[qb]);
+                        mx[qb] = fmaxf(mx[qb], s[qb][r]);
+                    }
+                    if constexpr (PV) {
+                        // row sums of p[qb]: 8 dwords (2 steps x 4), 8 / NA per slice
+#pragma unroll
+                        for (int w = i * (8 / NA); w < (i + 1) * (8 / NA); ++w) {
+                            typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+                            const u32x4 pw = __builtin_bit_cast(u32x4, p[qb][w >> 2]);
+                            const int dw = w & 3;
+                            const unsigned one_dw = dw == 0 ? pw.x : dw == 1 ? pw.y : dw == 2 ? pw.z : pw.w;
+                            sum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, one_dw), ones, sum[qb], false);
+                        }
+                    }
+                } else if (i == 0) {
+                    mx[qb] = s[qb][0];
+                }
                 __builtin_amdgcn_sched_barrier(0);
-                a_cur = a_nxt;
             }
+            q.c = q.n;
+            q.n = nxt;
         }
-        mx[0] = fmaxf(mx[0], __shfl_xor(mx[0], 32));
-        mx[1] = fmaxf(mx[1], __shfl_xor(mx[1], 32));
-        raise(mx);
+        if constexpr (PV) {
+            l_run[0] += sum[0];
+            l_run[1] += sum[1];
+            // every row has its reference by now (set at the item's first half)
+            if (__builtin_amdgcn_ballot_w64(fmaxf(mx[0], mx[1]) > 8.f) != 0) raise(mx, s);
+        } else {
+            raise(mx, s);
+        }
         __builtin_amdgcn_sched_barrier(0);
     };
-    // Phase B: s_dst = K(32 keys) . Q^T in KS slices of two matrix instructions, with the
-    // exponentials of s_src -> p_dst (bf16, B-operand order) spread over the slices.
-    auto phase_b = [&](uint32_t tile, int kb, f32x16 (&s_dst)[2], const f32x16 (&s_src)[2], bf16x8 (&p_dst)[2][2]) {
-        constexpr int VPS = 16 / KS;                          // score registers per slice and row block (2 or 4)
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-        float mc[2], sum[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) mc[qb] = (m_run[qb] == -INFINITY ? 0.f : m_run[qb]) * c2;
-        bf16x8 a_cur = read_k<D>(ring, tile, koff, kb, 0), a_nxt;
+    // Phase B: s_dst = K(32 keys kb*32.. of the tile at tk) . Q^T in 2*KS slices of one matrix
+    // instruction, with the exponentials of x -> p_dst (bf16, B-operand order) spread over the
+    // slices.  The last slices request the first operands of the phase A that follows (tile tv, key
+    // block kbv).
+    auto phase_b = [&](uint32_t tk, int kb, f32x16 (&s_dst)[2], const f32x16 (&x)[2], bf16x8 (&p_dst)[2][2],
+                       OpQ& q, uint32_t tv, int kbv) {
+        constexpr int VPS = 16 / KS;                          // score registers per d step and row block (2 or 4)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            if (ks + 1 < KS) a_nxt = read_k<D>(ring, tile, koff, kb, ks + 1);
-            if (ks == 0) {
-                s_dst[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur, qreg[0][ks], zero16(), 0, 0, 0);
-                s_dst[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur, qreg[1][ks], zero16(), 0, 0, 0);
-            } else {
-                s_dst[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur, qreg[0][ks], s_dst[0], 0, 0, 0);
-                s_dst[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur, qreg[1][ks], s_dst[1], 0, 0, 0);
-            }
+            bf16x8 nxt;
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-                for (int r = ks * VPS; r < (ks + 1) * VPS; r += 2) {
-                    bf16x2 pr;
-                    pr[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s_src[qb][r], c2, -mc[qb]));
-                    pr[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s_src[qb][r + 1], c2, -mc[qb]));
-                    sum[qb][(r >> 1) & 1] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum[qb][(r >> 1) & 1], false);
-                    p_dst[qb][r >> 3][r & 7] = pr[0];
-                    p_dst[qb][r >> 3][(r & 7) + 1] = pr[1];
+            for (int qb = 0; qb < 2; ++qb) {
+                if (qb == 0) {
+                    if (ks + 2 < KS) nxt = read_k<D>(ring, tk, koff, kb, ks + 2);
+                    else nxt = read_vt<D>(ring, tv, voff, kbv, (ks + 2 - KS) / DB, (ks + 2 - KS) % DB);
                 }
-            __builtin_amdgcn_sched_barrier(0);
-            a_cur = a_nxt;
+                if (ks == 0) s_dst[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q.c, qreg[qb][ks], zero16(), 0, 0, 0);
+                else s_dst[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q.c, qreg[qb][ks], s_dst[qb], 0, 0, 0);
+                if constexpr (!(VXL_PIPE_ABL & 1)) {
+#pragma unroll
+                    for (int r = ks * VPS; r < (ks + 1) * VPS; r += 2) {
+                        p_dst[qb][r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(x[qb][r]);
+                        p_dst[qb][r >> 3][(r & 7) + 1] = (__bf16)__builtin_amdgcn_exp2f(x[qb][r + 1]);
+                    }
+                } else if (ks == 0) {
+                    asm volatile("" : "+v"(p_dst[qb][0]) : "v"(x[qb]));
+                    asm volatile("" : "+v"(p_dst[qb][1]));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            q.c = q.n;
+            q.n = nxt;
         }
-        l_run[0] += sum[0][0] + sum[0][1];
-        l_run[1] += sum[1][0] + sum[1][1];
-        __builtin_amdgcn_sched_barrier(0);
     };
     typedef std::integral_constant<bool, true> yes;
     typedef std::integral_constant<bool, false> no;
 
     int t = 0;
     if (n_pipe > 0) {
-        // first pipelined tile: nothing is owed to O yet
-        step_top(0);
-        // S(0, half 0)
+        // first pipelined tile: S(0, half 0) computed up front, nothing is owed to O yet
         {
-            bf16x8 a_cur = read_k<D>(ring, stage_of(0), koff, 0, 0);
+            const uint32_t tk = stage_of(0);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                bf16x8 a_nxt = a_cur;
-                if (ks + 1 < KS) a_nxt = read_k<D>(ring, stage_of(0), koff, 0, ks + 1);
+                const bf16x8 a = read_k<D>(ring, tk, koff, 0, ks);
                 if (ks == 0) {
-                    s0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur, qreg[0][ks], zero16(), 0, 0, 0);
-                    s0[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur, qreg[1][ks], zero16(), 0, 0, 0);
+                    s0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[0][ks], zero16(), 0, 0, 0);
+                    s0[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[1][ks], zero16(), 0, 0, 0);
                 } else {
-                    s0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur, qreg[0][ks], s0[0], 0, 0, 0);
-                    s0[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cur, qreg[1][ks], s0[1], 0, 0, 0);
+                    s0[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[0][ks], s0[0], 0, 0, 0);
+                    s0[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[1][ks], s0[1], 0, 0, 0);
                 }
-                a_cur = a_nxt;
             }
         }
-        phase_a(no(), 0u, 0, p1, s0);
-        phase_b(stage_of(0), 1, s1, s0, p0);
-        phase_a(yes(), stage_of(0), 0, p0, s1);
-        phase_b(stage_of(1), 0, s0, s1, p1);                  // (operands are whatever the stage holds if n_pipe == 1)
-        for (t = 1; t < n_pipe; ++t) {
-            step_top(t);
-            phase_a(yes(), stage_of(t - 1), 1, p1, s0);
-            phase_b(stage_of(t), 1, s1, s0, p0);
-            phase_a(yes(), stage_of(t), 0, p0, s1);
-            phase_b(stage_of(t + 1), 0, s0, s1, p1);
-        }
-        // the last half's product
+        OpQ q;
         {
-            const uint32_t tile = stage_of(n_pipe - 1);
+            const TileSrc ts = tile_src(min(2, n_t - 1));
+            phase_a(no(), yes(), 0u, 0, p1, s0, q, stage_of(0), 1, ts);
+        }
+        phase_b(stage_of(0), 1, s1, s0, p0, q, stage_of(0), 0);
+        phase_a(yes(), no(), stage_of(0), 0, p0, s1, q, stage_of(1), 0, TileSrc());
+        step_barrier();
+        phase_b(stage_of(1), 0, s0, s1, p1, q, stage_of(0), 1);
+#if VXL_PIPE_ABL & 32
+        unsigned long long pc[7] = {0, 0, 0, 0, 0, 0, 0};     // measurement build: cycles per phase
+#define VXL_TICK(k_) do { const unsigned long long n_ = clock64(); pc[k_] += n_ - tk_; tk_ = n_; } while (0)
+#else
+#define VXL_TICK(k_) do {} while (0)
+#endif
+        for (t = 1; t < n_pipe; ++t) {
+#if VXL_PIPE_ABL & 32
+            unsigned long long tk_ = clock64();
+#endif
+            const TileSrc ts = tile_src(min(t + 2, n_t - 1));
+            VXL_TICK(0);
+            phase_a(yes(), yes(), stage_of(t - 1), 1, p1, s0, q, stage_of(t), 1, ts);
+            VXL_TICK(1);
+            phase_b(stage_of(t), 1, s1, s0, p0, q, stage_of(t), 0);
+            VXL_TICK(2);
+            phase_a(yes(), no(), stage_of(t), 0, p0, s1, q, stage_of(t + 1), 0, ts);
+            VXL_TICK(3);
+            step_barrier();
+            VXL_TICK(4);
+            phase_b(stage_of(t + 1), 0, s0, s1, p1, q, stage_of(t), 1);
+            VXL_TICK(5);
+#if VXL_PIPE_ABL & 32
+            pc[6] += 1;
+#endif
+        }
+#if VXL_PIPE_ABL & 32
+        if (LSE && lane == 0)
+            for (int k_ = 0; k_ < 7; ++k_) atomicAdd((unsigned long long*)(LSE + (size_t)n_q_heads * n_tokens) + k_, pc[k_]);
+#endif
+#undef VXL_TICK
+        // the last half's product (its first two operands are in the queue)
+        {
+            const uint32_t tv = stage_of(n_pipe - 1);
+            float sum[2] = {0.f, 0.f};
 #pragma unroll
-            for (int jj = 0; jj < 2; ++jj)
+            for (int i = 0; i < NA; ++i) {
+                const int jj = i / DB, db = i % DB;
+                const bf16x8 a = i == 0 ? q.c : (i == 1 ? q.n : read_vt<D>(ring, tv, voff, 1, jj, db));
+                mfma_acc(o[0][db], a, p1[0][jj]);
+                mfma_acc(o[1][db], a, p1[1][jj]);
+            }
 #pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const bf16x8 a = read_vt<D>(ring, tile, voff, 1, jj, db);
-                    mfma_acc(o[0][db], a, p1[0][jj]);
-                    mfma_acc(o[1][db], a, p1[1][jj]);
-                }
+            for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                for (int st = 0; st < 2; ++st)
+#pragma unroll
+                    for (int dw = 0; dw < 4; ++dw) {
+                        bf16x2 pr;
+                        pr[0] = p1[qb][st][2 * dw];
+                        pr[1] = p1[qb][st][2 * dw + 1];
+                        sum[qb] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum[qb], false);
+                    }
+            l_run[0] += sum[0];
+            l_run[1] += sum[1];
         }
     }
     // the remaining steps: masked tiles one after the other, other tiles only pass through the ring
     for (; t < n_t; ++t) {
-        step_top(t);
+        issue(min(t + 2, n_t - 1));
         const bool own = t >= n_full && t < n_full + n_own;
         const bool mine = wave_rows && (own ? t < own_end : true);     // (not own => the ragged history tile)
-        if (!mine) continue;
+        if (!mine) { step_barrier(); continue; }
         const int key0 = own ? (t - n_full) * kKeyTile : n_full * kKeyTile;
         const uint32_t tile = stage_of(t);
 #pragma unroll
@@ -382,24 +493,23 @@ __global__ __launch_bounds__(256, 1) void prefill_pipe_kernel(
             for (int qb = 0; qb < 2; ++qb) {
                 // tile-relative key kt is visible iff kt <= lim
                 const int lim = own ? wrow0 + sg.back + qb * 32 + l32 - key0 : sg.ctx_len - key0 - 1;
+                const float nmc = m2[qb] == -INFINITY ? 0.f : -m2[qb];
+                mx[qb] = -INFINITY;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[qb][r] = acc_key(kb, r, hi) <= lim ? s[qb][r] : -INFINITY;
-                mx[qb] = s[qb][0];
-#pragma unroll
-                for (int r = 1; r < 16; ++r) mx[qb] = fmaxf(mx[qb], s[qb][r]);
-                mx[qb] = fmaxf(mx[qb], __shfl_xor(mx[qb], 32));
+                for (int r = 0; r < 16; ++r) {
+                    s[qb][r] = acc_key(kb, r, hi) <= lim ? fmaf(s[qb][r], c2, nmc) : -INFINITY;
+                    mx[qb] = fmaxf(mx[qb], s[qb][r]);
+                }
             }
-            raise(mx);
-            const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+            if (__builtin_amdgcn_ballot_w64(wants_raise(mx)) != 0) raise(mx, s);
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
-                const float mc = (m_run[qb] == -INFINITY ? 0.f : m_run[qb]) * c2;
                 float sum = 0.f;
 #pragma unroll
                 for (int r = 0; r < 16; r += 2) {
                     bf16x2 pr;
-                    pr[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[qb][r], c2, -mc));
-                    pr[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[qb][r + 1], c2, -mc));
+                    pr[0] = (__bf16)__builtin_amdgcn_exp2f(s[qb][r]);
+                    pr[1] = (__bf16)__builtin_amdgcn_exp2f(s[qb][r + 1]);
                     sum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum, false);
                     p0[qb][r >> 3][r & 7] = pr[0];
                     p0[qb][r >> 3][(r & 7) + 1] = pr[1];
@@ -415,6 +525,7 @@ __global__ __launch_bounds__(256, 1) void prefill_pipe_kernel(
                     mfma_acc(o[1][db], a, p0[1][jj]);
                 }
         }
+        step_barrier();
     }
     wait_vmcnt<0>();                                          // drain the refills before the next item
 
@@ -438,7 +549,7 @@ __global__ __launch_bounds__(256, 1) void prefill_pipe_kernel(
                     *(bf16x4*)(obase + ooff + (db * 32 + rq * 8) * 2) = v;
                 }
             if (LSE && hi == 0)
-                (LSE + (size_t)h * n_tokens + sg.q_start)[q_off] = m_run[qb] * scale + logf(l_tot);
+                (LSE + (size_t)h * n_tokens + sg.q_start)[q_off] = m2[qb] * kLn2 + logf(l_tot);
         }
     }
     __syncthreads();                    // every wave is done with this item's tiles; next_slot[par] is written

@@ -225,7 +225,8 @@ def debug_force_simple(on: bool) -> None:
 
 def debug_prefill_variant(variant: int) -> None:
     """Cross-check and measurement only: 0 = the streaming kernel (default); 1, 2 = the 4-wave
-    register-staged kernel with one or two 32-row blocks per wave."""
+    register-staged kernel with one or two 32-row blocks per wave; 3 = the software-pipelined
+    4-wave kernel with 64 rows per wave."""
     lib().vxl_debug_prefill_variant(int(variant))
 
 

@@ -45,7 +45,7 @@ TINY_CASES = [
 
 
 @pytest.mark.parametrize("case", TINY_CASES, ids=lambda c: f"{c[0]}-h{c[1]}-d{c[3]}-p{c[4]}-s{c[8]}")
-@pytest.mark.parametrize("qb", [0, 1, 2])
+@pytest.mark.parametrize("qb", [0, 1, 2, 3])
 def test_prefill_ragged_layouts(case, qb):
     dtype, hq, hkv, d, p, nc, lo, hi, seed = case
     if dtype == "f32" and qb != 0:
@@ -83,7 +83,7 @@ def test_prefill_edge_layouts_bf16():
         assert_close(got, oracle_prefill(q, k, v, lay), "bf16", what="edge layout")
 
 
-@pytest.mark.parametrize("qb", [0, 1, 2])
+@pytest.mark.parametrize("qb", [0, 1, 2, 3])
 def test_prefill_medium_bf16_sharp_softmax(qb):
     """Several 256-token chunks at GQA 14/2, with logits of std ~3 so that the running maximum
     moves and the rescaling path is exercised."""
@@ -135,7 +135,7 @@ def sample_rows(lay, rng, n_full_chunks=3):
     return np.array(sorted(rows), dtype=np.int64)
 
 
-@pytest.mark.parametrize("qb", [0, 1, 2])
+@pytest.mark.parametrize("qb", [0, 1, 2, 3])
 def test_prefill_config1_sampled_rows(qb):
     w = wl.WORKLOADS["config1"]
     lay = wl.make_layout(w)
@@ -184,7 +184,7 @@ WINDOW_CASES = [
 
 
 @pytest.mark.parametrize("case", WINDOW_CASES, ids=lambda c: f"{c[0]}-d{c[3]}-p{c[4]}-w{c[8]}")
-@pytest.mark.parametrize("qb", [0, 1, 2])
+@pytest.mark.parametrize("qb", [0, 1, 2, 3])
 def test_prefill_sliding_window(case, qb):
     dtype, hq, hkv, d, p, nc, lo, hi, window, seed = case
     if dtype == "f32" and qb != 0:
