@@ -23,10 +23,12 @@ brute force on tiny inputs -- no function is pinned to a value printed in the pa
 """
 from .sets import allowed_mask, allowed_keys, allowed_pair_count, mixed_source_index
 from .prefill import prefill_def, prefill_blk
-from .bilevel import chunk_scores, chunk_scores_mass, select_topk, gather_bilevel, decode_mixed, decode_lse
+from .bilevel import (chunk_scores, chunk_scores_mass, select_topk, gather_bilevel, decode_mixed, decode_lse,
+                      pool_groups, pool_sparse_kv, gather_bilevel_pooled)
 
 __all__ = [
     "allowed_mask", "allowed_keys", "allowed_pair_count", "mixed_source_index",
     "prefill_def", "prefill_blk",
     "chunk_scores", "chunk_scores_mass", "select_topk", "gather_bilevel", "decode_mixed", "decode_lse",
+    "pool_groups", "pool_sparse_kv", "gather_bilevel_pooled",
 ]

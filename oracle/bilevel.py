@@ -133,3 +133,67 @@ def decode_lse(qd, kmix, vmix, mix_len, scale=None):
 
 def decode_mixed(qd, kmix, vmix, mix_len, scale=None):
     return decode_lse(qd, kmix, vmix, mix_len, scale)[0]
+
+
+# ---------------------------------------------------------------------------------------------
+# Pooled sparse KVs ("Bi-level KVs Decoding": the dense KVs are cut into chunks and a pooling
+# operation on each chunk yields its sparse KVs).  The paper gives neither window nor stride; the
+# reading taken here: a chunk of len_c rows that is to be represented by s_c sparse rows is cut
+# into s_c consecutive groups, group m = rows [floor(m*len_c/s_c), floor((m+1)*len_c/s_c)), and
+# sparse row m is the arithmetic mean of the group's rows (K and V alike) -- plain average pooling
+# with window len_c/s_c when that divides.  s_c comes from the CSR offsets of the layout.
+# ---------------------------------------------------------------------------------------------
+def pool_groups(length, count):
+    """[(lo, hi)] of the `count` consecutive groups that partition range(length)."""
+    return [((m * length) // count, ((m + 1) * length) // count) for m in range(count)]
+
+
+def pool_sparse_kv(k, v, chunk_bounds, sparse_offsets):
+    """(ksp, vsp) float64 [Hkv, S_total, D]: row sparse_offsets[c] + m is the mean of group m of
+    chunk c.  (The caller rounds to the storage dtype.)"""
+    b = np.asarray(chunk_bounds, dtype=np.int64)
+    off = np.asarray(sparse_offsets, dtype=np.int64)
+    hkv, _, d = k.shape
+    ksp = np.zeros((hkv, int(off[-1]), d), dtype=np.float64)
+    vsp = np.zeros_like(ksp)
+    for c in range(len(b) - 1):
+        cnt = int(off[c + 1] - off[c])
+        for m, (lo, hi) in enumerate(pool_groups(int(b[c + 1] - b[c]), cnt)):
+            ksp[:, off[c] + m] = np.asarray(k[:, b[c] + lo:b[c] + hi], dtype=np.float64).mean(axis=1)
+            vsp[:, off[c] + m] = np.asarray(v[:, b[c] + lo:b[c] + hi], dtype=np.float64).mean(axis=1)
+    return ksp, vsp
+
+
+def gather_bilevel_pooled(k, v, ksp, vsp, dense_mask, n_prefix, chunk_bounds, sparse_offsets, l_cap=None):
+    """Mixed KV with pooled sparse rows: the prefix, then per chunk its dense rows (mask 1) or its
+    pooled rows (mask 0).  k, v [Hkv, N, D] and ksp, vsp [Hkv, S_total, D] in one dtype, copied bit
+    for bit.  Returns (kmix, vmix [B, Hkv, Lcap, D], mix_len [B] int32, src_idx [B, Lcap] int32:
+    the token id of a dense row, -1 - (pooled row index) of a pooled row, padding -(2**31))."""
+    dense_mask = np.asarray(dense_mask)
+    b = np.asarray(chunk_bounds, dtype=np.int64)
+    off = np.asarray(sparse_offsets, dtype=np.int64)
+    bsz = dense_mask.shape[0]
+    srcs = []
+    for bi in range(bsz):
+        parts = [np.arange(n_prefix, dtype=np.int64)]
+        for c in range(len(b) - 1):
+            parts.append(np.arange(b[c], b[c + 1], dtype=np.int64) if dense_mask[bi, c]
+                         else -1 - np.arange(off[c], off[c + 1], dtype=np.int64))
+        srcs.append(np.concatenate(parts))
+    lens = np.array([len(s) for s in srcs], dtype=np.int32)
+    l_cap = int(lens.max()) if l_cap is None else int(l_cap)
+    assert l_cap >= lens.max()
+    hkv, _, d = k.shape
+    kmix = np.zeros((bsz, hkv, l_cap, d), dtype=k.dtype)
+    vmix = np.zeros((bsz, hkv, l_cap, d), dtype=v.dtype)
+    src_idx = np.full((bsz, l_cap), -(2 ** 31), dtype=np.int64)
+    for bi, s in enumerate(srcs):
+        dense = s >= 0
+        rows = np.flatnonzero(dense)
+        kmix[bi][:, rows] = k[:, s[dense]]
+        vmix[bi][:, rows] = v[:, s[dense]]
+        rows = np.flatnonzero(~dense)
+        kmix[bi][:, rows] = ksp[:, -1 - s[~dense]]
+        vmix[bi][:, rows] = vsp[:, -1 - s[~dense]]
+        src_idx[bi, :len(s)] = s
+    return kmix, vmix, lens, src_idx.astype(np.int64)

@@ -309,3 +309,100 @@ def test_lse_merge_identity():
     # LSE against its definition
     s = (qd[0, 0, 1].astype(np.float64) @ kmix[0, 0].astype(np.float64).T) / math.sqrt(8)
     assert abs(math.log(sum(math.exp(x) for x in s)) - l[0, 0, 1]) < 1e-12
+
+
+# --------------------------------------------------------------------------------- pooled sparse KVs
+def _pool_fixture():
+    rows = {}
+    for ln in open(os.path.join(GOLDEN, "pooled_kv_small.txt")):
+        if ln.startswith("#") or not ln.strip():
+            continue
+        i, vals = ln.split(":")
+        rows[int(i)] = [float(x) for x in vals.split()]
+    return rows
+
+
+def test_pooled_kv_hand_worked_fixture():
+    rows = _pool_fixture()
+    bounds, soff = [1, 5, 12, 14], [0, 2, 5, 7]
+    k = np.stack([np.arange(14.0), 10.0 * np.arange(14.0)], axis=1)[None]        # [1, 14, 2]
+    ksp, vsp = oracle.pool_sparse_kv(k, -k, bounds, soff)
+    assert ksp.shape == (1, 7, 2)
+    for i, want in rows.items():
+        assert np.array_equal(ksp[0, i], np.array(want)), i
+    assert np.array_equal(vsp, -ksp)
+
+
+def test_pool_groups_partition_the_chunk():
+    for length in range(1, 40):
+        for count in range(1, length + 1):
+            g = oracle.pool_groups(length, count)
+            assert len(g) == count and g[0][0] == 0 and g[-1][1] == length
+            sizes = [hi - lo for lo, hi in g]
+            assert all(g[i][1] == g[i + 1][0] for i in range(count - 1))
+            assert min(sizes) >= 1 and max(sizes) - min(sizes) <= 1              # as even as it gets
+            if length % count == 0:
+                assert set(sizes) == {length // count}                            # plain average pooling
+
+
+def test_pooled_kv_special_cases_and_brute_force():
+    rng = np.random.default_rng(81)
+    lay = wl.random_layout(rng, 3, 6, 1, 23, allow_empty_kept=False)
+    n, hkv, d = lay.n_tokens, 2, 4
+    k = rng.standard_normal((hkv, n, d))
+    v = rng.standard_normal((hkv, n, d))
+    b, off = lay.chunk_bounds, lay.sparse_offsets
+    ksp, vsp = oracle.pool_sparse_kv(k, v, b, off)
+    # brute force with python loops over tokens (nothing shared with the slicing code)
+    for c in range(lay.n_chunks):
+        ln, cnt = int(b[c + 1] - b[c]), int(off[c + 1] - off[c])
+        for m in range(cnt):
+            # membership by the group bounds: j in [floor(m*ln/cnt), floor((m+1)*ln/cnt))
+            toks = [int(b[c]) + j for j in range(ln) if (m * ln) // cnt <= j < ((m + 1) * ln) // cnt]
+            for g in range(hkv):
+                for e in range(d):
+                    want = sum(k[g, t, e] for t in toks) / len(toks)
+                    assert abs(ksp[g, off[c] + m, e] - want) < 1e-12
+                    want = sum(v[g, t, e] for t in toks) / len(toks)
+                    assert abs(vsp[g, off[c] + m, e] - want) < 1e-12
+    # as many sparse rows as dense rows: pooling is the identity
+    full_off = np.concatenate([[0], np.cumsum(np.diff(b))])
+    ksp, vsp = oracle.pool_sparse_kv(k, v, b, full_off)
+    assert np.array_equal(ksp, k[:, lay.n_prefix:]) and np.array_equal(vsp, v[:, lay.n_prefix:])
+    # one sparse row per chunk: the chunk mean (the summary the mean-logit score is built on)
+    one_off = np.arange(lay.n_chunks + 1)
+    ksp, _ = oracle.pool_sparse_kv(k, v, b, one_off)
+    for c in range(lay.n_chunks):
+        assert np.allclose(ksp[:, c], k[:, b[c]:b[c + 1]].mean(axis=1), rtol=0, atol=1e-12)
+    # constant rows stay constant; pooling is linear
+    kc = np.broadcast_to(np.array([1.0, -2.0, 0.5, 4.0]), (hkv, n, d))
+    ksp, _ = oracle.pool_sparse_kv(kc, kc, b, off)
+    assert np.array_equal(ksp, np.broadcast_to(kc[0, 0], ksp.shape))
+    a1, _ = oracle.pool_sparse_kv(k, v, b, off)
+    a2, _ = oracle.pool_sparse_kv(v, k, b, off)
+    a3, _ = oracle.pool_sparse_kv(2.0 * k - 3.0 * v, k, b, off)
+    assert np.allclose(a3, 2.0 * a1 - 3.0 * a2, rtol=0, atol=1e-12)
+
+
+def test_pooled_gather_structure():
+    rng = np.random.default_rng(82)
+    lay = wl.random_layout(rng, 2, 5, 2, 9, allow_empty_kept=False)
+    n, hkv, d = lay.n_tokens, 1, 3
+    k = rng.standard_normal((hkv, n, d))
+    v = rng.standard_normal((hkv, n, d))
+    b, off = lay.chunk_bounds, lay.sparse_offsets
+    ksp, vsp = oracle.pool_sparse_kv(k, v, b, off)
+    masks = np.array([[0] * 5, [1] * 5, [1, 0, 0, 1, 0]], dtype=np.uint8)
+    kmix, vmix, lens, src = oracle.gather_bilevel_pooled(k, v, ksp, vsp, masks, lay.n_prefix, b, off)
+    assert lens[0] == lay.n_prefix + off[-1] and lens[1] == n
+    assert np.array_equal(kmix[1, :, :n], k) and np.array_equal(src[1, :n], np.arange(n))     # all dense: the cache itself
+    assert np.array_equal(kmix[0, :, lay.n_prefix:lens[0]], ksp)                              # all sparse: prefix + pooled rows
+    assert np.array_equal(src[0, lay.n_prefix:lens[0]], -1 - np.arange(off[-1]))
+    # mixed: same lengths and the same dense rows as the index-selection gather for the same mask
+    _, _, lens_sel, src_sel = oracle.gather_bilevel(k, v, masks, lay.n_prefix, b, off, lay.sparse_idx)
+    assert np.array_equal(lens, lens_sel)
+    s2 = src[2, :lens[2]]
+    dense_rows = s2 >= 0
+    assert np.array_equal(s2[dense_rows], src_sel[2, :lens[2]][dense_rows])
+    assert np.array_equal(vmix[2][:, :lens[2]][:, dense_rows], v[:, s2[dense_rows]])
+    assert np.array_equal(vmix[2][:, :lens[2]][:, ~dense_rows], vsp[:, -1 - s2[~dense_rows]])
