@@ -191,6 +191,35 @@ vxl_status vxl_gather_bilevel_kv(const vxl_layout* layout, const vxl_attn_desc* 
                                  void* workspace, size_t workspace_bytes, vxl_stream stream);
 
 /*
+ * Pooled sparse KVs ("Bi-level KVs Decoding": the dense KVs are chunked and a pooling operation on
+ * every chunk yields its sparse KVs; the paper gives neither window nor stride).  Chunk c, which
+ * the layout represents by s_c = sparse_offsets[c+1] - sparse_offsets[c] sparse rows, is cut into
+ * s_c consecutive groups, group m = rows [floor(m*len_c/s_c), floor((m+1)*len_c/s_c)) of the
+ * chunk, and pooled row sparse_offsets[c] + m is the arithmetic mean of the group's rows (K and V
+ * alike; fp32 sums in row order, rounded once to the storage dtype).  The kept-token ids of the
+ * layout are not read, only their counts.
+ *   K, V      device dense [n_kv_heads, n_tokens, head_dim]
+ *   Ksp, Vsp  device [n_kv_heads, S_total, head_dim] (written), S_total = sparse_offsets[n_chunks]
+ * No workspace.  Errors: VXL_ERR_INVALID_ARG (null / misaligned / aliasing buffers),
+ * VXL_ERR_UNSUPPORTED, VXL_ERR_HIP.
+ */
+vxl_status vxl_pool_sparse_kv(const vxl_layout* layout, const vxl_attn_desc* desc, const void* K,
+                              const void* V, void* Ksp, void* Vsp, vxl_stream stream);
+
+/*
+ * vxl_gather_bilevel_kv with pooled sparse KVs: a chunk that is not dense contributes its pooled
+ * rows Ksp/Vsp[:, sparse_offsets[c] .. sparse_offsets[c+1]) instead of its kept rows.  Lengths,
+ * order and capacity are those of vxl_gather_bilevel_kv; src_idx (if given) holds the token id of
+ * a dense row and -1 - (pooled row index) of a pooled row.
+ */
+vxl_status vxl_gather_bilevel_kv_pooled(const vxl_layout* layout, const vxl_attn_desc* desc,
+                                        const void* K, const void* V, const void* Ksp,
+                                        const void* Vsp, const uint8_t* dense_mask, int32_t batch,
+                                        void* Kmix, void* Vmix, int32_t l_cap, int32_t* mix_len,
+                                        int32_t* src_idx, void* workspace, size_t workspace_bytes,
+                                        vxl_stream stream);
+
+/*
  * GQA decode attention over the mixed KV set ("Bi-level KVs Decoding"): every query token
  * attends to rows 0..mix_len[b]-1 of its mixed set; no mask among the query tokens.  Split-KV
  * partial results are merged by log-sum-exp in a fixed order (deterministic).

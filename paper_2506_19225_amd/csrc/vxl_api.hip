@@ -412,8 +412,40 @@ vxl_status vxl_gather_bilevel_kv(const vxl_layout* L, const vxl_attn_desc* d, co
     if (l_cap < vxl_mixed_kv_capacity(L, 0)) return VXL_ERR_INVALID_ARG;
     const size_t need = vxl_workspace_bytes(VXL_OP_GATHER, L, d, batch, 0, 0);
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return VXL_ERR_WORKSPACE;
-    return launch_gather(L, d, K, V, dense_mask, batch, Kmix, Vmix, l_cap, mix_len, src_idx,
+    return launch_gather(L, d, K, V, nullptr, nullptr, dense_mask, batch, Kmix, Vmix, l_cap, mix_len, src_idx,
                          (int32_t*)workspace, (hipStream_t)stream);
+}
+
+vxl_status vxl_pool_sparse_kv(const vxl_layout* L, const vxl_attn_desc* d, const void* K, const void* V,
+                              void* Ksp, void* Vsp, vxl_stream stream) {
+    vxl_status st;
+    if (!L) return VXL_ERR_INVALID_ARG;
+    if (!desc_ok(d, &st)) return st;
+    if (!K || !V || !aligned16(K) || !aligned16(V)) return VXL_ERR_INVALID_ARG;
+    if (L->s_total > 0 && (!Ksp || !Vsp || !aligned16(Ksp) || !aligned16(Vsp))) return VXL_ERR_INVALID_ARG;
+    if (Ksp == K || Ksp == V || Vsp == K || Vsp == V || (Ksp && Ksp == Vsp)) return VXL_ERR_INVALID_ARG;
+    return launch_pool_sparse(L, d, K, V, Ksp, Vsp, (hipStream_t)stream);
+}
+
+vxl_status vxl_gather_bilevel_kv_pooled(const vxl_layout* L, const vxl_attn_desc* d, const void* K,
+                                        const void* V, const void* Ksp, const void* Vsp,
+                                        const uint8_t* dense_mask, int32_t batch, void* Kmix, void* Vmix,
+                                        int32_t l_cap, int32_t* mix_len, int32_t* src_idx, void* workspace,
+                                        size_t workspace_bytes, vxl_stream stream) {
+    vxl_status st;
+    if (!L) return VXL_ERR_INVALID_ARG;
+    if (!desc_ok(d, &st)) return st;
+    if (!K || !V || !Kmix || !Vmix || !mix_len || batch <= 0) return VXL_ERR_INVALID_ARG;
+    if (L->n_chunks > 0 && !dense_mask) return VXL_ERR_INVALID_ARG;
+    if (L->s_total > 0 && (!Ksp || !Vsp || !aligned16(Ksp) || !aligned16(Vsp))) return VXL_ERR_INVALID_ARG;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(Kmix) || !aligned16(Vmix)) return VXL_ERR_INVALID_ARG;
+    if (l_cap < vxl_mixed_kv_capacity(L, 0)) return VXL_ERR_INVALID_ARG;
+    const size_t need = vxl_workspace_bytes(VXL_OP_GATHER, L, d, batch, 0, 0);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return VXL_ERR_WORKSPACE;
+    // (a layout without sparse rows never reads the pooled buffers; the kernel takes the pooled
+    // path only when they are given)
+    return launch_gather(L, d, K, V, L->s_total > 0 ? Ksp : nullptr, L->s_total > 0 ? Vsp : nullptr, dense_mask,
+                         batch, Kmix, Vmix, l_cap, mix_len, src_idx, (int32_t*)workspace, (hipStream_t)stream);
 }
 
 vxl_status vxl_bilevel_decode(const vxl_attn_desc* d, const void* Qd, int32_t batch,

@@ -238,6 +238,57 @@ __global__ __launch_bounds__(256) void topk_from_scores_kernel(const float* __re
 }
 
 // ------------------------------------------------------------------------------------------
+// Pooled sparse KVs: chunk c (len rows) is cut into cnt = soff[c+1] - soff[c] consecutive groups,
+// group m = rows [floor(m*len/cnt), floor((m+1)*len/cnt)); pooled row soff[c] + m is the mean of
+// the group's rows, K and V alike.  LPR lanes per pooled row (a 16-byte piece each), fp32 sums in
+// row order, one division, one rounding to the storage dtype.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void st_round(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_round(uint16_t* p, float v) {
+    uint32_t b = __float_as_uint(v);
+    if ((b & 0x7fffffffu) > 0x7f800000u) { *p = 0x7fc0; return; }
+    b += 0x7fffu + ((b >> 16) & 1u);
+    *p = (uint16_t)(b >> 16);
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void pool_sparse_kernel(const T* __restrict__ K, const T* __restrict__ V,
+                                                          const int32_t* __restrict__ bounds,
+                                                          const int32_t* __restrict__ soff, int n_chunks,
+                                                          int n_tokens, int s_total, T* __restrict__ Ksp,
+                                                          T* __restrict__ Vsp) {
+    constexpr int EPC = 16 / (int)sizeof(T);        // elements per 16-byte piece
+    constexpr int LPR = D / EPC;                    // lanes per row
+    constexpr int ROWS = 256 / LPR;
+    const int r = blockIdx.x * ROWS + threadIdx.x / LPR, part = threadIdx.x % LPR, g = blockIdx.y;
+    if (r >= s_total) return;
+    int c = 0, hi_c = n_chunks;                     // last chunk with soff[c] <= r (its range holds r)
+    while (hi_c - c > 1) {
+        const int mid = (c + hi_c) >> 1;
+        if (soff[mid] <= r) c = mid; else hi_c = mid;
+    }
+    const long long len = bounds[c + 1] - bounds[c], cnt = soff[c + 1] - soff[c], m = r - soff[c];
+    const int lo = bounds[c] + (int)((m * len) / cnt), hi = bounds[c] + (int)(((m + 1) * len) / cnt);
+    float ak[EPC], av[EPC];
+#pragma unroll
+    for (int i = 0; i < EPC; ++i) ak[i] = av[i] = 0.f;
+    const uint4* kp = (const uint4*)(K + (size_t)g * n_tokens * D) + part;
+    const uint4* vp = (const uint4*)(V + (size_t)g * n_tokens * D) + part;
+    for (int t = lo; t < hi; ++t) {
+        const uint4 kq = kp[(size_t)t * LPR], vq = vp[(size_t)t * LPR];
+        const T* ke = (const T*)&kq;
+        const T* ve = (const T*)&vq;
+#pragma unroll
+        for (int i = 0; i < EPC; ++i) { ak[i] += ld(ke + i); av[i] += ld(ve + i); }
+    }
+    const float n = (float)(hi - lo);
+    T* ko = Ksp + ((size_t)g * s_total + r) * D + part * EPC;
+    T* vo = Vsp + ((size_t)g * s_total + r) * D + part * EPC;
+#pragma unroll
+    for (int i = 0; i < EPC; ++i) { st_round(ko + i, ak[i] / n); st_round(vo + i, av[i] / n); }
+}
+
+// ------------------------------------------------------------------------------------------
 // Gather.  Step 1 (one block per query): exclusive scan of the rows every chunk contributes
 // (its length if dense, its kept count if sparse) -> dst_off[b, 0..C], mix_len[b].
 // Step 2: every group of LPR lanes copies one mixed row (all kv heads, K and V) with 16-byte
@@ -285,7 +336,8 @@ __global__ __launch_bounds__(256) void gather_copy_kernel(
     const uint4* __restrict__ K, const uint4* __restrict__ V, const uint8_t* __restrict__ dense_mask,
     const int32_t* __restrict__ bounds, const int32_t* __restrict__ soff, const int32_t* __restrict__ sidx,
     const int32_t* __restrict__ dst_off, int n_chunks, int n_prefix, int n_tokens, int n_kv_heads, int l_cap,
-    uint4* __restrict__ Kmix, uint4* __restrict__ Vmix, int32_t* __restrict__ src_idx) {
+    uint4* __restrict__ Kmix, uint4* __restrict__ Vmix, int32_t* __restrict__ src_idx,
+    const uint4* __restrict__ Ksp, const uint4* __restrict__ Vsp, int s_total) {
     constexpr int LPR = ROW_BYTES / 16;                       // lanes per row
     constexpr int ROWS = 256 / LPR;                           // rows per block pass
     const int b = blockIdx.y;
@@ -294,7 +346,7 @@ __global__ __launch_bounds__(256) void gather_copy_kernel(
     const int r = blockIdx.x * ROWS + threadIdx.x / LPR;
     const int part = threadIdx.x % LPR;
     if (r >= len) return;
-    int src;
+    int src;                                                  // token id, or -1 - pooled row
     if (r < n_prefix) {
         src = r;
     } else {
@@ -304,14 +356,19 @@ __global__ __launch_bounds__(256) void gather_copy_kernel(
             if (off[mid] <= r) lo = mid; else hi = mid;
         }
         const int o = r - off[lo];
-        src = dense_mask[(size_t)b * n_chunks + lo] ? bounds[lo] + o : sidx[soff[lo] + o];
+        if (dense_mask[(size_t)b * n_chunks + lo]) src = bounds[lo] + o;
+        else src = Ksp ? -1 - (soff[lo] + o) : sidx[soff[lo] + o];
     }
     if (src_idx && part == 0) src_idx[(size_t)b * l_cap + r] = src;
+    const uint4* ks = src >= 0 ? K : Ksp;
+    const uint4* vs = src >= 0 ? V : Vsp;
+    const size_t rows = src >= 0 ? (size_t)n_tokens : (size_t)s_total;
+    const size_t row = src >= 0 ? (size_t)src : (size_t)(-1 - src);
     for (int g = 0; g < n_kv_heads; ++g) {
-        const size_t s_off = ((size_t)g * n_tokens + src) * LPR + part;
+        const size_t s_off = (g * rows + row) * LPR + part;
         const size_t d_off = (((size_t)b * n_kv_heads + g) * l_cap + r) * LPR + part;
-        const uint4 kv = K[s_off];
-        const uint4 vv = V[s_off];
+        const uint4 kv = ks[s_off];
+        const uint4 vv = vs[s_off];
         Kmix[d_off] = kv;
         Vmix[d_off] = vv;
     }
@@ -362,9 +419,26 @@ vxl_status launch_topk_from_scores(const vxl_layout* L, const float* scores, int
     return VXL_OK;
 }
 
+vxl_status launch_pool_sparse(const vxl_layout* L, const vxl_attn_desc* d, const void* K, const void* V,
+                              void* Ksp, void* Vsp, hipStream_t s) {
+    if (L->s_total == 0) return VXL_OK;
+    const int epc = d->dtype == VXL_BF16 ? 8 : 4;
+    const int rows = 256 / (d->head_dim / epc);
+    const dim3 grid((L->s_total + rows - 1) / rows, d->n_kv_heads), block(256);
+#define VXL_LAUNCH(T, D)                                                                            \
+    hipLaunchKernelGGL((pool_sparse_kernel<T, D>), grid, block, 0, s, (const T*)K, (const T*)V,      \
+                       L->d_bounds, L->d_soff, L->n_chunks, L->n_tokens, L->s_total, (T*)Ksp, (T*)Vsp)
+    if (d->dtype == VXL_F32) { if (d->head_dim == 64) VXL_LAUNCH(float, 64); else VXL_LAUNCH(float, 128); }
+    else { if (d->head_dim == 64) VXL_LAUNCH(uint16_t, 64); else VXL_LAUNCH(uint16_t, 128); }
+#undef VXL_LAUNCH
+    VXL_HIP_TRY(hipGetLastError());
+    return VXL_OK;
+}
+
 vxl_status launch_gather(const vxl_layout* L, const vxl_attn_desc* d, const void* K, const void* V,
-                         const uint8_t* dense_mask, int batch, void* Kmix, void* Vmix, int l_cap,
-                         int32_t* mix_len, int32_t* src_idx, int32_t* ws_offsets, hipStream_t s) {
+                         const void* Ksp, const void* Vsp, const uint8_t* dense_mask, int batch, void* Kmix,
+                         void* Vmix, int l_cap, int32_t* mix_len, int32_t* src_idx, int32_t* ws_offsets,
+                         hipStream_t s) {
     hipLaunchKernelGGL(gather_scan_kernel, dim3(batch), dim3(256), 0, s, dense_mask, L->d_bounds,
                        L->d_soff, L->n_chunks, L->n_prefix, l_cap, ws_offsets, mix_len);
     VXL_HIP_TRY(hipGetLastError());
@@ -376,7 +450,8 @@ vxl_status launch_gather(const vxl_layout* L, const vxl_attn_desc* d, const void
         hipLaunchKernelGGL((gather_copy_kernel<RB>), grid, dim3(256), 0, s, (const uint4*)K,       \
                            (const uint4*)V, dense_mask, L->d_bounds, L->d_soff, L->d_sidx,         \
                            ws_offsets, L->n_chunks, L->n_prefix, L->n_tokens, d->n_kv_heads, l_cap, \
-                           (uint4*)Kmix, (uint4*)Vmix, src_idx);                                   \
+                           (uint4*)Kmix, (uint4*)Vmix, src_idx, (const uint4*)Ksp,                 \
+                           (const uint4*)Vsp, L->s_total);                                         \
     } while (0)
     if (row_bytes == 128) VXL_LAUNCH(128);
     else if (row_bytes == 256) VXL_LAUNCH(256);

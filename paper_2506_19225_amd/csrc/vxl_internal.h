@@ -126,9 +126,13 @@ vxl_status launch_score_mass(const vxl_layout* L, const vxl_attn_desc* d, float 
                              int batch, int T, const void* K, float* scores, void* ws, bool force_simple,
                              hipStream_t s);
 
+// Ksp / Vsp: pooled sparse rows [Hkv, S_total, D] read instead of the kept rows, or null
 vxl_status launch_gather(const vxl_layout* L, const vxl_attn_desc* d, const void* K, const void* V,
-                         const uint8_t* dense_mask, int batch, void* Kmix, void* Vmix, int l_cap,
-                         int32_t* mix_len, int32_t* src_idx, int32_t* ws_offsets, hipStream_t s);
+                         const void* Ksp, const void* Vsp, const uint8_t* dense_mask, int batch, void* Kmix,
+                         void* Vmix, int l_cap, int32_t* mix_len, int32_t* src_idx, int32_t* ws_offsets,
+                         hipStream_t s);
+vxl_status launch_pool_sparse(const vxl_layout* L, const vxl_attn_desc* d, const void* K, const void* V,
+                              void* Ksp, void* Vsp, hipStream_t s);
 
 // ---- decode ----
 struct DecodePlan {

@@ -71,6 +71,10 @@ def lib() -> C.CDLL:
     L.vxl_chunk_score_topk_mass.argtypes = [vp, dp, vp, i32, i32, vp, i32, vp, vp, vp, vp, sz, vp]
     L.vxl_gather_bilevel_kv.restype = C.c_int
     L.vxl_gather_bilevel_kv.argtypes = [vp, dp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, sz, vp]
+    L.vxl_pool_sparse_kv.restype = C.c_int
+    L.vxl_pool_sparse_kv.argtypes = [vp, dp, vp, vp, vp, vp, vp]
+    L.vxl_gather_bilevel_kv_pooled.restype = C.c_int
+    L.vxl_gather_bilevel_kv_pooled.argtypes = [vp, dp, vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, sz, vp]
     L.vxl_bilevel_decode.restype = C.c_int
     L.vxl_bilevel_decode.argtypes = [dp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     L.vxl_debug_force_simple.argtypes = [C.c_int]
@@ -205,6 +209,24 @@ def gather_bilevel_kv(layout: Layout, desc: AttnDesc, k, v, dense_mask, kmix, vm
                                      _ptr(workspace), workspace.numel() if workspace is not None else 0,
                                      _stream(stream))
     _check(st, "vxl_gather_bilevel_kv")
+
+
+def pool_sparse_kv(layout: Layout, desc: AttnDesc, k, v, ksp, vsp, stream=None):
+    """vxl_pool_sparse_kv: k/v [Hkv,N,D] -> ksp/vsp [Hkv,S_total,D]."""
+    st = lib().vxl_pool_sparse_kv(layout.handle, C.byref(desc), _ptr(k), _ptr(v), _ptr(ksp), _ptr(vsp),
+                                  _stream(stream))
+    _check(st, "vxl_pool_sparse_kv")
+
+
+def gather_bilevel_kv_pooled(layout: Layout, desc: AttnDesc, k, v, ksp, vsp, dense_mask, kmix, vmix, mix_len,
+                             src_idx=None, workspace=None, stream=None):
+    """vxl_gather_bilevel_kv_pooled: as gather_bilevel_kv, sparse rows taken from ksp/vsp."""
+    b, l_cap = int(kmix.shape[0]), int(kmix.shape[2])
+    st = lib().vxl_gather_bilevel_kv_pooled(layout.handle, C.byref(desc), _ptr(k), _ptr(v), _ptr(ksp), _ptr(vsp),
+                                            _ptr(dense_mask), b, _ptr(kmix), _ptr(vmix), l_cap, _ptr(mix_len),
+                                            _ptr(src_idx), _ptr(workspace),
+                                            workspace.numel() if workspace is not None else 0, _stream(stream))
+    _check(st, "vxl_gather_bilevel_kv_pooled")
 
 
 def bilevel_decode(desc: AttnDesc, qd, kmix, vmix, mix_len, out, lse=None, workspace=None, stream=None):
