@@ -39,7 +39,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="config1", choices=["config1", "config2", "config4"])
     ap.add_argument("--prefill-variant", type=int, default=0,
-                    help="debug: 1 or 2 = the 4-wave register-staged kernel with 1 or 2 row blocks per wave")
+                    help="debug: 1 or 2 = the 4-wave register-staged kernel with 1 or 2 row blocks per wave, "
+                         "3 = the software-pipelined 4-wave kernel with 64 rows per wave")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the separate gather/decode measurements")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -158,7 +159,7 @@ def main():
     achieved = eff_flops / (kernel_ms * 1e-3) / 1e12
     mixlen = int(mix_len.cpu()[0])
 
-    kernel_name = "prefill_mfma_kernel" if args.prefill_variant else "prefill_dma_kernel"
+    kernel_name = {0: "prefill_dma_kernel", 3: "prefill_pipe_kernel"}.get(args.prefill_variant, "prefill_mfma_kernel")
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
@@ -190,9 +191,44 @@ def main():
             "config2": bilevel_case(torch, vxl, wl, "config2", wl.WORKLOADS["config2"].k),
             "config4_k_all": bilevel_case(torch, vxl, wl, "config4", 1 << 30),
         }
+        result["widening"] = measure_widening(torch, vxl, w, lay, gl, desc, dk, dv, dqd)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, lay, q, k, v)
     print(json.dumps(result))
+
+
+def measure_widening(torch, vxl, w, lay, gl, desc, dk, dv, dqd):
+    """The calls beyond the four of the step, timed on their own on the step's workload: the
+    attention-mass relevance score (streams the dense K once) and the pooling of the dense KVs
+    into sparse KVs (streams K and V once)."""
+    B, T, C, D, Hkv = w.B, w.T, lay.n_chunks, w.head_dim, w.n_kv_heads
+    e = 2
+    idx = torch.zeros((B, min(w.k, C)), dtype=torch.int32, device="cuda")
+    mask = torch.zeros((B, C), dtype=torch.uint8, device="cuda")
+    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_SCORE_MASS, gl, desc, B, T))
+    s_total = int(lay.sparse_offsets[-1])
+    ksp = torch.empty((Hkv, max(s_total, 1), D), dtype=dk.dtype, device="cuda")
+    vsp = torch.empty_like(ksp)
+
+    def timed(fn, iters=50):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(iters):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / iters
+
+    us_mass = timed(lambda: vxl.chunk_score_topk_mass(gl, desc, dqd, dk, w.k, idx, mask, None, workspace=ws))
+    us_pool = timed(lambda: vxl.pool_sparse_kv(gl, desc, dk, dv, ksp, vsp))
+    k_bytes = Hkv * lay.n_tokens * D * e
+    pool_bytes = 2 * k_bytes + 2 * Hkv * s_total * D * e
+    return {"timing": "back-to-back launches, inputs cache-resident where they fit",
+            "score_mass": {"us": us_mass, "k_bytes": k_bytes, "GBps": k_bytes / us_mass / 1e3},
+            "pool_sparse_kv": {"us": us_pool, "bytes": pool_bytes, "GBps": pool_bytes / us_pool / 1e3}}
 
 
 def bilevel_case(torch, vxl, wl, name, top_k):
