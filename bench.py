@@ -226,9 +226,24 @@ def measure_widening(torch, vxl, w, lay, gl, desc, dk, dv, dqd):
     us_pool = timed(lambda: vxl.pool_sparse_kv(gl, desc, dk, dv, ksp, vsp))
     k_bytes = Hkv * lay.n_tokens * D * e
     pool_bytes = 2 * k_bytes + 2 * Hkv * s_total * D * e
+    # offline store: the mixed KV of one query rebuilt from pinned host memory (host link, not HBM)
+    store = vxl.KvStore(gl, desc)
+    store.offload(dk, dv, ksp, vsp)
+    torch.cuda.synchronize()
+    hmask = np.zeros((B, C), dtype=np.uint8)
+    hmask[:, :min(w.k, C)] = 1
+    l_cap = gl.mixed_kv_capacity(w.k)
+    kmix = torch.empty((B, Hkv, l_cap, D), dtype=dk.dtype, device="cuda")
+    vmix = torch.empty_like(kmix)
+    mlen = torch.zeros((B,), dtype=torch.int32, device="cuda")
+    lens = store.reload(hmask, kmix, vmix, mlen)
+    us_reload = timed(lambda: store.reload(hmask, kmix, vmix, mlen), iters=20)
+    reload_bytes = 2 * Hkv * int(lens.sum()) * D * e
     return {"timing": "back-to-back launches, inputs cache-resident where they fit",
             "score_mass": {"us": us_mass, "k_bytes": k_bytes, "GBps": k_bytes / us_mass / 1e3},
-            "pool_sparse_kv": {"us": us_pool, "bytes": pool_bytes, "GBps": pool_bytes / us_pool / 1e3}}
+            "pool_sparse_kv": {"us": us_pool, "bytes": pool_bytes, "GBps": pool_bytes / us_pool / 1e3},
+            "store_reload": {"us": us_reload, "bytes_over_host_link": reload_bytes,
+                             "GBps": reload_bytes / us_reload / 1e3, "host_store_bytes": store.host_bytes()}}
 
 
 def bilevel_case(torch, vxl, wl, name, top_k):

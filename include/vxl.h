@@ -232,6 +232,41 @@ vxl_status vxl_bilevel_decode(const vxl_attn_desc* desc, const void* Qd, int32_t
                               int32_t l_cap, const int32_t* mix_len, void* O, float* LSE,
                               void* workspace, size_t workspace_bytes, vxl_stream stream);
 
+/*
+ * Offline (host-memory) bi-level KV store of one layer ("Bi-level KVs Decoding": both the dense
+ * and the sparse KVs are stored in an offline memory and selectively reloaded for a query).
+ * The store owns pinned host copies of the dense K/V [n_kv_heads, n_tokens, head_dim] and of the
+ * sparse K/V [n_kv_heads, S_total, head_dim] (kept rows in chunk order, or the pooled rows of
+ * vxl_pool_sparse_kv).
+ *   vxl_kv_store_create   allocates the pinned memory (hipHostMalloc; synchronous, not a hot call)
+ *   vxl_kv_store_offload  device -> host copies of K, V (dense) and Ksp, Vsp (sparse; may be NULL
+ *                         when the layout keeps no rows), asynchronous on `stream`; the store may
+ *                         be reloaded from once these copies have completed
+ *   vxl_kv_store_reload   builds the mixed KV set of `batch` queries in DEVICE memory straight
+ *                         from the host store, with the row order and lengths of
+ *                         vxl_gather_bilevel_kv: one strided host -> device copy per run of rows
+ *                         that are consecutive in one source, asynchronous on `stream`
+ *       dense_mask     HOST uint8 [batch, n_chunks] (the caller has brought the selection back)
+ *       Kmix, Vmix     device [batch, n_kv_heads, l_cap, head_dim]; rows >= length untouched
+ *       mix_len_host   host int32 [batch] written before the call returns, or NULL
+ *       mix_len        device int32 [batch] written by a copy on `stream`, or NULL (batch <= 256;
+ *                      its pinned staging array belongs to the store: reloads of one store that
+ *                      write mix_len must be ordered, e.g. by using one stream)
+ *   Errors: VXL_ERR_INVALID_ARG (null pointers; a query whose mixed length exceeds l_cap --
+ *   nothing is copied then), VXL_ERR_UNSUPPORTED, VXL_ERR_HIP.
+ * The reload moves 2 * n_kv_heads * mix_len * head_dim * elem bytes per query over the host link;
+ * on a side stream it overlaps the decode of another query.
+ */
+typedef struct vxl_kv_store vxl_kv_store;
+vxl_status vxl_kv_store_create(const vxl_layout* layout, const vxl_attn_desc* desc, vxl_kv_store** out);
+vxl_status vxl_kv_store_destroy(vxl_kv_store* store);
+size_t vxl_kv_store_host_bytes(const vxl_kv_store* store);
+vxl_status vxl_kv_store_offload(vxl_kv_store* store, const void* K, const void* V, const void* Ksp,
+                                const void* Vsp, vxl_stream stream);
+vxl_status vxl_kv_store_reload(vxl_kv_store* store, const uint8_t* dense_mask, int32_t batch,
+                               void* Kmix, void* Vmix, int32_t l_cap, int32_t* mix_len_host,
+                               int32_t* mix_len, vxl_stream stream);
+
 const char* vxl_status_string(vxl_status s);
 const char* vxl_last_error(void);   /* text of the last failing HIP call on this thread */
 int vxl_version(void);

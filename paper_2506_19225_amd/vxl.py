@@ -75,6 +75,16 @@ def lib() -> C.CDLL:
     L.vxl_pool_sparse_kv.argtypes = [vp, dp, vp, vp, vp, vp, vp]
     L.vxl_gather_bilevel_kv_pooled.restype = C.c_int
     L.vxl_gather_bilevel_kv_pooled.argtypes = [vp, dp, vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, sz, vp]
+    L.vxl_kv_store_create.restype = C.c_int
+    L.vxl_kv_store_create.argtypes = [vp, dp, C.POINTER(vp)]
+    L.vxl_kv_store_destroy.restype = C.c_int
+    L.vxl_kv_store_destroy.argtypes = [vp]
+    L.vxl_kv_store_host_bytes.restype = sz
+    L.vxl_kv_store_host_bytes.argtypes = [vp]
+    L.vxl_kv_store_offload.restype = C.c_int
+    L.vxl_kv_store_offload.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.vxl_kv_store_reload.restype = C.c_int
+    L.vxl_kv_store_reload.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp]
     L.vxl_bilevel_decode.restype = C.c_int
     L.vxl_bilevel_decode.argtypes = [dp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     L.vxl_debug_force_simple.argtypes = [C.c_int]
@@ -238,6 +248,45 @@ def bilevel_decode(desc: AttnDesc, qd, kmix, vmix, mix_len, out, lse=None, works
                                   workspace.numel() if workspace is not None else 0, _stream(stream))
     _check(st, "vxl_bilevel_decode")
     return out
+
+
+class KvStore:
+    """Owns a vxl_kv_store handle: pinned host copies of one layer's dense and sparse K/V."""
+
+    def __init__(self, layout: Layout, desc: AttnDesc):
+        handle = C.c_void_p()
+        _check(lib().vxl_kv_store_create(layout.handle, C.byref(desc), C.byref(handle)), "vxl_kv_store_create")
+        self.handle = handle
+        self.n_chunks = layout.n_chunks
+
+    def close(self) -> None:
+        if getattr(self, "handle", None):
+            lib().vxl_kv_store_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def host_bytes(self) -> int:
+        return int(lib().vxl_kv_store_host_bytes(self.handle))
+
+    def offload(self, k, v, ksp=None, vsp=None, stream=None) -> None:
+        _check(lib().vxl_kv_store_offload(self.handle, _ptr(k), _ptr(v), _ptr(ksp), _ptr(vsp), _stream(stream)),
+               "vxl_kv_store_offload")
+
+    def reload(self, dense_mask_host: np.ndarray, kmix, vmix, mix_len=None, stream=None) -> np.ndarray:
+        """dense_mask_host: numpy uint8 [B, C]; returns the mixed lengths (numpy int32 [B])."""
+        m = np.ascontiguousarray(dense_mask_host, dtype=np.uint8)
+        b, l_cap = int(kmix.shape[0]), int(kmix.shape[2])
+        assert m.shape == (b, self.n_chunks)
+        lens = np.zeros((b,), dtype=np.int32)
+        st = lib().vxl_kv_store_reload(self.handle, m.ctypes.data if m.size else None, b, _ptr(kmix), _ptr(vmix),
+                                       l_cap, lens.ctypes.data, _ptr(mix_len), _stream(stream))
+        _check(st, "vxl_kv_store_reload")
+        return lens
 
 
 def debug_force_simple(on: bool) -> None:

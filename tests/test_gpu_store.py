@@ -1,0 +1,135 @@
+"""The offline (host-memory) bi-level KV store: a reload from pinned host memory must build the
+same mixed KV set, bit for bit, as the oracle's gather (and as vxl_gather_bilevel_kv on the
+device), for kept-row and for pooled sparse KVs; a reload on a side stream runs beside a decode."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_19225_amd import vxl, workloads as wl
+
+from gpu_util import assert_close, desc_of, gpu_decode, gpu_gather, make_layout
+
+pytestmark = pytest.mark.gpu
+
+
+def kept_rows_on_device(w, lay, gl, dk, dv):
+    """[Hkv, S_total, D] kept rows in chunk order, produced by the device gather with no dense chunk."""
+    s_total = int(lay.sparse_offsets[-1])
+    if s_total == 0:
+        return None, None
+    zero = np.zeros((1, lay.n_chunks), dtype=np.uint8)
+    kmix, vmix, mix_len, _ = gpu_gather(w, lay, None, None, zero, lay.n_prefix + s_total, gl=gl, dev=(dk, dv))
+    p = lay.n_prefix
+    return kmix[0, :, p:p + s_total].contiguous(), vmix[0, :, p:p + s_total].contiguous()
+
+
+def reload_and_check(w, lay, k, v, masks, pooled=False):
+    gl = make_layout(lay)
+    desc = desc_of(w)
+    dk, dv = vxl.to_device(k, w.dtype), vxl.to_device(v, w.dtype)
+    s_total = int(lay.sparse_offsets[-1])
+    if pooled:
+        ksp = torch.empty((w.n_kv_heads, max(s_total, 1), w.head_dim), dtype=dk.dtype, device="cuda")
+        vsp = torch.empty_like(ksp)
+        vxl.pool_sparse_kv(gl, desc, dk, dv, ksp, vsp)
+    else:
+        ksp, vsp = kept_rows_on_device(w, lay, gl, dk, dv)
+    store = vxl.KvStore(gl, desc)
+    assert store.host_bytes() >= 2 * k.size * (2 if w.dtype == "bf16" else 4)
+    store.offload(dk, dv, ksp, vsp)
+    torch.cuda.synchronize()
+    bsz = masks.shape[0]
+    l_cap = gl.mixed_kv_capacity(int(masks.sum(axis=1).max()))
+    kmix = torch.full((bsz, w.n_kv_heads, l_cap, w.head_dim), 7.0, dtype=dk.dtype, device="cuda")
+    vmix = torch.full_like(kmix, 7.0)
+    mix_len = torch.full((bsz,), -1, dtype=torch.int32, device="cuda")
+    lens = store.reload(masks, kmix, vmix, mix_len)
+    torch.cuda.synchronize()
+    if pooled:
+        hk, hv = vxl.to_host(ksp), vxl.to_host(vsp)
+        wk, wv, wlen, _ = oracle.gather_bilevel_pooled(k, v, hk, hv, masks, lay.n_prefix, lay.chunk_bounds,
+                                                       lay.sparse_offsets, l_cap=l_cap)
+    else:
+        wk, wv, wlen, _ = oracle.gather_bilevel(k, v, masks, lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets,
+                                                lay.sparse_idx, l_cap=l_cap)
+    assert np.array_equal(lens, wlen) and np.array_equal(mix_len.cpu().numpy(), wlen)
+    gk, gv = vxl.to_host(kmix), vxl.to_host(vmix)
+    for b in range(bsz):
+        n = int(wlen[b])
+        assert np.array_equal(gk[b, :, :n], wk[b, :, :n]) and np.array_equal(gv[b, :, :n], wv[b, :, :n])
+        assert (gk[b, :, n:] == 7.0).all() and (gv[b, :, n:] == 7.0).all()          # rows beyond untouched
+    return store, gl, desc, kmix, vmix, mix_len
+
+
+def test_store_reload_bit_exact():
+    rng = np.random.default_rng(101)
+    for name in ("config0", "config1"):
+        w = wl.WORKLOADS[name]
+        lay = wl.make_layout(w)
+        _, k, v = wl.make_qkv(w, lay, with_q=False)
+        c_n = lay.n_chunks
+        masks = np.zeros((3, c_n), dtype=np.uint8)
+        masks[1] = 1
+        masks[2, rng.choice(c_n, size=w.k, replace=False)] = 1
+        reload_and_check(w, lay, k, v, masks)
+        reload_and_check(w, lay, k, v, masks, pooled=True)
+    # ragged layout, chunks without kept rows, no prefix, adjacent dense chunks (runs are merged)
+    w = wl.tiny_workload("bf16", 4, 2, 64, T=1, B=1, k=2, seed=102)
+    lay = wl.random_layout(rng, 0, 9, 1, 70, allow_empty_kept=True)
+    _, k, v = wl.make_qkv(w, lay, with_q=False)
+    masks = np.array([[1, 1, 0, 0, 1, 0, 1, 1, 1], [0] * 9, [0, 1, 0, 1, 0, 1, 0, 1, 0]], dtype=np.uint8)
+    reload_and_check(w, lay, k, v, masks)
+
+
+def test_store_rejects_a_query_that_does_not_fit():
+    w = wl.WORKLOADS["config0"]
+    lay = wl.make_layout(w)
+    _, k, v = wl.make_qkv(w, lay, with_q=False)
+    gl = make_layout(lay)
+    desc = desc_of(w)
+    dk, dv = vxl.to_device(k, w.dtype), vxl.to_device(v, w.dtype)
+    ksp, vsp = kept_rows_on_device(w, lay, gl, dk, dv)
+    store = vxl.KvStore(gl, desc)
+    store.offload(dk, dv, ksp, vsp)
+    torch.cuda.synchronize()
+    l_cap = gl.mixed_kv_capacity(1)
+    kmix = torch.zeros((1, w.n_kv_heads, l_cap, w.head_dim), dtype=dk.dtype, device="cuda")
+    vmix = torch.zeros_like(kmix)
+    with pytest.raises(vxl.VxlError):
+        store.reload(np.ones((1, lay.n_chunks), dtype=np.uint8), kmix, vmix)        # all dense needs N rows
+    torch.cuda.synchronize()
+    assert float(kmix.abs().sum()) == 0.0                                          # nothing was copied
+
+
+def test_reload_on_a_side_stream_beside_a_decode():
+    """Query 0 is decoded on the main stream while the mixed KV of query 1 is reloaded on a side
+    stream; both decodes must match the oracle."""
+    w = wl.WORKLOADS["config1"]
+    lay = wl.make_layout(w)
+    _, k, v = wl.make_qkv(w, lay, with_q=False)
+    qd = wl.make_decode_queries(w)
+    rng = np.random.default_rng(103)
+    masks = np.zeros((2, lay.n_chunks), dtype=np.uint8)
+    for b in range(2):
+        masks[b, rng.choice(lay.n_chunks, size=w.k, replace=False)] = 1
+    store, gl, desc, kmix, vmix, mix_len = reload_and_check(w, lay, k, v, masks[:1])
+    l_cap = kmix.shape[2]
+    dqd = vxl.to_device(qd, w.dtype)
+    out0, out1 = torch.empty_like(dqd), torch.empty_like(dqd)
+    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_DECODE, None, desc, 1, w.T, l_cap))
+    kmix1, vmix1 = torch.zeros_like(kmix), torch.zeros_like(vmix)
+    mix_len1 = torch.zeros_like(mix_len)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        store.reload(masks[1:], kmix1, vmix1, mix_len1, stream=side)
+    vxl.bilevel_decode(desc, dqd, kmix, vmix, mix_len, out0, None, ws)             # meanwhile, on the main stream
+    torch.cuda.current_stream().wait_stream(side)
+    vxl.bilevel_decode(desc, dqd, kmix1, vmix1, mix_len1, out1, None, ws)
+    torch.cuda.synchronize()
+    for b, out in ((0, out0), (1, out1)):
+        wk, wv, wlen, _ = oracle.gather_bilevel(k, v, masks[b:b + 1], lay.n_prefix, lay.chunk_bounds,
+                                                lay.sparse_offsets, lay.sparse_idx, l_cap=l_cap)
+        want = oracle.decode_mixed(qd, wk, wv, wlen)
+        assert_close(vxl.to_host(out), want, w.dtype, head_axis=2, what=f"decode of query {b} after reload")
