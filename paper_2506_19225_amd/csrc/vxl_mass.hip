@@ -197,24 +197,43 @@ __global__ __launch_bounds__(256) void mass_partial_simple_kernel(
     }
 }
 
-// Per stacked row (b, g, rho): M = max over the items of m, 1/L with L = sum l * 2^(m - M), items in
-// table order.
+// Per stacked row (b, g, rho): M = max over the items of m, 1/L with L = sum l * 2^(m - M).  A block
+// handles 32 consecutive rows of one (b, g) with 8 item groups: thread (ig, r) folds the items
+// ig, ig + 8, ... of row r into a running (M, L) in that order (loads coalesced over the rows),
+// and the eight partial pairs of a row are folded in group order -- a fixed summation order.
 __global__ __launch_bounds__(256) void mass_rowstat_kernel(const float* __restrict__ part_m,
                                                            const float* __restrict__ part_l,
                                                            float* __restrict__ row_m, float* __restrict__ row_il,
-                                                           int n_items, int n_rows, long total_rows) {
-    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= total_rows) return;
-    const long bg = idx / n_rows;
-    const int rho = (int)(idx % n_rows);
-    const size_t base = (size_t)bg * n_items * n_rows + rho;
-    float M = -INFINITY;
-    for (int it = 0; it < n_items; ++it) M = fmaxf(M, part_m[base + (size_t)it * n_rows]);
-    float L = 0.f;
-    for (int it = 0; it < n_items; ++it)
-        L = fmaf(part_l[base + (size_t)it * n_rows], exp2f(part_m[base + (size_t)it * n_rows] - M), L);
-    row_m[idx] = M;
-    row_il[idx] = 1.f / L;
+                                                           int n_items, int n_rows) {
+    __shared__ float sm[8][32], sl[8][32];
+    const int r = threadIdx.x & 31, ig = threadIdx.x >> 5;
+    const int rho = blockIdx.x * 32 + r;
+    const size_t bg = blockIdx.y;
+    float M = -INFINITY, L = 0.f;
+    if (rho < n_rows) {
+        const size_t base = bg * n_items * n_rows + rho;
+        for (int it = ig; it < n_items; it += 8) {
+            const float m = part_m[base + (size_t)it * n_rows], l = part_l[base + (size_t)it * n_rows];
+            const float Mn = fmaxf(M, m);
+            L = L * exp2f(M - Mn) + l * exp2f(m - Mn);         // (M = -inf: L = 0 and 2^-inf = 0)
+            M = Mn;
+        }
+    }
+    sm[ig][r] = M;
+    sl[ig][r] = L;
+    __syncthreads();
+    if (ig == 0 && rho < n_rows) {
+#pragma unroll
+        for (int k = 1; k < 8; ++k) {
+            const float m = sm[k][r], l = sl[k][r];
+            if (m == -INFINITY) continue;                      // a group without items
+            const float Mn = fmaxf(M, m);
+            L = L * exp2f(M - Mn) + l * exp2f(m - Mn);
+            M = Mn;
+        }
+        row_m[bg * n_rows + rho] = M;
+        row_il[bg * n_rows + rho] = 1.f / L;
+    }
 }
 
 // One block per (chunk c, query b): score = (1 / (T * Hq)) * sum over the stacked rows of all KV
@@ -296,9 +315,8 @@ vxl_status launch_score_mass(const vxl_layout* L, const vxl_attn_desc* d, float 
 #undef VXL_LAUNCH
     }
     VXL_HIP_TRY(hipGetLastError());
-    const long total_rows = (long)batch * d->n_kv_heads * n_rows;
-    hipLaunchKernelGGL(mass_rowstat_kernel, dim3((unsigned)((total_rows + 255) / 256)), dim3(256), 0, s, part_m,
-                       part_l, row_m, row_il, n_items, n_rows, total_rows);
+    hipLaunchKernelGGL(mass_rowstat_kernel, dim3((n_rows + 31) / 32, batch * d->n_kv_heads), dim3(256), 0, s,
+                       part_m, part_l, row_m, row_il, n_items, n_rows);
     VXL_HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(mass_chunk_kernel, dim3(L->n_chunks, batch), dim3(256), 0, s, part_m, part_l, row_m,
                        row_il, L->d_mass_off, scores, n_items, n_rows, d->n_kv_heads, L->n_chunks,
