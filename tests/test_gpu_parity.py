@@ -466,3 +466,53 @@ def test_whole_path_on_a_side_stream_and_in_a_replayed_graph():
         torch.cuda.synchronize()
         for a, b in zip(eager[:7], captured[:7]):
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), f"replay {rep} differs"
+
+
+@pytest.mark.parametrize("name,t_q", [("config1", 1), ("config1", 4), ("config2", 1)])
+def test_decode_step_mode_many_splits(name, t_q):
+    """Step mode (at most 32 stacked rows) at the mixed-set sizes of config1 / config2: many key
+    splits, a workspace that starts with arbitrary bytes, repeated calls on one workspace, and
+    replays of a captured graph with eager calls in between."""
+    w = wl.WORKLOADS[name]
+    lay = wl.make_layout(w)
+    _, k, v = wl.make_qkv(w, lay, with_q=False)
+    qd = wl.make_decode_queries(w)[:, :t_q].copy()
+    _, mask = oracle.select_topk(oracle.chunk_scores(qd, k, lay.chunk_bounds), w.k)
+    gl = make_layout(lay)
+    l_cap = gl.mixed_kv_capacity(w.k)
+    kmix, vmix, mix_len, _ = gpu_gather(w, lay, k, v, mask, l_cap, gl=gl)
+    wk, wv, wlen, _ = oracle.gather_bilevel(k, v, mask, *lay_args(lay), l_cap=l_cap)
+    want, wlse = oracle.decode_lse(qd, wk, wv, wlen)
+    desc = desc_of(w)
+    dqd = vxl.to_device(qd, w.dtype)
+    nbytes = vxl.workspace_bytes(vxl.OP_DECODE, None, desc, qd.shape[0], t_q, l_cap)
+    ws = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device="cuda")        # arbitrary initial bytes
+    outs = []
+    for _ in range(3):
+        out = torch.full_like(dqd, float("nan"))
+        lse = torch.full(dqd.shape[:3], float("nan"), dtype=torch.float32, device="cuda")
+        vxl.bilevel_decode(desc, dqd, kmix, vmix, mix_len, out, lse, ws)
+        torch.cuda.synchronize()
+        assert_close(vxl.to_host(out), want, w.dtype, head_axis=2, what=f"{name} step decode T={t_q}")
+        assert np.abs(vxl.to_host(lse) - wlse).max() < 2e-2
+        outs.append(out.clone())
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])          # deterministic
+    # captured once, replayed three times with eager work in between
+    side = torch.cuda.Stream()
+    out = torch.zeros_like(dqd)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        vxl.bilevel_decode(desc, dqd, kmix, vmix, mix_len, out, None, ws, stream=side)      # warm-up on the stream
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            vxl.bilevel_decode(desc, dqd, kmix, vmix, mix_len, out, None, ws, stream=side)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, outs[0])
+        vxl.bilevel_decode(desc, dqd, kmix, vmix, mix_len, out, None, ws)           # an eager call between replays
+        torch.cuda.synchronize()
+        assert torch.equal(out, outs[0])
