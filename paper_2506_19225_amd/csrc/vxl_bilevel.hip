@@ -2,6 +2,8 @@
 // scores + top-k selection (LDS bitonic sort), and the dense/sparse gather into the mixed KV.
 #include <math.h>
 
+#include <algorithm>
+
 #include "vxl_internal.h"
 
 namespace vxl {
@@ -289,29 +291,35 @@ __global__ __launch_bounds__(256) void pool_sparse_kernel(const T* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------
-// Gather.  Step 1 (one block per query): exclusive scan of the rows every chunk contributes
-// (its length if dense, its kept count if sparse) -> dst_off[b, 0..C], mix_len[b].
-// Step 2: every group of LPR lanes copies one mixed row (all kv heads, K and V) with 16-byte
-// accesses; the source row is found by binary search in dst_off.
+// Gather, one launch.  Every block first forms, in LDS, the exclusive scan of the rows every chunk
+// of its query contributes (its length if dense, its sparse-row count otherwise) -- C <= 4096
+// entries, a few hundred nanoseconds, cheaper than a launch of its own -- and then copies its
+// share of the mixed rows: a group of LPR lanes per row (all KV heads, K and V, 16-byte
+// accesses), the source row found by binary search in the scanned offsets.  A block handles
+// `groups` consecutive passes of 256 / LPR rows (chosen by the host so that small gathers still
+// fill the chip and large ones amortise the scan).  Block 0 of a query writes mix_len.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void gather_scan_kernel(const uint8_t* __restrict__ dense_mask,
-                                                          const int32_t* __restrict__ bounds,
-                                                          const int32_t* __restrict__ soff, int n_chunks,
-                                                          int n_prefix, int l_cap,
-                                                          int32_t* __restrict__ dst_off,
-                                                          int32_t* __restrict__ mix_len) {
+template <int ROW_BYTES>
+__global__ __launch_bounds__(256) void gather_kernel(
+    const uint4* __restrict__ K, const uint4* __restrict__ V, const uint8_t* __restrict__ dense_mask,
+    const int32_t* __restrict__ bounds, const int32_t* __restrict__ soff, const int32_t* __restrict__ sidx,
+    int n_chunks, int n_prefix, int n_tokens, int n_kv_heads, int l_cap, int groups, uint4* __restrict__ Kmix,
+    uint4* __restrict__ Vmix, int32_t* __restrict__ mix_len, int32_t* __restrict__ src_idx,
+    const uint4* __restrict__ Ksp, const uint4* __restrict__ Vsp, int s_total) {
+    constexpr int LPR = ROW_BYTES / 16;                       // lanes per row
+    constexpr int ROWS = 256 / LPR;                           // rows per pass
+    extern __shared__ int off[];                              // [n_chunks + 1] first mixed row of every chunk
     __shared__ int wave_tot[4];
     __shared__ int carry;
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int32_t* out = dst_off + (size_t)b * (n_chunks + 1);
+    const int b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint8_t* mask = dense_mask + (size_t)b * n_chunks;
     if (tid == 0) carry = n_prefix;
     __syncthreads();
     for (int base = 0; base < n_chunks; base += 256) {
         const int c = base + tid;
         int v = 0;
-        if (c < n_chunks)
-            v = dense_mask[(size_t)b * n_chunks + c] ? bounds[c + 1] - bounds[c] : soff[c + 1] - soff[c];
-        int inc = v;                                         // inclusive scan inside the wave
+        if (c < n_chunks) v = mask[c] ? bounds[c + 1] - bounds[c] : soff[c + 1] - soff[c];
+        int inc = v;                                          // inclusive scan inside the wave
         for (int o = 1; o < 64; o <<= 1) {
             const int t = __shfl_up(inc, o);
             if (lane >= o) inc += t;
@@ -320,57 +328,47 @@ __global__ __launch_bounds__(256) void gather_scan_kernel(const uint8_t* __restr
         __syncthreads();
         int before = carry;
         for (int w = 0; w < wave; ++w) before += wave_tot[w];
-        if (c < n_chunks) out[c] = before + inc - v;
+        if (c < n_chunks) off[c] = before + inc - v;
         __syncthreads();
         if (tid == 0) carry += wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
         __syncthreads();
     }
     if (tid == 0) {
-        out[n_chunks] = carry;
-        mix_len[b] = min(carry, l_cap);
+        off[n_chunks] = carry;
+        if (blockIdx.x == 0) mix_len[b] = min(carry, l_cap);
     }
-}
-
-template <int ROW_BYTES>
-__global__ __launch_bounds__(256) void gather_copy_kernel(
-    const uint4* __restrict__ K, const uint4* __restrict__ V, const uint8_t* __restrict__ dense_mask,
-    const int32_t* __restrict__ bounds, const int32_t* __restrict__ soff, const int32_t* __restrict__ sidx,
-    const int32_t* __restrict__ dst_off, int n_chunks, int n_prefix, int n_tokens, int n_kv_heads, int l_cap,
-    uint4* __restrict__ Kmix, uint4* __restrict__ Vmix, int32_t* __restrict__ src_idx,
-    const uint4* __restrict__ Ksp, const uint4* __restrict__ Vsp, int s_total) {
-    constexpr int LPR = ROW_BYTES / 16;                       // lanes per row
-    constexpr int ROWS = 256 / LPR;                           // rows per block pass
-    const int b = blockIdx.y;
-    const int32_t* off = dst_off + (size_t)b * (n_chunks + 1);
+    __syncthreads();
     const int len = min(off[n_chunks], l_cap);
-    const int r = blockIdx.x * ROWS + threadIdx.x / LPR;
-    const int part = threadIdx.x % LPR;
-    if (r >= len) return;
-    int src;                                                  // token id, or -1 - pooled row
-    if (r < n_prefix) {
-        src = r;
-    } else {
-        int lo = 0, hi = n_chunks;                            // last chunk with off[c] <= r
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (off[mid] <= r) lo = mid; else hi = mid;
+    const int part = tid % LPR;
+    for (int gi = 0; gi < groups; ++gi) {
+        const int r = (blockIdx.x * groups + gi) * ROWS + tid / LPR;
+        if (r >= len) break;                                  // (rows ascend with gi)
+        int src;                                              // token id, or -1 - pooled row
+        if (r < n_prefix) {
+            src = r;
+        } else {
+            int lo = 0, hi = n_chunks;                        // last chunk with off[c] <= r
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (off[mid] <= r) lo = mid; else hi = mid;
+            }
+            const int o = r - off[lo];
+            if (mask[lo]) src = bounds[lo] + o;
+            else src = Ksp ? -1 - (soff[lo] + o) : sidx[soff[lo] + o];
         }
-        const int o = r - off[lo];
-        if (dense_mask[(size_t)b * n_chunks + lo]) src = bounds[lo] + o;
-        else src = Ksp ? -1 - (soff[lo] + o) : sidx[soff[lo] + o];
-    }
-    if (src_idx && part == 0) src_idx[(size_t)b * l_cap + r] = src;
-    const uint4* ks = src >= 0 ? K : Ksp;
-    const uint4* vs = src >= 0 ? V : Vsp;
-    const size_t rows = src >= 0 ? (size_t)n_tokens : (size_t)s_total;
-    const size_t row = src >= 0 ? (size_t)src : (size_t)(-1 - src);
-    for (int g = 0; g < n_kv_heads; ++g) {
-        const size_t s_off = (g * rows + row) * LPR + part;
-        const size_t d_off = (((size_t)b * n_kv_heads + g) * l_cap + r) * LPR + part;
-        const uint4 kv = ks[s_off];
-        const uint4 vv = vs[s_off];
-        Kmix[d_off] = kv;
-        Vmix[d_off] = vv;
+        if (src_idx && part == 0) src_idx[(size_t)b * l_cap + r] = src;
+        const uint4* ks = src >= 0 ? K : Ksp;
+        const uint4* vs = src >= 0 ? V : Vsp;
+        const size_t rows = src >= 0 ? (size_t)n_tokens : (size_t)s_total;
+        const size_t row = src >= 0 ? (size_t)src : (size_t)(-1 - src);
+        for (int g = 0; g < n_kv_heads; ++g) {
+            const size_t s_off = (g * rows + row) * LPR + part;
+            const size_t d_off = (((size_t)b * n_kv_heads + g) * l_cap + r) * LPR + part;
+            const uint4 kv = ks[s_off];
+            const uint4 vv = vs[s_off];
+            Kmix[d_off] = kv;
+            Vmix[d_off] = vv;
+        }
     }
 }
 
@@ -439,18 +437,19 @@ vxl_status launch_gather(const vxl_layout* L, const vxl_attn_desc* d, const void
                          const void* Ksp, const void* Vsp, const uint8_t* dense_mask, int batch, void* Kmix,
                          void* Vmix, int l_cap, int32_t* mix_len, int32_t* src_idx, int32_t* ws_offsets,
                          hipStream_t s) {
-    hipLaunchKernelGGL(gather_scan_kernel, dim3(batch), dim3(256), 0, s, dense_mask, L->d_bounds,
-                       L->d_soff, L->n_chunks, L->n_prefix, l_cap, ws_offsets, mix_len);
-    VXL_HIP_TRY(hipGetLastError());
+    (void)ws_offsets;                                         // (the offsets live in LDS)
     const int row_bytes = d->head_dim * (d->dtype == VXL_BF16 ? 2 : 4);
+    const size_t smem = (size_t)(L->n_chunks + 1) * sizeof(int);
 #define VXL_LAUNCH(RB)                                                                             \
     do {                                                                                           \
         constexpr int rows = 256 / (RB / 16);                                                      \
-        const dim3 grid((l_cap + rows - 1) / rows, batch);                                         \
-        hipLaunchKernelGGL((gather_copy_kernel<RB>), grid, dim3(256), 0, s, (const uint4*)K,       \
+        const long passes = (l_cap + rows - 1) / rows;                                             \
+        const int groups = (int)std::max<long>(1, std::min<long>(8, passes * batch / 512));        \
+        const dim3 grid((unsigned)((passes + groups - 1) / groups), batch);                        \
+        hipLaunchKernelGGL((gather_kernel<RB>), grid, dim3(256), smem, s, (const uint4*)K,         \
                            (const uint4*)V, dense_mask, L->d_bounds, L->d_soff, L->d_sidx,         \
-                           ws_offsets, L->n_chunks, L->n_prefix, L->n_tokens, d->n_kv_heads, l_cap, \
-                           (uint4*)Kmix, (uint4*)Vmix, src_idx, (const uint4*)Ksp,                 \
+                           L->n_chunks, L->n_prefix, L->n_tokens, d->n_kv_heads, l_cap, groups,    \
+                           (uint4*)Kmix, (uint4*)Vmix, mix_len, src_idx, (const uint4*)Ksp,        \
                            (const uint4*)Vsp, L->s_total);                                         \
     } while (0)
     if (row_bytes == 128) VXL_LAUNCH(128);
