@@ -144,6 +144,7 @@ vxl_status vxl_chunk_prefill(const vxl_layout* layout, const vxl_attn_desc* desc
  *   K           device dense keys (read only when kbar_ready == 0)
  *   kbar        device float [n_kv_heads, n_chunks, head_dim] per-chunk mean keys: written when
  *               kbar_ready == 0, read as a cache when kbar_ready != 0; NULL uses the workspace
+ *   workspace   always needed (it also holds the mean queries), sized by VXL_OP_SCORE_TOPK
  *   topk_idx    device int32 [batch, min(k, n_chunks)], best first (may be NULL if k == 0)
  *   dense_mask  device uint8 [batch, n_chunks], 1 = dense
  *   scores      device float [batch, n_chunks] or NULL

@@ -314,9 +314,10 @@ size_t vxl_workspace_bytes(vxl_op op, const vxl_layout* L, const vxl_attn_desc* 
         case VXL_OP_PREFILL:
             if (!L) return 0;
             return std::max<size_t>(256, prefill_workspace(L, d).total);
-        case VXL_OP_SCORE_TOPK:
+        case VXL_OP_SCORE_TOPK:     // mean queries [B][Hkv][D], then mean keys [Hkv][C][D] (used when no cache is given)
             if (!L || batch <= 0) return 0;
-            return std::max<size_t>(256, align_up((size_t)d->n_kv_heads * std::max(1, L->n_chunks) * d->head_dim * 4, 256));
+            return align_up((size_t)batch * d->n_kv_heads * d->head_dim * 4, 256) +
+                   align_up((size_t)d->n_kv_heads * std::max(1, L->n_chunks) * d->head_dim * 4, 256);
         case VXL_OP_GATHER:
             if (!L || batch <= 0) return 0;
             return align_up((size_t)batch * (L->n_chunks + 2) * 4, 256);
@@ -363,18 +364,14 @@ vxl_status vxl_chunk_score_topk(const vxl_layout* L, const vxl_attn_desc* d, con
     if (kbar_ready && !kbar) return VXL_ERR_INVALID_ARG;
     if (!kbar_ready && (!K || !aligned16(K))) return VXL_ERR_INVALID_ARG;
     if (L->n_chunks == 0) return VXL_OK;      // nothing to score, nothing to write
-    float* kb = kbar;
-    if (!kb) {
-        const size_t need = vxl_workspace_bytes(VXL_OP_SCORE_TOPK, L, d, batch, n_q_tokens, 0);
-        if (!workspace || workspace_bytes < need || !aligned16(workspace)) return VXL_ERR_WORKSPACE;
-        kb = (float*)workspace;
-    }
-    if (!kbar_ready) {
-        st = launch_chunk_summarize(L, d, K, kb, (hipStream_t)stream);
-        if (st != VXL_OK) return st;
-    }
-    return launch_score_topk(L, d, resolve_scale(d), Qd, batch, n_q_tokens, kk, kb, topk_idx,
-                             dense_mask, scores, (hipStream_t)stream);
+    const size_t need = vxl_workspace_bytes(VXL_OP_SCORE_TOPK, L, d, batch, n_q_tokens, 0);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return VXL_ERR_WORKSPACE;
+    float* qbar = (float*)workspace;
+    float* kb = kbar ? kbar : (float*)((char*)workspace + align_up((size_t)batch * d->n_kv_heads * d->head_dim * 4, 256));
+    st = launch_summaries(L, d, K, kb, !kbar_ready, Qd, batch, n_q_tokens, qbar, (hipStream_t)stream);
+    if (st != VXL_OK) return st;
+    return launch_score_topk(L, d, resolve_scale(d), batch, kk, qbar, kb, topk_idx, dense_mask, scores,
+                             (hipStream_t)stream);
 }
 
 vxl_status vxl_chunk_score_topk_mass(const vxl_layout* L, const vxl_attn_desc* d, const void* Qd,

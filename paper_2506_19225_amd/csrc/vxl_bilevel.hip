@@ -21,15 +21,67 @@ __device__ __forceinline__ float ld(const uint16_t* p) { return __uint_as_float(
 // values and their offsets inside the chunk: two chunks with equal contents get bit-identical
 // means, hence exactly tied scores.
 // ------------------------------------------------------------------------------------------
+// qbar[b, g, :] = mean over the T query tokens and the query heads of KV head g of Qd[b, t, h, :].
+// One block per (b, g): a thread owns one 16-byte column piece of one head and adds its T tokens in
+// token order (16 loads in flight at a time); the heads of the group are then added in head order.
+template <typename T, int D>
+__device__ __forceinline__ void query_mean_block(const T* __restrict__ Qd, float* __restrict__ qbar, int b, int g,
+                                                 int T_q, int n_q_heads, int n_kv_heads, float* hsum /*[group][D]*/) {
+    constexpr int EPC = 16 / (int)sizeof(T);
+    constexpr int PPR = D / EPC;
+    const int group = n_q_heads / n_kv_heads, tid = threadIdx.x;
+    const T* qb = Qd + (size_t)b * T_q * n_q_heads * D;
+    const int row_pieces = n_q_heads * PPR;
+    for (int p = tid; p < group * PPR; p += 256) {
+        const int gp = g * group * PPR + p;                    // piece index inside a token's [Hq*D] row
+        float acc[EPC];
+#pragma unroll
+        for (int i = 0; i < EPC; ++i) acc[i] = 0.f;
+        for (int t0 = 0; t0 < T_q; t0 += 16) {
+            uint4 v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int t = t0 + u < T_q ? t0 + u : T_q - 1;      // clamped rows are not added below
+                v[u] = ((const uint4*)qb)[(size_t)t * row_pieces + gp];
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                if (t0 + u < T_q) {
+                    const T* e = (const T*)&v[u];
+#pragma unroll
+                    for (int i = 0; i < EPC; ++i) acc[i] += ld(e + i);
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < EPC; ++i) hsum[p * EPC + i] = acc[i];
+    }
+    __syncthreads();
+    for (int dd = tid; dd < D; dd += 256) {
+        float a = 0.f;
+        for (int hg = 0; hg < group; ++hg) a += hsum[hg * D + dd];
+        qbar[((size_t)b * n_kv_heads + g) * D + dd] = a / (float)(T_q * group);
+    }
+}
+
+// Blocks x < n_chunks summarise chunk x; blocks x >= n_chunks (when Qd is given) form the mean
+// query of query x - n_chunks: both feed the scoring kernel, one launch serves both.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void chunk_summarize_kernel(const T* __restrict__ K,
                                                               const int32_t* __restrict__ bounds,
                                                               float* __restrict__ kbar, int n_tokens,
-                                                              int n_chunks) {
+                                                              int n_chunks, const T* __restrict__ Qd,
+                                                              float* __restrict__ qbar, int T_q, int n_q_heads,
+                                                              int n_kv_heads) {
     constexpr int EPC = 16 / (int)sizeof(T);        // elements per 16-byte piece
     constexpr int PPR = D / EPC;                    // pieces per row
     constexpr int RG = 256 / PPR;                   // row groups
+    extern __shared__ float dyn[];                  // [group][D] for the query blocks
     __shared__ float part[RG][D];
+    if ((int)blockIdx.x >= n_chunks) {
+        query_mean_block<T, D>(Qd, qbar, blockIdx.x - n_chunks, blockIdx.y, T_q, n_q_heads, n_kv_heads, dyn);
+        return;
+    }
     const int c = blockIdx.x, g = blockIdx.y;
     const int piece = threadIdx.x % PPR, rg = threadIdx.x / PPR;
     const int lo = bounds[c], hi = bounds[c + 1];
@@ -86,6 +138,20 @@ __device__ __forceinline__ bool ranks_before(float sa, int ia, float sb, int ib)
 __device__ __forceinline__ void sort_select(float* s_val, int* s_idx, int n_sort, int n_chunks, int k, int b,
                                             int32_t* __restrict__ topk_idx, uint8_t* __restrict__ dense_mask) {
     const int tid = threadIdx.x;
+    if (n_sort <= 256) {
+        // Few chunks: every thread ranks one chunk by counting the chunks that come before it in
+        // the order (score descending, id ascending) -- a total order, so the ranks are a permutation
+        // -- instead of the barrier-per-step sort below.
+        const int c = tid;
+        if (c < n_chunks) {
+            const float sc = s_val[c];
+            int rank = 0;
+            for (int o = 0; o < n_chunks; ++o) rank += ranks_before(s_val[o], o, sc, c) ? 1 : 0;
+            if (rank < k) topk_idx[(size_t)b * k + rank] = c;
+            dense_mask[(size_t)b * n_chunks + c] = (uint8_t)(rank < k ? 1 : 0);
+        }
+        return;
+    }
     // bitonic sort, best first
     for (int size = 2; size <= n_sort; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
@@ -115,64 +181,17 @@ __device__ __forceinline__ void sort_select(float* s_val, int* s_idx, int n_sort
     for (int c = tid; c < n_chunks; c += 256) dense_mask[(size_t)b * n_chunks + c] = (uint8_t)flag[c];
 }
 
-template <typename T, int D>
+template <int D>
 __global__ __launch_bounds__(256) void score_topk_kernel(
-    const T* __restrict__ Qd, const float* __restrict__ kbar, int T_q, int n_q_heads, int n_kv_heads,
-    int n_chunks, int k, int n_sort, float scale, int32_t* __restrict__ topk_idx,
-    uint8_t* __restrict__ dense_mask, float* __restrict__ scores) {
+    const float* __restrict__ qbar_g, const float* __restrict__ kbar, int n_kv_heads, int n_chunks, int k,
+    int n_sort, float scale, int32_t* __restrict__ topk_idx, uint8_t* __restrict__ dense_mask,
+    float* __restrict__ scores) {
     extern __shared__ unsigned char smem[];
     float* qbar = (float*)smem;                               // [Hkv][D]
     float* s_val = qbar + n_kv_heads * D;                     // [n_sort]
     int* s_idx = (int*)(s_val + n_sort);                      // [n_sort]
-    float* hsum = (float*)(s_idx + n_sort);                   // [Hq][D] per-head sums over tokens
     const int b = blockIdx.x, tid = threadIdx.x;
-    const int group = n_q_heads / n_kv_heads;
-    const T* qb = Qd + (size_t)b * T_q * n_q_heads * D;
-    // mean query of every kv head.  Step 1: every thread owns 16-byte columns of the [T, Hq*D]
-    // query matrix, two at a time, and sums them over the tokens in token order; the loads of 16
-    // tokens of both columns are independent and in flight together.
-    constexpr int EPC = 16 / (int)sizeof(T);                  // elements per 16-byte piece
-    const int row_pieces = n_q_heads * D / EPC;
-    for (int p0 = tid; p0 < row_pieces; p0 += 512) {
-        const int p1 = p0 + 256 < row_pieces ? p0 + 256 : p0;      // second column (or the first again)
-        float acc0[EPC], acc1[EPC];
-#pragma unroll
-        for (int i = 0; i < EPC; ++i) acc0[i] = acc1[i] = 0.f;
-        for (int t0 = 0; t0 < T_q; t0 += 16) {
-            uint4 v0[16], v1[16];
-#pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const int t = t0 + u < T_q ? t0 + u : T_q - 1;     // clamped rows are not added below
-                v0[u] = ((const uint4*)qb)[(size_t)t * row_pieces + p0];
-                v1[u] = ((const uint4*)qb)[(size_t)t * row_pieces + p1];
-            }
-#pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                if (t0 + u < T_q) {
-                    const T* e0 = (const T*)&v0[u];
-                    const T* e1 = (const T*)&v1[u];
-#pragma unroll
-                    for (int i = 0; i < EPC; ++i) {
-                        acc0[i] += ld(e0 + i);
-                        acc1[i] += ld(e1 + i);
-                    }
-                }
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < EPC; ++i) {
-            hsum[p0 * EPC + i] = acc0[i];
-            if (p1 != p0) hsum[p1 * EPC + i] = acc1[i];
-        }
-    }
-    __syncthreads();
-    // Step 2: add the heads of a group in head order.
-    for (int e = tid; e < n_kv_heads * D; e += 256) {
-        const int g = e / D, dd = e % D;
-        float a = 0.f;
-        for (int hg = 0; hg < group; ++hg) a += hsum[(g * group + hg) * D + dd];
-        qbar[e] = a / (float)(T_q * group);
-    }
+    for (int e = tid; e < n_kv_heads * D; e += 256) qbar[e] = qbar_g[(size_t)b * n_kv_heads * D + e];
     __syncthreads();
     // Scores: 8 consecutive lanes share a chunk; lane `part` takes the part-th eighth of the
     // flattened (kv head, d) index range, and the eight partial dot products are added in a fixed
@@ -374,12 +393,16 @@ __global__ __launch_bounds__(256) void gather_kernel(
 
 }  // namespace
 
-vxl_status launch_chunk_summarize(const vxl_layout* L, const vxl_attn_desc* d, const void* K,
-                                  float* kbar, hipStream_t s) {
-    const dim3 grid(L->n_chunks, d->n_kv_heads), block(256);
-#define VXL_LAUNCH(T, D)                                                                         \
-    hipLaunchKernelGGL((chunk_summarize_kernel<T, D>), grid, block, 0, s, (const T*)K, L->d_bounds, \
-                       kbar, L->n_tokens, L->n_chunks)
+// kbar (n_chunks blocks per KV head; skipped when do_chunks is false) and qbar (batch blocks per KV
+// head) in one launch.
+vxl_status launch_summaries(const vxl_layout* L, const vxl_attn_desc* d, const void* K, float* kbar,
+                            bool do_chunks, const void* Qd, int batch, int T, float* qbar, hipStream_t s) {
+    const int nc = do_chunks ? L->n_chunks : 0;
+    const dim3 grid(nc + batch, d->n_kv_heads), block(256);
+    const size_t smem = (size_t)(d->n_q_heads / d->n_kv_heads) * d->head_dim * sizeof(float);
+#define VXL_LAUNCH(T_, D)                                                                         \
+    hipLaunchKernelGGL((chunk_summarize_kernel<T_, D>), grid, block, smem, s, (const T_*)K, L->d_bounds, \
+                       kbar, L->n_tokens, nc, (const T_*)Qd, qbar, T, d->n_q_heads, d->n_kv_heads)
     if (d->dtype == VXL_F32) { if (d->head_dim == 64) VXL_LAUNCH(float, 64); else VXL_LAUNCH(float, 128); }
     else { if (d->head_dim == 64) VXL_LAUNCH(uint16_t, 64); else VXL_LAUNCH(uint16_t, 128); }
 #undef VXL_LAUNCH
@@ -387,22 +410,20 @@ vxl_status launch_chunk_summarize(const vxl_layout* L, const vxl_attn_desc* d, c
     return VXL_OK;
 }
 
-vxl_status launch_score_topk(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Qd,
-                             int batch, int T, int k, const float* kbar, int32_t* topk_idx,
-                             uint8_t* dense_mask, float* scores, hipStream_t s) {
+vxl_status launch_score_topk(const vxl_layout* L, const vxl_attn_desc* d, float scale, int batch, int k,
+                             const float* qbar, const float* kbar, int32_t* topk_idx, uint8_t* dense_mask,
+                             float* scores, hipStream_t s) {
     int n_sort = 2;
     while (n_sort < L->n_chunks) n_sort <<= 1;
-    const size_t smem = (size_t)d->n_kv_heads * d->head_dim * 4 + (size_t)n_sort * 8 +
-                        (size_t)d->n_q_heads * d->head_dim * 4;
+    const size_t smem = (size_t)d->n_kv_heads * d->head_dim * 4 + (size_t)n_sort * 8;
     if (smem > 64 * 1024) return VXL_ERR_UNSUPPORTED;
     const dim3 grid(batch), block(256);
-#define VXL_LAUNCH(T_, D)                                                                          \
-    hipLaunchKernelGGL((score_topk_kernel<T_, D>), grid, block, smem, s, (const T_*)Qd, kbar, T,   \
-                       d->n_q_heads, d->n_kv_heads, L->n_chunks, k, n_sort, scale, topk_idx,       \
-                       dense_mask, scores)
-    if (d->dtype == VXL_F32) { if (d->head_dim == 64) VXL_LAUNCH(float, 64); else VXL_LAUNCH(float, 128); }
-    else { if (d->head_dim == 64) VXL_LAUNCH(uint16_t, 64); else VXL_LAUNCH(uint16_t, 128); }
-#undef VXL_LAUNCH
+    if (d->head_dim == 64)
+        hipLaunchKernelGGL((score_topk_kernel<64>), grid, block, smem, s, qbar, kbar, d->n_kv_heads, L->n_chunks, k,
+                           n_sort, scale, topk_idx, dense_mask, scores);
+    else
+        hipLaunchKernelGGL((score_topk_kernel<128>), grid, block, smem, s, qbar, kbar, d->n_kv_heads, L->n_chunks, k,
+                           n_sort, scale, topk_idx, dense_mask, scores);
     VXL_HIP_TRY(hipGetLastError());
     return VXL_OK;
 }

@@ -106,11 +106,11 @@ vxl_status launch_prefill_simple(const vxl_layout* L, const vxl_attn_desc* d, fl
                                  hipStream_t s);
 
 // ---- scoring / selection / gather ----
-vxl_status launch_chunk_summarize(const vxl_layout* L, const vxl_attn_desc* d, const void* K,
-                                  float* kbar, hipStream_t s);
-vxl_status launch_score_topk(const vxl_layout* L, const vxl_attn_desc* d, float scale,
-                             const void* Qd, int batch, int T, int k, const float* kbar,
-                             int32_t* topk_idx, uint8_t* dense_mask, float* scores, hipStream_t s);
+vxl_status launch_summaries(const vxl_layout* L, const vxl_attn_desc* d, const void* K, float* kbar,
+                            bool do_chunks, const void* Qd, int batch, int T, float* qbar, hipStream_t s);
+vxl_status launch_score_topk(const vxl_layout* L, const vxl_attn_desc* d, float scale, int batch, int k,
+                             const float* qbar, const float* kbar, int32_t* topk_idx, uint8_t* dense_mask,
+                             float* scores, hipStream_t s);
 vxl_status launch_topk_from_scores(const vxl_layout* L, const float* scores, int batch, int k,
                                    int32_t* topk_idx, uint8_t* dense_mask, hipStream_t s);
 
