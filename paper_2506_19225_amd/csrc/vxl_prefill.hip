@@ -308,12 +308,20 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     if (tid == 0) next_slot[0] = atomicAdd(queue + qid, 1);
     __syncthreads();
     int j = __builtin_amdgcn_readfirstlane(next_slot[0]);
+    // The descriptors of an item (two dependent scalar loads) are fetched while the item before it
+    // runs, as soon as its index is known.
+    auto item_of = [&](int jj) { return xpg > 0 ? jj / group : jj / n_q_heads; };
+    WorkItem wi_next = {0, 0};
+    Segment sg_next = {0, 0, 0, 0, 0};
+    if (j < q_len_items) {
+        wi_next = work[item_of(j)];
+        sg_next = segs[wi_next.seg];
+    }
   for (int par = 1; j < q_len_items; par ^= 1) {
-    const int item = xpg > 0 ? j / group : j / n_q_heads;
     const int h = xpg > 0 ? qid * group + j % group : j % n_q_heads;
     const int g = h / group;
-    const WorkItem wi = work[item];
-    const Segment sg = segs[wi.seg];
+    const WorkItem wi = wi_next;
+    const Segment sg = sg_next;
     const int m0 = wi.m_tile * C::BM;
     const int wrow0 = m0 + wave * 32;
     const int n_ctx_t = (sg.ctx_len + kKeyTile - 1) / kKeyTile;
@@ -409,12 +417,19 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     for (int t0 = 0; t0 < n_t; t0 += TPB) {
         wait_vmcnt<0>();                                      // this wave's parts of tiles t0, t0+1 have landed
         __builtin_amdgcn_s_barrier();                         // ... and everyone's; the other group is free
-        issue(min(t0 + TPB, n_t - 1));
-        process(t0);
-        issue(min(t0 + TPB + 1, n_t - 1));                    // the second refill between the two tiles
+        if (t0 == 0) {                                        // the next item's index was written before this barrier
+            const int jn = __builtin_amdgcn_readfirstlane(next_slot[par]);
+            if (jn < q_len_items) {
+                wi_next = work[item_of(jn)];
+                sg_next = segs[wi_next.seg];
+            }
+        }
+        if (t0 + TPB < n_t) issue(t0 + TPB);                  // (all waits are vmcnt(0): nothing is issued past the last tile,
+        process(t0);                                          //  so the item does not end waiting for loads nobody reads)
+        if (t0 + TPB + 1 < n_t) issue(t0 + TPB + 1);          // the second refill between the two tiles
         if (t0 + 1 < n_t) process(t0 + 1);
     }
-    wait_vmcnt<0>();                                          // drain the refills before the wave ends
+    wait_vmcnt<0>();                                          // nothing of the ring is in flight when the item ends
 
     {
         const int q_off = wrow0 + l32;
