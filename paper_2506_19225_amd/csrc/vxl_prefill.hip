@@ -281,8 +281,8 @@ struct PrefillDmaCfg {
 };
 
 // The kernel is persistent: the grid is one workgroup per compute unit, and every workgroup keeps
-// taking the next (work item, query head) pair of its queue from a counter in global memory until
-// the queue is empty.  The work list is sorted heaviest first, so this is greedy longest-first
+// taking the next (band of query rows, part of its row-block x head grid) pair of its queue from a
+// counter in global memory until the queue is empty.  The work list is sorted heaviest first, so this is greedy longest-first
 // scheduling without gaps between workgroups.  With xpg > 0 there is one queue per KV head group,
 // served by the xpg XCDs (blockIdx.x % 8, the order workgroups are dealt out in) whose L2 then
 // holds that group's K and V; otherwise a single queue.  The counters must be zero at launch.
@@ -318,15 +318,30 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
         sg_next = segs[wi_next.seg];
     }
   for (int par = 1; j < q_len_items; par ^= 1) {
-    const int h = xpg > 0 ? qid * group + j % group : j % n_q_heads;
-    const int g = h / group;
+    // A list entry is a band of C::BM query rows of a segment; with the `group` query heads that
+    // share a KV head it makes a grid of (up to 8 row blocks of 32) x group cells, which is cut
+    // row block major into `group` parts of 8 cells, one per wave.  A part spans few row blocks
+    // (all heads of one or two of them), so all its waves stop at about the same own tile, and
+    // the cells of a ragged last band fill as few parts as possible: cut head by head, every
+    // part of such a band would run with most of its waves idle (variable chunk lengths: +11 %).
+    // Parts left without cells walk one tile and write nothing.
+    const int part_id = xpg > 0 ? qid * group + j % group : j % n_q_heads;
+    const int g = part_id / group;                            // KV head
+    const int part = part_id - g * group;
     const WorkItem wi = wi_next;
     const Segment sg = sg_next;
     const int m0 = wi.m_tile * C::BM;
-    const int wrow0 = m0 + wave * 32;
+    const int band_blocks = min(C::WAVES, (sg.q_len - m0 + 31) / 32);
+    const int cell = part * C::WAVES + wave;
+    const int rb = cell / group;                              // this wave's row block and head
+    const int h = g * group + (cell - rb * group);
+    const bool idle = rb >= band_blocks;                      // (the grid of a ragged last band is smaller)
+    const int wrow0 = m0 + rb * 32;
     const int n_ctx_t = (sg.ctx_len + kKeyTile - 1) / kKeyTile;
-    const int last_row = min(m0 + C::BM, sg.q_len) - 1;
-    const int n_t = n_ctx_t + (last_row + sg.back) / kKeyTile + 1;      // own keys start `back` rows early
+    const int rb_last = min(band_blocks - 1, (part * C::WAVES + C::WAVES - 1) / group);
+    const int last_row = min(m0 + (rb_last + 1) * 32, sg.q_len) - 1;
+    // own keys start `back` rows early; a part without cells still walks one tile (every wave idle)
+    const int n_t = part * C::WAVES < band_blocks * group ? n_ctx_t + (last_row + sg.back) / kKeyTile + 1 : 1;
 
     const char* kctx_g = (const char*)(Kctx + (size_t)g * ctx_rows_pad * D);
     const char* vctx_g = (const char*)(Vctx + (size_t)g * ctx_rows_pad * D);
@@ -394,7 +409,7 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     auto process = [&](int ti) {
         const bool is_ctx = ti < n_ctx_t;
         const int key0 = is_ctx ? ti * kKeyTile : (ti - n_ctx_t) * kKeyTile;
-        const bool skip = !is_ctx && key0 > wrow0 + sg.back + 31;   // the tile lies above this wave's rows
+        const bool skip = idle || (!is_ctx && key0 > wrow0 + sg.back + 31);   // the tile lies above this wave's rows
         if (!skip) {
             const uint16_t* kt = lds + (ti % NS) * C::STAGE;
             const uint16_t* vt = kt + C::TILE;
@@ -434,7 +449,7 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     {
         const int q_off = wrow0 + l32;
         const float l_tot = l_run + __shfl_xor(l_run, 32);
-        if (q_off < sg.q_len) {
+        if (q_off < sg.q_len && !idle) {
             const float inv = 1.f / l_tot;
             // uniform bases + 32-bit lane offsets, as for the query loads
             char* obase = (char*)(O + ((size_t)h * n_tokens + sg.q_start) * D);

@@ -41,6 +41,9 @@ TINY_CASES = [
     ("bf16", 6, 2, 64, 7, 5, 2, 90, 103),
     ("bf16", 7, 1, 128, 70, 4, 60, 200, 104),
     ("bf16", 2, 2, 128, 129, 3, 127, 300, 105),
+    # several 256-row bands per chunk, the last ragged, 7 and 12 query heads per KV head
+    ("bf16", 14, 2, 128, 33, 3, 257, 600, 106),
+    ("bf16", 12, 1, 64, 10, 2, 100, 400, 107),
 ]
 
 
