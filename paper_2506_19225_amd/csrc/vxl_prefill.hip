@@ -305,6 +305,19 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     const float c2 = scale * kLog2e;
     const int r_in = lane / C::PPR, pp = lane % C::PPR;
 
+    // Lane-constant parts of the refill addresses of a full tile: row and (swizzled) 16-byte piece
+    // of this lane in each of the wave's load instructions.
+    uint32_t koff_full[C::IPW], voff_full[C::IPW];
+#pragma unroll
+    for (int i = 0; i < C::IPW; ++i) {
+        const int row = (wave + i * C::WAVES) * C::RPI + r_in;
+        const int kp = pp ^ ((row / (16 / C::PPR)) & (C::PPR - 1));
+        constexpr int CPR = D * 2 / 64, RPL = D == 128 ? 1 : 2;
+        const int vp = (((pp >> 2) ^ ((row / RPL) & (CPR - 1))) << 2) | (pp & 3);
+        koff_full[i] = (uint32_t)row * (D * 2) + kp * 16;
+        voff_full[i] = (uint32_t)row * (D * 2) + vp * 16;
+    }
+
     if (tid == 0) next_slot[0] = atomicAdd(queue + qid, 1);
     __syncthreads();
     int j = __builtin_amdgcn_readfirstlane(next_slot[0]);
@@ -356,16 +369,22 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
         const char* kb = (ctx ? kctx_g : kown) + (size_t)row0 * (D * 2);
         const char* vb = (ctx ? vctx_g : vown) + (size_t)row0 * (D * 2);
         const uint32_t st = lds_base + (uint32_t)(t % NS) * (C::STAGE * 2);
+        if (rlim == kKeyTile - 1) {
 #pragma unroll
-        for (int i = 0; i < C::IPW; ++i) {
-            const int slot = wave + i * C::WAVES;
-            const int row = slot * C::RPI + r_in;
-            const uint32_t roff = (uint32_t)min(row, rlim) * (D * 2);
-            const int kp = pp ^ ((row / (16 / C::PPR)) & (C::PPR - 1));
-            constexpr int CPR = D * 2 / 64, RPL = D == 128 ? 1 : 2;
-            const int vp = (((pp >> 2) ^ ((row / RPL) & (CPR - 1))) << 2) | (pp & 3);
-            dma16(kb, roff + kp * 16, st + slot * 1024);
-            dma16(vb, roff + vp * 16, st + C::TILE * 2 + slot * 1024);
+            for (int i = 0; i < C::IPW; ++i) {
+                const int slot = wave + i * C::WAVES;
+                dma16(kb, koff_full[i], st + slot * 1024);
+                dma16(vb, voff_full[i], st + C::TILE * 2 + slot * 1024);
+            }
+        } else {                                              // rows past the segment's last key repeat it
+#pragma unroll
+            for (int i = 0; i < C::IPW; ++i) {
+                const int slot = wave + i * C::WAVES;
+                const int row = slot * C::RPI + r_in;
+                const uint32_t back_rows = (uint32_t)(row - min(row, rlim)) * (D * 2);
+                dma16(kb, koff_full[i] - back_rows, st + slot * 1024);
+                dma16(vb, voff_full[i] - back_rows, st + C::TILE * 2 + slot * 1024);
+            }
         }
     };
 
