@@ -58,12 +58,26 @@ typedef enum {
     VXL_OP_SCORE_MASS = 4
 } vxl_op;
 
+/*
+ * Heads, element type and memory layout of the per-layer tensors Q, O (query heads) and K, V (KV
+ * heads) over the N tokens of a prompt.  Row (head h, token i) of a tensor starts at element
+ * h * stride_head + i * stride_tok and holds head_dim contiguous elements.  All four strides 0
+ * (the default) selects the dense head-major layout [heads, N, head_dim]; token-major storage
+ * [N, heads, head_dim], as a projection writes it, is stride_head = head_dim, stride_tok =
+ * heads * head_dim.  Strides are in elements, each a multiple of 16 bytes' worth (8 for bf16, 4
+ * for fp32), stride_tok >= head_dim, and either all four are 0 or all four are set; rows must
+ * not overlap (not checked).  O is written in Q's layout.  The mixed KVs, the pooled sparse KVs,
+ * the decode queries Qd and every other buffer keep the dense layouts stated at their calls.
+ */
 typedef struct {
     int32_t n_q_heads;
     int32_t n_kv_heads;
     int32_t head_dim;
     int32_t dtype;           /* vxl_dtype */
     float softmax_scale;     /* 0 selects 1/sqrt(head_dim); otherwise must be > 0 */
+    int32_t reserved;        /* must be 0 */
+    int64_t q_stride_head, q_stride_tok;     /* Q and O */
+    int64_t kv_stride_head, kv_stride_tok;   /* K and V */
 } vxl_attn_desc;
 
 typedef struct vxl_layout vxl_layout;   /* opaque: chunking + kept-token lists of one prompt */
@@ -240,7 +254,8 @@ vxl_status vxl_bilevel_decode(const vxl_attn_desc* desc, const void* Qd, int32_t
  * sparse K/V [n_kv_heads, S_total, head_dim] (kept rows in chunk order, or the pooled rows of
  * vxl_pool_sparse_kv).
  *   vxl_kv_store_create   allocates the pinned memory (hipHostMalloc; synchronous, not a hot call)
- *   vxl_kv_store_offload  device -> host copies of K, V (dense) and Ksp, Vsp (sparse; may be NULL
+ *   vxl_kv_store_offload  device -> host copies of K, V (read in the layout of the descriptor given
+ *                         at creation; the host copy is dense) and Ksp, Vsp (sparse; may be NULL
  *                         when the layout keeps no rows), asynchronous on `stream`; the store may
  *                         be reloaded from once these copies have completed
  *   vxl_kv_store_reload   builds the mixed KV set of `batch` queries in DEVICE memory straight

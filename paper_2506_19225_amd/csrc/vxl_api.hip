@@ -27,6 +27,15 @@ static bool desc_ok(const vxl_attn_desc* d, vxl_status* st) {
     if ((d->dtype != VXL_F32 && d->dtype != VXL_BF16) || (d->head_dim != 64 && d->head_dim != 128)) {
         *st = VXL_ERR_UNSUPPORTED; return false;
     }
+    const int64_t sv[4] = {d->q_stride_head, d->q_stride_tok, d->kv_stride_head, d->kv_stride_tok};
+    const bool any = sv[0] || sv[1] || sv[2] || sv[3];
+    if (any) {                                                // all set, 16-byte multiples, rows of head_dim fit
+        const int64_t unit = d->dtype == VXL_BF16 ? 8 : 4;
+        for (int64_t v : sv)
+            if (v <= 0 || v % unit != 0) { *st = VXL_ERR_INVALID_ARG; return false; }
+        if (d->q_stride_tok < d->head_dim || d->kv_stride_tok < d->head_dim) { *st = VXL_ERR_INVALID_ARG; return false; }
+    }
+    if (d->reserved != 0) { *st = VXL_ERR_INVALID_ARG; return false; }
     return true;
 }
 

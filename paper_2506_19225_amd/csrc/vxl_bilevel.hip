@@ -69,7 +69,8 @@ __device__ __forceinline__ void query_mean_block(const T* __restrict__ Qd, float
 template <typename T, int D>
 __global__ __launch_bounds__(256) void chunk_summarize_kernel(const T* __restrict__ K,
                                                               const int32_t* __restrict__ bounds,
-                                                              float* __restrict__ kbar, int n_tokens,
+                                                              float* __restrict__ kbar, long long kv_head_u4,
+                                                              long long kv_tok_u4,   // K strides, 16-byte units
                                                               int n_chunks, const T* __restrict__ Qd,
                                                               float* __restrict__ qbar, int T_q, int n_q_heads,
                                                               int n_kv_heads) {
@@ -85,7 +86,7 @@ __global__ __launch_bounds__(256) void chunk_summarize_kernel(const T* __restric
     const int c = blockIdx.x, g = blockIdx.y;
     const int piece = threadIdx.x % PPR, rg = threadIdx.x / PPR;
     const int lo = bounds[c], hi = bounds[c + 1];
-    const uint4* base = (const uint4*)(K + (size_t)g * n_tokens * D) + piece;
+    const uint4* base = (const uint4*)K + (size_t)g * kv_head_u4 + piece;
     float acc[4][EPC];
 #pragma unroll
     for (int u = 0; u < 4; ++u)
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(256) void chunk_summarize_kernel(const T* __restric
     for (; r + 3 * RG < hi; r += 4 * RG) {
         uint4 v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = base[(size_t)(r + u * RG) * PPR];
+        for (int u = 0; u < 4; ++u) v[u] = base[(size_t)(r + u * RG) * kv_tok_u4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const T* e = (const T*)&v[u];
@@ -104,7 +105,7 @@ __global__ __launch_bounds__(256) void chunk_summarize_kernel(const T* __restric
         }
     }
     for (int u = 0; r < hi; r += RG, ++u) {
-        const uint4 v = base[(size_t)r * PPR];
+        const uint4 v = base[(size_t)r * kv_tok_u4];
         const T* e = (const T*)&v;
 #pragma unroll
         for (int i = 0; i < EPC; ++i) {
@@ -276,7 +277,8 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void pool_sparse_kernel(const T* __restrict__ K, const T* __restrict__ V,
                                                           const int32_t* __restrict__ bounds,
                                                           const int32_t* __restrict__ soff, int n_chunks,
-                                                          int n_tokens, int s_total, T* __restrict__ Ksp,
+                                                          long long kv_head_u4, long long kv_tok_u4,
+                                                          int s_total, T* __restrict__ Ksp,
                                                           T* __restrict__ Vsp) {
     constexpr int EPC = 16 / (int)sizeof(T);        // elements per 16-byte piece
     constexpr int LPR = D / EPC;                    // lanes per row
@@ -293,10 +295,10 @@ __global__ __launch_bounds__(256) void pool_sparse_kernel(const T* __restrict__ 
     float ak[EPC], av[EPC];
 #pragma unroll
     for (int i = 0; i < EPC; ++i) ak[i] = av[i] = 0.f;
-    const uint4* kp = (const uint4*)(K + (size_t)g * n_tokens * D) + part;
-    const uint4* vp = (const uint4*)(V + (size_t)g * n_tokens * D) + part;
+    const uint4* kp = (const uint4*)K + (size_t)g * kv_head_u4 + part;   // (K, V strides in 16-byte units)
+    const uint4* vp = (const uint4*)V + (size_t)g * kv_head_u4 + part;
     for (int t = lo; t < hi; ++t) {
-        const uint4 kq = kp[(size_t)t * LPR], vq = vp[(size_t)t * LPR];
+        const uint4 kq = kp[(size_t)t * kv_tok_u4], vq = vp[(size_t)t * kv_tok_u4];
         const T* ke = (const T*)&kq;
         const T* ve = (const T*)&vq;
 #pragma unroll
@@ -322,7 +324,8 @@ template <int ROW_BYTES>
 __global__ __launch_bounds__(256) void gather_kernel(
     const uint4* __restrict__ K, const uint4* __restrict__ V, const uint8_t* __restrict__ dense_mask,
     const int32_t* __restrict__ bounds, const int32_t* __restrict__ soff, const int32_t* __restrict__ sidx,
-    int n_chunks, int n_prefix, int n_tokens, int n_kv_heads, int l_cap, int groups, uint4* __restrict__ Kmix,
+    int n_chunks, int n_prefix, long long kv_head_u4, long long kv_tok_u4,   // K, V strides in 16-byte units
+    int n_kv_heads, int l_cap, int groups, uint4* __restrict__ Kmix,
     uint4* __restrict__ Vmix, int32_t* __restrict__ mix_len, int32_t* __restrict__ src_idx,
     const uint4* __restrict__ Ksp, const uint4* __restrict__ Vsp, int s_total) {
     constexpr int LPR = ROW_BYTES / 16;                       // lanes per row
@@ -378,10 +381,11 @@ __global__ __launch_bounds__(256) void gather_kernel(
         if (src_idx && part == 0) src_idx[(size_t)b * l_cap + r] = src;
         const uint4* ks = src >= 0 ? K : Ksp;
         const uint4* vs = src >= 0 ? V : Vsp;
-        const size_t rows = src >= 0 ? (size_t)n_tokens : (size_t)s_total;
-        const size_t row = src >= 0 ? (size_t)src : (size_t)(-1 - src);
+        // the pooled rows are dense [Hkv, S_total, D]; K and V have the caller's strides
+        const size_t head_u4 = src >= 0 ? (size_t)kv_head_u4 : (size_t)s_total * LPR;
+        const size_t row_u4 = src >= 0 ? (size_t)src * kv_tok_u4 : (size_t)(-1 - src) * LPR;
         for (int g = 0; g < n_kv_heads; ++g) {
-            const size_t s_off = (g * rows + row) * LPR + part;
+            const size_t s_off = g * head_u4 + row_u4 + part;
             const size_t d_off = (((size_t)b * n_kv_heads + g) * l_cap + r) * LPR + part;
             const uint4 kv = ks[s_off];
             const uint4 vv = vs[s_off];
@@ -400,9 +404,12 @@ vxl_status launch_summaries(const vxl_layout* L, const vxl_attn_desc* d, const v
     const int nc = do_chunks ? L->n_chunks : 0;
     const dim3 grid(nc + batch, d->n_kv_heads), block(256);
     const size_t smem = (size_t)(d->n_q_heads / d->n_kv_heads) * d->head_dim * sizeof(float);
+    const TokStrides ts = tok_strides(d, L->n_tokens);
+    const long long epc = d->dtype == VXL_BF16 ? 8 : 4;       // elements per 16 bytes
 #define VXL_LAUNCH(T_, D)                                                                         \
     hipLaunchKernelGGL((chunk_summarize_kernel<T_, D>), grid, block, smem, s, (const T_*)K, L->d_bounds, \
-                       kbar, L->n_tokens, nc, (const T_*)Qd, qbar, T, d->n_q_heads, d->n_kv_heads)
+                       kbar, ts.kh / epc, ts.kt / epc, nc, (const T_*)Qd, qbar, T, d->n_q_heads,   \
+                       d->n_kv_heads)
     if (d->dtype == VXL_F32) { if (d->head_dim == 64) VXL_LAUNCH(float, 64); else VXL_LAUNCH(float, 128); }
     else { if (d->head_dim == 64) VXL_LAUNCH(uint16_t, 64); else VXL_LAUNCH(uint16_t, 128); }
 #undef VXL_LAUNCH
@@ -444,9 +451,11 @@ vxl_status launch_pool_sparse(const vxl_layout* L, const vxl_attn_desc* d, const
     const int epc = d->dtype == VXL_BF16 ? 8 : 4;
     const int rows = 256 / (d->head_dim / epc);
     const dim3 grid((L->s_total + rows - 1) / rows, d->n_kv_heads), block(256);
+    const TokStrides ts = tok_strides(d, L->n_tokens);
 #define VXL_LAUNCH(T, D)                                                                            \
     hipLaunchKernelGGL((pool_sparse_kernel<T, D>), grid, block, 0, s, (const T*)K, (const T*)V,      \
-                       L->d_bounds, L->d_soff, L->n_chunks, L->n_tokens, L->s_total, (T*)Ksp, (T*)Vsp)
+                       L->d_bounds, L->d_soff, L->n_chunks, ts.kh / epc, ts.kt / epc, L->s_total,   \
+                       (T*)Ksp, (T*)Vsp)
     if (d->dtype == VXL_F32) { if (d->head_dim == 64) VXL_LAUNCH(float, 64); else VXL_LAUNCH(float, 128); }
     else { if (d->head_dim == 64) VXL_LAUNCH(uint16_t, 64); else VXL_LAUNCH(uint16_t, 128); }
 #undef VXL_LAUNCH
@@ -461,6 +470,8 @@ vxl_status launch_gather(const vxl_layout* L, const vxl_attn_desc* d, const void
     (void)ws_offsets;                                         // (the offsets live in LDS)
     const int row_bytes = d->head_dim * (d->dtype == VXL_BF16 ? 2 : 4);
     const size_t smem = (size_t)(L->n_chunks + 1) * sizeof(int);
+    const TokStrides ts = tok_strides(d, L->n_tokens);
+    const long long epc = d->dtype == VXL_BF16 ? 8 : 4;
 #define VXL_LAUNCH(RB)                                                                             \
     do {                                                                                           \
         constexpr int rows = 256 / (RB / 16);                                                      \
@@ -469,7 +480,8 @@ vxl_status launch_gather(const vxl_layout* L, const vxl_attn_desc* d, const void
         const dim3 grid((unsigned)((passes + groups - 1) / groups), batch);                        \
         hipLaunchKernelGGL((gather_kernel<RB>), grid, dim3(256), smem, s, (const uint4*)K,         \
                            (const uint4*)V, dense_mask, L->d_bounds, L->d_soff, L->d_sidx,         \
-                           L->n_chunks, L->n_prefix, L->n_tokens, d->n_kv_heads, l_cap, groups,    \
+                           L->n_chunks, L->n_prefix, ts.kh / epc, ts.kt / epc, d->n_kv_heads,      \
+                           l_cap, groups,                                                         \
                            (uint4*)Kmix, (uint4*)Vmix, mix_len, src_idx, (const uint4*)Ksp,        \
                            (const uint4*)Vsp, L->s_total);                                         \
     } while (0)

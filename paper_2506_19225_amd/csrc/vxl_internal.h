@@ -86,6 +86,17 @@ void set_last_error(const char* what, hipError_t e);
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- pre-filling ----
+// Element strides of the per-layer tensors (the descriptor's, or the dense head-major default).
+struct TokStrides {
+    long long qh, qt, kh, kt;
+};
+inline TokStrides tok_strides(const vxl_attn_desc* d, int n_tokens) {
+    if (d->q_stride_tok == 0)
+        return {(long long)n_tokens * d->head_dim, d->head_dim, (long long)n_tokens * d->head_dim, d->head_dim};
+    return {d->q_stride_head, d->q_stride_tok, d->kv_stride_head, d->kv_stride_tok};
+}
+inline bool dense_layout(const vxl_attn_desc* d) { return d->q_stride_tok == 0; }
+
 struct PrefillWorkspace {      // byte offsets into the caller's workspace (bf16 path)
     size_t kctx;               // [Hkv][n_ctx_tiles*64][D] compacted history keys
     size_t vctx;               // [Hkv][n_ctx_tiles*64][D] compacted history values

@@ -33,8 +33,8 @@ struct KTileRegs {
     uint4 k0, k1, k2, k3;
     // kb: wave-uniform byte pointer to row 0 of the tile; rows beyond rlim are clamped to it (the
     // caller masks their scores).
-    __device__ __forceinline__ void fetch(const char* kb, int ld_r, int ld_part, int rlim) {
-#define VXL_TILE_OFF(i_) ((uint32_t)min(ld_r + (i_) * RPP, rlim) * (D * 2) + ld_part * 16)
+    __device__ __forceinline__ void fetch(const char* kb, int ld_r, int ld_part, int rlim, uint32_t row_bytes) {
+#define VXL_TILE_OFF(i_) ((uint32_t)min(ld_r + (i_) * RPP, rlim) * row_bytes + ld_part * 16)
         k0 = *(const uint4*)(kb + VXL_TILE_OFF(0));
         k1 = *(const uint4*)(kb + VXL_TILE_OFF(1));
         if constexpr (LD > 2) {
@@ -60,7 +60,7 @@ template <int D>
 __global__ __launch_bounds__(256, 2) void mass_partial_kernel(
     const uint16_t* __restrict__ Qd, const uint16_t* __restrict__ K, const MassItem* __restrict__ items,
     float* __restrict__ part_m, float* __restrict__ part_l, int T_q, int n_q_heads, int n_kv_heads, int group,
-    int n_tokens, int n_items, float scale) {
+    long long kv_head, long long kv_tok, int n_items, float scale) {   // K strides in elements
     __shared__ __attribute__((aligned(16))) uint16_t Ks[2][kKeyTile * D];
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -83,11 +83,12 @@ __global__ __launch_bounds__(256, 2) void mass_partial_kernel(
     float m_run = -INFINITY, l_run = 0.f;
     const float c2 = scale * kLog2e;
 
-    const char* kbase = (const char*)(K + (size_t)g * n_tokens * D);
+    const char* kbase = (const char*)(K + (size_t)g * kv_head);
+    const uint32_t row_bytes = (uint32_t)kv_tok * 2;
     const int ld_r = tid / (D / 8), ld_part = tid % (D / 8);
     KTileRegs<D> tr;
     const int n_t = (k_hi - k_lo + kKeyTile - 1) / kKeyTile;
-    tr.fetch(kbase + (size_t)k_lo * (D * 2), ld_r, ld_part, min(kKeyTile - 1, k_hi - 1 - k_lo));
+    tr.fetch(kbase + (size_t)k_lo * row_bytes, ld_r, ld_part, min(kKeyTile - 1, k_hi - 1 - k_lo), row_bytes);
     tr.stage(Ks[0], ld_r, ld_part);
     __syncthreads();
     for (int ti = 0; ti < n_t; ++ti) {
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(256, 2) void mass_partial_kernel(
         const int key0 = k_lo + ti * kKeyTile;
         {   // next tile (the last iteration re-reads its own), in flight during the arithmetic
             const int nk0 = k_lo + min(ti + 1, n_t - 1) * kKeyTile;
-            tr.fetch(kbase + (size_t)nk0 * (D * 2), ld_r, ld_part, min(kKeyTile - 1, k_hi - 1 - nk0));
+            tr.fetch(kbase + (size_t)nk0 * row_bytes, ld_r, ld_part, min(kKeyTile - 1, k_hi - 1 - nk0), row_bytes);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (wave_active) {
@@ -155,14 +156,14 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void mass_partial_simple_kernel(
     const T* __restrict__ Qd, const T* __restrict__ K, const MassItem* __restrict__ items,
     float* __restrict__ part_m, float* __restrict__ part_l, int T_q, int n_q_heads, int n_kv_heads, int group,
-    int n_tokens, int n_items, float scale) {
+    long long kv_head, long long kv_tok, int n_items, float scale) {   // K strides in elements
     __shared__ float q_lds[4][D];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int item = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int n_rows = group * T_q;
     const int k_lo = items[item].key_lo, k_hi = items[item].key_hi;
     const float c2 = scale * kLog2e;
-    const T* kbase = K + (size_t)g * n_tokens * D;
+    const T* kbase = K + (size_t)g * kv_head;
     for (int rho = wave; rho < n_rows; rho += 4) {
         const int t = rho / group, hg = rho % group;
         const T* qrow = Qd + (((size_t)b * T_q + t) * n_q_heads + g * group + hg) * D;
@@ -176,7 +177,7 @@ __global__ __launch_bounds__(256) void mass_partial_simple_kernel(
             const bool valid = j < k_hi;
             float s = -INFINITY;
             if (valid) {
-                const T* kp = kbase + (size_t)j * D;
+                const T* kp = kbase + (size_t)j * kv_tok;
                 float a = 0.f;
 #pragma unroll 8
                 for (int d = 0; d < D; ++d) a = fmaf(q_lds[wave][d], ldf(kp + d), a);
@@ -295,13 +296,14 @@ vxl_status launch_score_mass(const vxl_layout* L, const vxl_attn_desc* d, float 
     const int group = d->n_q_heads / d->n_kv_heads;
     const int n_rows = group * T;
     const int n_items = L->n_mass_items;
+    const TokStrides ts = tok_strides(d, L->n_tokens);
     if (d->dtype == VXL_BF16 && !force_simple) {
         const int n_rt = (n_rows + kMassRowTile - 1) / kMassRowTile;
         const dim3 grid(n_items, n_rt * d->n_kv_heads, batch);
 #define VXL_LAUNCH(D)                                                                                   \
     hipLaunchKernelGGL((mass_partial_kernel<D>), grid, dim3(256), 0, s, (const uint16_t*)Qd,            \
                        (const uint16_t*)K, L->d_mass_items, part_m, part_l, T, d->n_q_heads,            \
-                       d->n_kv_heads, group, L->n_tokens, n_items, scale)
+                       d->n_kv_heads, group, ts.kh, ts.kt, n_items, scale)
         if (d->head_dim == 64) VXL_LAUNCH(64); else VXL_LAUNCH(128);
 #undef VXL_LAUNCH
     } else {
@@ -309,7 +311,7 @@ vxl_status launch_score_mass(const vxl_layout* L, const vxl_attn_desc* d, float 
 #define VXL_LAUNCH(T_, D)                                                                               \
     hipLaunchKernelGGL((mass_partial_simple_kernel<T_, D>), grid, dim3(256), 0, s, (const T_*)Qd,       \
                        (const T_*)K, L->d_mass_items, part_m, part_l, T, d->n_q_heads, d->n_kv_heads,   \
-                       group, L->n_tokens, n_items, scale)
+                       group, ts.kh, ts.kt, n_items, scale)
         if (d->dtype == VXL_F32) { if (d->head_dim == 64) VXL_LAUNCH(float, 64); else VXL_LAUNCH(float, 128); }
         else { if (d->head_dim == 64) VXL_LAUNCH(uint16_t, 64); else VXL_LAUNCH(uint16_t, 128); }
 #undef VXL_LAUNCH

@@ -122,6 +122,35 @@ __device__ __forceinline__ void qk_tile(const uint16_t* kt, const bf16x8 (&qreg)
         }
 }
 
+// The same product for one row block with the K operands requested AHEAD steps before the matrix
+// instructions that use them, the order pinned for the scheduler: (AHEAD + 1) x 2 operand reads,
+// then per step two matrix instructions followed by the two reads of step + AHEAD + 1.  Left to
+// itself the compiler reads an operand pair right before its two instructions and, depending on
+// unrelated code, waits for both reads before the first instruction.
+template <int D, int AHEAD>
+__device__ __forceinline__ void qk_tile_ahead(const uint16_t* kt, const bf16x8 (&qreg)[1][D / 16], int l32, int hi,
+                                              f32x16 (&s)[1][2]) {
+    constexpr int NK = D / 16;
+    s[0][0] = zero16();
+    s[0][1] = zero16();
+    bf16x8 a[NK][2];
+#pragma unroll
+    for (int ks = 0; ks < NK; ++ks)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) a[ks][kb] = *(const bf16x8*)(kt + k_tile_off<D>(kb * 32 + l32, ks * 2 + hi));
+#pragma unroll
+    for (int ks = 0; ks < NK; ++ks)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+            s[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][kb], qreg[0][ks], s[0][kb], 0, 0, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * (AHEAD + 1), 0);          // LDS reads
+#pragma unroll
+    for (int ks = 0; ks < NK; ++ks) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                    // matrix instructions
+        if (ks + AHEAD + 1 < NK) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+}
+
 // Online-softmax update of one query block.  m_run is the reference logit of the running
 // exponentials (raw units), l_run this lane's half of the running sum, c2 = softmax_scale*log2(e).
 // The reference is raised -- and l_run and the output accumulators rescaled -- only when some

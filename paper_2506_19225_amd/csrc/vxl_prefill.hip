@@ -33,13 +33,14 @@ template <int D>
 __global__ __launch_bounds__(256) void compact_kv_kernel(const uint4* __restrict__ K, const uint4* __restrict__ V,
                                                          const int32_t* __restrict__ tile_src,
                                                          uint4* __restrict__ Kctx, uint4* __restrict__ Vctx,
-                                                         int n_rows_pad, int n_tokens, int* __restrict__ queue) {
+                                                         int n_rows_pad, long long kv_head_u4, long long kv_tok_u4,
+                                                         int* __restrict__ queue) {
     constexpr int LPR = D * 2 / 16, ROWS = 256 / LPR;
     if (queue && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 8) queue[threadIdx.x] = 0;
     const int r = blockIdx.x * ROWS + threadIdx.x / LPR, part = threadIdx.x % LPR, g = blockIdx.y;
     if (r >= n_rows_pad) return;
     const int src = tile_src[r];
-    const size_t so = ((size_t)g * n_tokens + max(src, 0)) * LPR + part;
+    const size_t so = (size_t)g * kv_head_u4 + (size_t)max(src, 0) * kv_tok_u4 + part;   // (strides in 16-byte units)
     const size_t dk = ((size_t)g * n_rows_pad + r) * LPR + part;
     Kctx[dk] = src >= 0 ? K[so] : zero4();
     Vctx[dk] = src >= 0 ? V[so] : zero4();
@@ -286,14 +287,20 @@ struct PrefillDmaCfg {
 // scheduling without gaps between workgroups.  With xpg > 0 there is one queue per KV head group,
 // served by the xpg XCDs (blockIdx.x % 8, the order workgroups are dealt out in) whose L2 then
 // holds that group's K and V; otherwise a single queue.  The counters must be zero at launch.
-template <int D, int NS>
+template <int D, int NS, bool STRIDED>
 __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     const uint16_t* __restrict__ Kctx, const uint16_t* __restrict__ Vctx, uint16_t* __restrict__ O,
     float* __restrict__ LSE, const Segment* __restrict__ segs, const WorkItem* __restrict__ work,
     int n_tokens, int n_q_heads, int group, int ctx_rows_pad, float scale, int n_items, int xpg,
-    int* __restrict__ queue) {
+    int* __restrict__ queue, long long q_head_arg, int q_tok_arg, long long kv_head_arg, int kv_tok_arg) {
     using C = PrefillDmaCfg<D, NS>;
+    // Element strides of Q/O and K/V rows: the arguments, or (STRIDED false, the dense head-major
+    // layout) constants, so that the dense instance carries no stride arithmetic or registers.
+    const long long q_head = STRIDED ? q_head_arg : (long long)n_tokens * D;
+    const long long kv_head = STRIDED ? kv_head_arg : (long long)n_tokens * D;
+    const int q_tok = STRIDED ? q_tok_arg : D;
+    const int kv_tok = STRIDED ? kv_tok_arg : D;
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
     int* next_slot = (int*)(lds + NS * C::STAGE);
@@ -306,16 +313,19 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     const int r_in = lane / C::PPR, pp = lane % C::PPR;
 
     // Lane-constant parts of the refill addresses of a full tile: row and (swizzled) 16-byte piece
-    // of this lane in each of the wave's load instructions.
-    uint32_t koff_full[C::IPW], voff_full[C::IPW];
+    // of this lane in each of the wave's load instructions -- for the compact history tiles
+    // (rows D elements apart) and for the own tiles, read in place (rows kv_tok elements apart).
+    uint32_t koff_ctx[C::IPW], voff_ctx[C::IPW], koff_own[C::IPW], voff_own[C::IPW];
 #pragma unroll
     for (int i = 0; i < C::IPW; ++i) {
         const int row = (wave + i * C::WAVES) * C::RPI + r_in;
         const int kp = pp ^ ((row / (16 / C::PPR)) & (C::PPR - 1));
         constexpr int CPR = D * 2 / 64, RPL = D == 128 ? 1 : 2;
         const int vp = (((pp >> 2) ^ ((row / RPL) & (CPR - 1))) << 2) | (pp & 3);
-        koff_full[i] = (uint32_t)row * (D * 2) + kp * 16;
-        voff_full[i] = (uint32_t)row * (D * 2) + vp * 16;
+        koff_ctx[i] = (uint32_t)row * (D * 2) + kp * 16;
+        voff_ctx[i] = (uint32_t)row * (D * 2) + vp * 16;
+        koff_own[i] = STRIDED ? (uint32_t)row * (uint32_t)(kv_tok * 2) + kp * 16 : koff_ctx[i];
+        voff_own[i] = STRIDED ? (uint32_t)row * (uint32_t)(kv_tok * 2) + vp * 16 : voff_ctx[i];
     }
 
     if (tid == 0) next_slot[0] = atomicAdd(queue + qid, 1);
@@ -358,32 +368,40 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
 
     const char* kctx_g = (const char*)(Kctx + (size_t)g * ctx_rows_pad * D);
     const char* vctx_g = (const char*)(Vctx + (size_t)g * ctx_rows_pad * D);
-    const char* kown = (const char*)(K + ((size_t)g * n_tokens + sg.q_start - sg.back) * D);
-    const char* vown = (const char*)(V + ((size_t)g * n_tokens + sg.q_start - sg.back) * D);
+    const char* kown = (const char*)(K + (size_t)g * kv_head + (size_t)(sg.q_start - sg.back) * kv_tok);
+    const char* vown = (const char*)(V + (size_t)g * kv_head + (size_t)(sg.q_start - sg.back) * kv_tok);
 
     // Tile t -> stage t % NS.  Every wave issues GROUP loads: instruction slots wave, wave + 8, ...
     auto issue = [&](int t) {
         const bool ctx = t < n_ctx_t;
         const int row0 = ctx ? t * kKeyTile : (t - n_ctx_t) * kKeyTile;
         const int rlim = ctx ? kKeyTile - 1 : min(kKeyTile - 1, sg.back + sg.q_len - 1 - row0);
-        const char* kb = (ctx ? kctx_g : kown) + (size_t)row0 * (D * 2);
-        const char* vb = (ctx ? vctx_g : vown) + (size_t)row0 * (D * 2);
+        const uint32_t row_bytes = ctx ? D * 2 : (uint32_t)kv_tok * 2;
+        const char* kb = (ctx ? kctx_g : kown) + (size_t)row0 * row_bytes;
+        const char* vb = (ctx ? vctx_g : vown) + (size_t)row0 * row_bytes;
         const uint32_t st = lds_base + (uint32_t)(t % NS) * (C::STAGE * 2);
-        if (rlim == kKeyTile - 1) {
+        if (STRIDED && ctx) {
 #pragma unroll
             for (int i = 0; i < C::IPW; ++i) {
                 const int slot = wave + i * C::WAVES;
-                dma16(kb, koff_full[i], st + slot * 1024);
-                dma16(vb, voff_full[i], st + C::TILE * 2 + slot * 1024);
+                dma16(kb, koff_ctx[i], st + slot * 1024);
+                dma16(vb, voff_ctx[i], st + C::TILE * 2 + slot * 1024);
+            }
+        } else if (rlim == kKeyTile - 1) {
+#pragma unroll
+            for (int i = 0; i < C::IPW; ++i) {
+                const int slot = wave + i * C::WAVES;
+                dma16(kb, koff_own[i], st + slot * 1024);
+                dma16(vb, voff_own[i], st + C::TILE * 2 + slot * 1024);
             }
         } else {                                              // rows past the segment's last key repeat it
 #pragma unroll
             for (int i = 0; i < C::IPW; ++i) {
                 const int slot = wave + i * C::WAVES;
                 const int row = slot * C::RPI + r_in;
-                const uint32_t back_rows = (uint32_t)(row - min(row, rlim)) * (D * 2);
-                dma16(kb, koff_full[i] - back_rows, st + slot * 1024);
-                dma16(vb, voff_full[i] - back_rows, st + C::TILE * 2 + slot * 1024);
+                const uint32_t back_rows = (uint32_t)(row - min(row, rlim)) * row_bytes;
+                dma16(kb, koff_own[i] - back_rows, st + slot * 1024);
+                dma16(vb, voff_own[i] - back_rows, st + C::TILE * 2 + slot * 1024);
             }
         }
     };
@@ -410,8 +428,8 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     bf16x8 qreg[1][D / 16];
     {
         // uniform base + 32-bit lane offset: the address stays out of the vector registers
-        const char* qbase = (const char*)(Q + ((size_t)h * n_tokens + sg.q_start) * D);
-        const uint32_t qoff = (uint32_t)min(wrow0 + l32, sg.q_len - 1) * (D * 2) + hi * 16;
+        const char* qbase = (const char*)(Q + (size_t)h * q_head + (size_t)sg.q_start * q_tok);
+        const uint32_t qoff = (uint32_t)min(wrow0 + l32, sg.q_len - 1) * (uint32_t)(q_tok * 2) + hi * 16;
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks)
             qreg[0][ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qbase + qoff + ks * 32));
@@ -433,7 +451,7 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
             const uint16_t* kt = lds + (ti % NS) * C::STAGE;
             const uint16_t* vt = kt + C::TILE;
             f32x16 s[1][2];
-            qk_tile<D, 1, D>(kt, qreg, l32, hi, s);
+            qk_tile_ahead<D, 1>(kt, qreg, l32, hi, s);
             const bool need_mask = is_ctx ? (key0 + kKeyTile > sg.ctx_len) : (key0 + kKeyTile - 1 > wrow0 + sg.back);
             if (need_mask) {
                 const int lim = is_ctx ? sg.ctx_len - key0 - 1 : wrow0 + sg.back + l32 - key0;
@@ -471,8 +489,8 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
         if (q_off < sg.q_len && !idle) {
             const float inv = 1.f / l_tot;
             // uniform bases + 32-bit lane offsets, as for the query loads
-            char* obase = (char*)(O + ((size_t)h * n_tokens + sg.q_start) * D);
-            const uint32_t ooff = (uint32_t)q_off * (D * 2) + hi * 8;
+            char* obase = (char*)(O + (size_t)h * q_head + (size_t)sg.q_start * q_tok);
+            const uint32_t ooff = (uint32_t)q_off * (uint32_t)(q_tok * 2) + hi * 8;
 #pragma unroll
             for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -527,6 +545,8 @@ template <int D, int QB>
 static vxl_status run_prefill(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Q,
                               const void* K, const void* V, void* O, float* LSE, void* ws, hipStream_t s) {
     using C = PrefillCfg<D, QB>;
+    if (!dense_layout(d)) return VXL_ERR_UNSUPPORTED;          // (the cross-check kernels read dense tensors only)
+    const TokStrides ts = tok_strides(d, L->n_tokens);
     const PrefillWorkspace w = prefill_workspace(L, d);
     uint16_t* kctx = (uint16_t*)((char*)ws + w.kctx);
     uint16_t* vctx = (uint16_t*)((char*)ws + w.vctx);
@@ -535,7 +555,7 @@ static vxl_status run_prefill(const vxl_layout* L, const vxl_attn_desc* d, float
         constexpr int rows = 256 / (D * 2 / 16);
         hipLaunchKernelGGL((compact_kv_kernel<D>), dim3((n_rows_pad + rows - 1) / rows, d->n_kv_heads),
                            dim3(256), 0, s, (const uint4*)K, (const uint4*)V, L->d_tile_src, (uint4*)kctx,
-                           (uint4*)vctx, n_rows_pad, L->n_tokens, (int*)nullptr);
+                           (uint4*)vctx, n_rows_pad, ts.kh / 8, ts.kt / 8, (int*)nullptr);
         VXL_HIP_TRY(hipGetLastError());
     }
     static bool attr_done = false;
@@ -577,6 +597,12 @@ template <int D, int NS>
 static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Q,
                                   const void* K, const void* V, void* O, float* LSE, void* ws, hipStream_t s) {
     using C = PrefillDmaCfg<D, NS>;
+    const TokStrides ts = tok_strides(d, L->n_tokens);
+    // 32-bit byte offsets inside a segment's rows (longest segment plus its look-back)
+    long long max_rows = 0;
+    for (const Segment& sg : L->segs) max_rows = std::max<long long>(max_rows, (long long)sg.q_len + sg.back);
+    if (max_rows * std::max(ts.qt, ts.kt) * 2 >= (1ll << 32) || ts.qt >= (1ll << 30) || ts.kt >= (1ll << 30))
+        return VXL_ERR_UNSUPPORTED;
     const PrefillWorkspace w = prefill_workspace(L, d);
     uint16_t* kctx = (uint16_t*)((char*)ws + w.kctx);
     uint16_t* vctx = (uint16_t*)((char*)ws + w.vctx);
@@ -586,14 +612,15 @@ static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, f
         constexpr int rows = 256 / (D * 2 / 16);
         hipLaunchKernelGGL((compact_kv_kernel<D>), dim3((n_rows_pad + rows - 1) / rows, d->n_kv_heads),
                            dim3(256), 0, s, (const uint4*)K, (const uint4*)V, L->d_tile_src, (uint4*)kctx,
-                           (uint4*)vctx, n_rows_pad, L->n_tokens, queue);
+                           (uint4*)vctx, n_rows_pad, ts.kh / 8, ts.kt / 8, queue);
     } else {
         hipLaunchKernelGGL(reset_queue_kernel, dim3(1), dim3(64), 0, s, queue);
     }
     VXL_HIP_TRY(hipGetLastError());
     static bool attr_done = false;
     if (!attr_done) {
-        vxl_status st = enable_big_lds(prefill_dma_kernel<D, NS>, C::LDS_BYTES);
+        vxl_status st = enable_big_lds(prefill_dma_kernel<D, NS, false>, C::LDS_BYTES);
+        if (st == VXL_OK) st = enable_big_lds(prefill_dma_kernel<D, NS, true>, C::LDS_BYTES);
         if (st != VXL_OK) return st;
         attr_done = true;
     }
@@ -607,6 +634,7 @@ static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, f
     const bool timed = g_ev_start && g_ev_stop;
     if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_start, s));
     if (g_prefill_variant == 3) {
+        if (!dense_layout(d)) return VXL_ERR_UNSUPPORTED;
         const vxl_status st = launch_prefill_pipe_main(L, d, scale, Q, K, V, kctx, vctx, O, LSE, queue, s);
         if (st != VXL_OK) return st;
         if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_stop, s));
@@ -617,10 +645,13 @@ static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, f
     const long long n_pairs = (long long)L->n_work[1] * d->n_q_heads;
     // no more workgroups than pairs (rounded up to whole rounds over the 8 XCDs when queues are per XCD group)
     const unsigned n_blocks = (unsigned)std::min<long long>(n_cus / 8 * 8, xpg ? (n_pairs + 7) / 8 * 8 : n_pairs);
-    hipLaunchKernelGGL((prefill_dma_kernel<D, NS>), dim3(n_blocks), dim3(512), C::LDS_BYTES, s,
-                       (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V, kctx, vctx, (uint16_t*)O, LSE,
-                       L->d_segs, L->d_work[1], L->n_tokens, d->n_q_heads, group, n_rows_pad, scale,
-                       L->n_work[1], xpg, queue);
+#define VXL_LAUNCH(STRIDED_)                                                                             \
+    hipLaunchKernelGGL((prefill_dma_kernel<D, NS, STRIDED_>), dim3(n_blocks), dim3(512), C::LDS_BYTES, s, \
+                       (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V, kctx, vctx,           \
+                       (uint16_t*)O, LSE, L->d_segs, L->d_work[1], L->n_tokens, d->n_q_heads, group,      \
+                       n_rows_pad, scale, L->n_work[1], xpg, queue, ts.qh, (int)ts.qt, ts.kh, (int)ts.kt)
+    if (dense_layout(d)) VXL_LAUNCH(false); else VXL_LAUNCH(true);
+#undef VXL_LAUNCH
     VXL_HIP_TRY(hipGetLastError());
     if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_stop, s));
     return VXL_OK;

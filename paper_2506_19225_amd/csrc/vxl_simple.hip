@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256) void prefill_simple_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ LSE, const int32_t* __restrict__ bounds, const int32_t* __restrict__ soff,
     const int32_t* __restrict__ sidx, int n_tokens, int n_prefix, int n_chunks, int group,
-    float scale, int window) {
+    float scale, int window, long long q_head, long long q_tok, long long kv_head_stride, long long kv_tok) {
     __shared__ float q_lds[4][D];
     const int wave = threadIdx.x >> 6;
     const int i = blockIdx.x * 4 + wave;
@@ -110,10 +110,10 @@ __global__ __launch_bounds__(256) void prefill_simple_kernel(
         int tok;
         if (slot < n_hist) tok = slot < n_prefix ? slot : sidx[slot - n_prefix];
         else tok = own_start + (slot - n_hist);
-        return (size_t)tok * D;
+        return (size_t)tok * kv_tok;
     };
-    const size_t kv_head = (size_t)g * n_tokens * D;
-    const size_t q_off = ((size_t)h * n_tokens + i) * D;
+    const size_t kv_head = (size_t)g * kv_head_stride;
+    const size_t q_off = (size_t)h * q_head + (size_t)i * q_tok;
     attend_row<T, D>(Q + q_off, K + kv_head, V + kv_head, key, n_keys, scale, q_lds[wave], O + q_off,
                      LSE ? LSE + (size_t)h * n_tokens + i : nullptr);
 }
@@ -152,10 +152,11 @@ vxl_status launch_prefill_simple(const vxl_layout* L, const vxl_attn_desc* d, fl
                                  hipStream_t s) {
     const dim3 grid((L->n_tokens + 3) / 4, d->n_q_heads), block(256);
     const int group = d->n_q_heads / d->n_kv_heads;
+    const TokStrides ts = tok_strides(d, L->n_tokens);
 #define VXL_LAUNCH(T, D)                                                                          \
     hipLaunchKernelGGL((prefill_simple_kernel<T, D>), grid, block, 0, s, (const T*)Q, (const T*)K, \
                        (const T*)V, (T*)O, LSE, L->d_bounds, L->d_soff, L->d_sidx, L->n_tokens,   \
-                       L->n_prefix, L->n_chunks, group, scale, L->window)
+                       L->n_prefix, L->n_chunks, group, scale, L->window, ts.qh, ts.qt, ts.kh, ts.kt)
     if (d->dtype == VXL_F32) { if (d->head_dim == 64) VXL_LAUNCH(float, 64); else VXL_LAUNCH(float, 128); }
     else { if (d->head_dim == 64) VXL_LAUNCH(uint16_t, 64); else VXL_LAUNCH(uint16_t, 128); }
 #undef VXL_LAUNCH

@@ -20,6 +20,8 @@ struct vxl_kv_store {
     int32_t n_tokens = 0, n_prefix = 0, n_chunks = 0, s_total = 0;
     int32_t n_kv_heads = 0, head_dim = 0;
     size_t elem = 0;
+    bool strided = false;                  // the device K, V are not dense [Hkv, N, D]
+    long long kv_head = 0, kv_tok = 0;     // their strides, in elements
     std::vector<int32_t> bounds, soff;
     // pinned host memory (one allocation): dense K, dense V, sparse K, sparse V, mix_len staging
     void* h_blob = nullptr;
@@ -43,11 +45,15 @@ vxl_status vxl_kv_store_create(const vxl_layout* L, const vxl_attn_desc* d, vxl_
     if (d->n_kv_heads <= 0 || (d->head_dim != 64 && d->head_dim != 128) ||
         (d->dtype != VXL_F32 && d->dtype != VXL_BF16))
         return VXL_ERR_UNSUPPORTED;
+    if (!dense_layout(d) && (d->kv_stride_head <= 0 || d->kv_stride_tok < d->head_dim)) return VXL_ERR_INVALID_ARG;
     vxl_kv_store* S = new (std::nothrow) vxl_kv_store();
     if (!S) return VXL_ERR_INVALID_ARG;
     S->n_tokens = L->n_tokens; S->n_prefix = L->n_prefix; S->n_chunks = L->n_chunks; S->s_total = L->s_total;
     S->n_kv_heads = d->n_kv_heads; S->head_dim = d->head_dim;
     S->elem = d->dtype == VXL_BF16 ? 2 : 4;
+    const TokStrides ts = tok_strides(d, L->n_tokens);
+    S->strided = !dense_layout(d);
+    S->kv_head = ts.kh; S->kv_tok = ts.kt;
     S->bounds = L->bounds; S->soff = L->soff;
     const size_t dense = align_up((size_t)S->n_kv_heads * S->n_tokens * S->head_dim * S->elem, 256);
     const size_t sparse = align_up((size_t)S->n_kv_heads * std::max(1, S->s_total) * S->head_dim * S->elem, 256);
@@ -88,8 +94,19 @@ vxl_status vxl_kv_store_offload(vxl_kv_store* S, const void* K, const void* V, c
     hipStream_t s = (hipStream_t)stream;
     const size_t dense = (size_t)S->n_kv_heads * S->n_tokens * S->head_dim * S->elem;
     const size_t sparse = (size_t)S->n_kv_heads * S->s_total * S->head_dim * S->elem;
-    VXL_HIP_TRY(hipMemcpyAsync(S->h_k, K, dense, hipMemcpyDeviceToHost, s));
-    VXL_HIP_TRY(hipMemcpyAsync(S->h_v, V, dense, hipMemcpyDeviceToHost, s));
+    if (!S->strided) {
+        VXL_HIP_TRY(hipMemcpyAsync(S->h_k, K, dense, hipMemcpyDeviceToHost, s));
+        VXL_HIP_TRY(hipMemcpyAsync(S->h_v, V, dense, hipMemcpyDeviceToHost, s));
+    } else {                                                  // the host copy is dense: one strided copy per KV head
+        const size_t row = (size_t)S->head_dim * S->elem, head = (size_t)S->n_tokens * row;
+        for (int g = 0; g < S->n_kv_heads; ++g) {
+            const size_t src = (size_t)g * S->kv_head * S->elem;
+            VXL_HIP_TRY(hipMemcpy2DAsync(S->h_k + g * head, row, (const char*)K + src, (size_t)S->kv_tok * S->elem,
+                                         row, S->n_tokens, hipMemcpyDeviceToHost, s));
+            VXL_HIP_TRY(hipMemcpy2DAsync(S->h_v + g * head, row, (const char*)V + src, (size_t)S->kv_tok * S->elem,
+                                         row, S->n_tokens, hipMemcpyDeviceToHost, s));
+        }
+    }
     if (sparse) {
         VXL_HIP_TRY(hipMemcpyAsync(S->h_ksp, Ksp, sparse, hipMemcpyDeviceToHost, s));
         VXL_HIP_TRY(hipMemcpyAsync(S->h_vsp, Vsp, sparse, hipMemcpyDeviceToHost, s));

@@ -22,7 +22,9 @@ MAX_CHUNKS = 4096
 
 class AttnDesc(C.Structure):
     _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
-                ("dtype", C.c_int32), ("softmax_scale", C.c_float)]
+                ("dtype", C.c_int32), ("softmax_scale", C.c_float), ("reserved", C.c_int32),
+                ("q_stride_head", C.c_int64), ("q_stride_tok", C.c_int64),
+                ("kv_stride_head", C.c_int64), ("kv_stride_tok", C.c_int64)]
 
 
 class VxlError(RuntimeError):
@@ -113,14 +115,19 @@ def _stream(stream) -> Optional[int]:
     return stream.cuda_stream or None
 
 
-def make_desc(n_q_heads: int, n_kv_heads: int, head_dim: int, dtype, softmax_scale: float = 0.0) -> AttnDesc:
+def make_desc(n_q_heads: int, n_kv_heads: int, head_dim: int, dtype, softmax_scale: float = 0.0,
+              token_major: bool = False) -> AttnDesc:
+    """token_major: Q/O are stored [N, Hq, D] and K/V [N, Hkv, D] instead of head-major."""
     if dtype in (torch.bfloat16, "bf16", VXL_BF16):
         code = VXL_BF16
     elif dtype in (torch.float32, "f32", VXL_F32):
         code = VXL_F32
     else:
         raise ValueError(f"unsupported dtype {dtype}")
-    return AttnDesc(n_q_heads, n_kv_heads, head_dim, code, float(softmax_scale))
+    if token_major:
+        return AttnDesc(n_q_heads, n_kv_heads, head_dim, code, float(softmax_scale), 0,
+                        head_dim, n_q_heads * head_dim, head_dim, n_kv_heads * head_dim)
+    return AttnDesc(n_q_heads, n_kv_heads, head_dim, code, float(softmax_scale), 0, 0, 0, 0, 0)
 
 
 def torch_dtype(desc: AttnDesc):

@@ -1,0 +1,150 @@
+"""Token-major storage (Q/O as [N, Hq, D], K/V as [N, Hkv, D], selected by the descriptor's strides):
+every call that reads the per-layer tensors must give the oracle's result for the pre-filling
+output, and bit for bit what the same call gives on head-major copies of the same values."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_19225_amd import vxl, workloads as wl
+
+from gpu_util import assert_close, make_layout
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # (dtype, Hq, Hkv, D, P, n_chunks, len_lo, len_hi, seed)
+    ("f32", 4, 2, 64, 5, 3, 3, 70, 301),
+    ("bf16", 14, 2, 128, 33, 3, 100, 400, 302),
+    ("bf16", 6, 2, 64, 0, 4, 20, 130, 303),
+]
+
+
+def both_layouts(w, x):
+    """Device copies of a [H, N, D] host array: head-major, and token-major [N, H, D]."""
+    d = vxl.to_device(x, w.dtype)
+    return d, d.permute(1, 0, 2).contiguous()
+
+
+def descs(w):
+    return (vxl.make_desc(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype),
+            vxl.make_desc(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, token_major=True))
+
+
+def setup(case):
+    dtype, hq, hkv, d, p, n_chunks, lo, hi, seed = case
+    w = wl.tiny_workload(dtype, hq, hkv, d, T=3, B=2, k=2, seed=seed, value_scale=0.5)
+    lay = wl.random_layout(np.random.default_rng(seed), p, n_chunks, lo, hi)
+    q, k, v = wl.make_qkv(w, lay)
+    return w, lay, q, k, v
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: f"{c[0]}-h{c[1]}-d{c[3]}")
+def test_prefill_token_major(case):
+    w, lay, q, k, v = setup(case)
+    gl = make_layout(lay)
+    dh, dt = descs(w)
+    (qh, qt), (kh, kt), (vh, vt) = (both_layouts(w, x) for x in (q, k, v))
+    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_PREFILL, gl, dh))
+    oh = torch.full_like(qh, float("nan"))
+    ot = torch.full_like(qt, float("nan"))
+    lse_h = torch.full(qh.shape[:2], float("nan"), dtype=torch.float32, device="cuda")
+    lse_t = torch.full_like(lse_h, float("nan"))
+    vxl.chunk_prefill(gl, dh, qh, kh, vh, oh, lse_h, ws)
+    vxl.chunk_prefill(gl, dt, qt, kt, vt, ot, lse_t, ws)
+    torch.cuda.synchronize()
+    got = vxl.to_host(ot.permute(1, 0, 2).contiguous())
+    want = oracle.prefill_blk(q, k, v, lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx)
+    assert_close(got, want, w.dtype, what="token-major pre-filling")
+    assert torch.equal(ot.permute(1, 0, 2), oh), "the two layouts must give the same bits"
+    assert torch.equal(lse_t, lse_h)
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: f"{c[0]}-h{c[1]}-d{c[3]}")
+def test_scores_gather_pool_store_token_major(case):
+    w, lay, q, k, v = setup(case)
+    gl = make_layout(lay)
+    dh, dt = descs(w)
+    (kh, kt), (vh, vt) = (both_layouts(w, x) for x in (k, v))
+    qd = wl.make_decode_queries(w)
+    dqd = vxl.to_device(qd, w.dtype)
+    bsz, c_n, kk = qd.shape[0], lay.n_chunks, min(w.k, lay.n_chunks)
+
+    def score(fn, op, desc, kdev):
+        idx = torch.full((bsz, max(kk, 1)), -7, dtype=torch.int32, device="cuda")
+        mask = torch.full((bsz, max(c_n, 1)), 9, dtype=torch.uint8, device="cuda")
+        sc = torch.full((bsz, max(c_n, 1)), float("nan"), dtype=torch.float32, device="cuda")
+        ws = vxl.alloc_workspace(vxl.workspace_bytes(op, gl, desc, bsz, qd.shape[1]))
+        fn(gl, desc, dqd, kdev, w.k, idx, mask, sc, workspace=ws)
+        torch.cuda.synchronize()
+        return idx, mask, sc
+
+    for fn, op in ((vxl.chunk_score_topk, vxl.OP_SCORE_TOPK), (vxl.chunk_score_topk_mass, vxl.OP_SCORE_MASS)):
+        a, b = score(fn, op, dh, kh), score(fn, op, dt, kt)
+        for x, y in zip(a, b):
+            assert torch.equal(x, y), fn.__name__
+    mask = score(vxl.chunk_score_topk, vxl.OP_SCORE_TOPK, dt, kt)[1]
+
+    # pooled sparse KVs and both gathers
+    s_total = int(lay.sparse_offsets[-1])
+    l_cap = gl.mixed_kv_capacity(kk)
+
+    def gathers(desc, kdev, vdev):
+        ksp = torch.zeros((w.n_kv_heads, max(s_total, 1), w.head_dim), dtype=kdev.dtype, device="cuda")
+        vsp = torch.zeros_like(ksp)
+        vxl.pool_sparse_kv(gl, desc, kdev, vdev, ksp, vsp)
+        out = []
+        for pooled in (False, True):
+            kmix = torch.full((bsz, w.n_kv_heads, l_cap, w.head_dim), 7.0, dtype=kdev.dtype, device="cuda")
+            vmix = torch.full_like(kmix, 7.0)
+            mix_len = torch.full((bsz,), -1, dtype=torch.int32, device="cuda")
+            src = torch.full((bsz, l_cap), -5, dtype=torch.int32, device="cuda")
+            ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_GATHER, gl, desc, bsz))
+            if pooled:
+                vxl.gather_bilevel_kv_pooled(gl, desc, kdev, vdev, ksp, vsp, mask, kmix, vmix, mix_len, src, ws)
+            else:
+                vxl.gather_bilevel_kv(gl, desc, kdev, vdev, mask, kmix, vmix, mix_len, src, ws)
+            out += [kmix, vmix, mix_len, src]
+        torch.cuda.synchronize()
+        return [ksp, vsp] + out
+
+    for x, y in zip(gathers(dh, kh, vh), gathers(dt, kt, vt)):
+        assert torch.equal(x, y)
+    # against the oracle too (kept-row gather)
+    got = gathers(dt, kt, vt)
+    wk, wv, wlen, _ = oracle.gather_bilevel(k, v, mask.cpu().numpy(), lay.n_prefix, lay.chunk_bounds,
+                                            lay.sparse_offsets, lay.sparse_idx, l_cap=l_cap)
+    gk, gv = vxl.to_host(got[2]), vxl.to_host(got[3])
+    assert np.array_equal(got[4].cpu().numpy(), wlen)
+    for b in range(bsz):
+        n = int(wlen[b])
+        assert np.array_equal(gk[b, :, :n], wk[b, :, :n]) and np.array_equal(gv[b, :, :n], wv[b, :, :n])
+
+    # offline store: offload from token-major K/V, reload = device gather
+    ksp, vsp = got[0], got[1]
+    store = vxl.KvStore(gl, dt)
+    store.offload(kt, vt, ksp, vsp)
+    torch.cuda.synchronize()
+    kmix = torch.full((bsz, w.n_kv_heads, l_cap, w.head_dim), 7.0, dtype=kt.dtype, device="cuda")
+    vmix = torch.full_like(kmix, 7.0)
+    mix_len = torch.full((bsz,), -1, dtype=torch.int32, device="cuda")
+    store.reload(mask.cpu().numpy(), kmix, vmix, mix_len)
+    torch.cuda.synchronize()
+    assert torch.equal(mix_len, got[8])
+    for b in range(bsz):
+        n = int(mix_len[b])
+        assert torch.equal(kmix[b, :, :n], got[6][b, :, :n]) and torch.equal(vmix[b, :, :n], got[7][b, :, :n])
+    store.close()
+
+
+def test_descriptor_strides_are_validated():
+    w, lay, q, k, v = setup(CASES[1])
+    gl = make_layout(lay)
+    (qh, _), (kh, _), (vh, _) = (both_layouts(w, x) for x in (q, k, v))
+    out = torch.empty_like(qh)
+    for bad in ((128, 0, 128, 256), (128, 1792, 128, 100), (128, 1796, 128, 256), (-8, 1792, 128, 256)):
+        desc = vxl.make_desc(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
+        desc.q_stride_head, desc.q_stride_tok, desc.kv_stride_head, desc.kv_stride_tok = bad
+        ws = vxl.alloc_workspace(1 << 24)
+        with pytest.raises(vxl.VxlError):
+            vxl.chunk_prefill(gl, desc, qh, kh, vh, out, None, ws)
