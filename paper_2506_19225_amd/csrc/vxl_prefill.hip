@@ -463,7 +463,7 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
             }
             bf16x8 pb[1][2][2];
             softmax_tile<D / 32>(s[0], c2, m_run, l_run, o[0], pb[0]);
-            pv_tile<D, 1, D>(vt, pb, lane, o);
+            pv_tile_ahead<D, 2>(vt, pb, lane, o);
         }
     };
     for (int t0 = 0; t0 < n_t; t0 += TPB) {
