@@ -101,3 +101,25 @@ def test_hot_calls_reject_bad_descriptors_before_launch():
         == vxl.VXL_ERR_INVALID_ARG
     assert lib.vxl_workspace_bytes(vxl.OP_DECODE, None, C.byref(good), 1, 32, 4096) > 0
     assert lib.vxl_mixed_kv_capacity(None, 3) == 0
+
+
+def test_descriptor_strides_are_checked_on_the_host():
+    """All four strides or none; positive multiples of 16 bytes; a token stride that holds a row."""
+    lib = vxl.lib()
+    fake = C.c_void_p(0x1000)
+    ok = vxl.make_desc(28, 4, 128, "bf16", token_major=True)
+    assert (ok.q_stride_head, ok.q_stride_tok, ok.kv_stride_head, ok.kv_stride_tok) == (128, 28 * 128, 128, 4 * 128)
+    assert lib.vxl_workspace_bytes(vxl.OP_DECODE, None, C.byref(ok), 1, 1, 64) > 0
+    for bad in ((128, 0, 128, 512), (128, 3584, 128, 64), (128, 3588, 128, 512), (-8, 3584, 128, 512),
+                (0, 3584, 0, 512)):
+        d = vxl.make_desc(28, 4, 128, "bf16")
+        d.q_stride_head, d.q_stride_tok, d.kv_stride_head, d.kv_stride_tok = bad
+        assert lib.vxl_workspace_bytes(vxl.OP_DECODE, None, C.byref(d), 1, 1, 64) == 0, bad
+        st = lib.vxl_bilevel_decode(C.byref(d), fake, 1, 1, fake, fake, 64, fake, fake, None, fake, 1 << 20, None)
+        assert st == vxl.VXL_ERR_INVALID_ARG, bad
+    f32 = vxl.make_desc(4, 2, 64, "f32")
+    f32.q_stride_head, f32.q_stride_tok, f32.kv_stride_head, f32.kv_stride_tok = (64, 260, 64, 132)   # multiples of 4
+    assert lib.vxl_workspace_bytes(vxl.OP_DECODE, None, C.byref(f32), 1, 1, 64) > 0
+    r = vxl.make_desc(28, 4, 128, "bf16")
+    r.reserved = 1
+    assert lib.vxl_workspace_bytes(vxl.OP_DECODE, None, C.byref(r), 1, 1, 64) == 0
