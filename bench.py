@@ -192,9 +192,43 @@ def main():
             "config4_k_all": bilevel_case(torch, vxl, wl, "config4", 1 << 30),
         }
         result["widening"] = measure_widening(torch, vxl, w, lay, gl, desc, dk, dv, dqd)
+        # one layer of the 28-layer workload: its 28 decode calls per token read 28 distinct mixed
+        # KV sets (1.04 GB), which is what the rotating buffers of the measurement stand for
+        c3 = bilevel_case(torch, vxl, wl, "config3", wl.WORKLOADS["config3"].k)
+        c3["us_per_token_28_layers"] = 28 * c3["decode_step"]["us_per_token"]
+        result["bilevel_large"]["config3_per_layer"] = c3
+        result["attained_peaks"] = measure_attained_peaks(torch, vxl)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, lay, q, k, v)
     print(json.dumps(result))
+
+
+def measure_attained_peaks(torch, vxl):
+    """What this box attains on the two rooflines with nothing in the way: a register-resident
+    stream of the matrix instruction the kernels use, and a plain 1 GiB device-to-device copy."""
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    out = torch.empty((n_cu * 512,), dtype=torch.float32, device="cuda")
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    iters = 100000
+    vxl.debug_mfma_stream(out, n_cu, iters)                   # warm-up (clocks)
+    torch.cuda.synchronize()
+    a.record()
+    flops = vxl.debug_mfma_stream(out, n_cu, iters)
+    b.record()
+    torch.cuda.synchronize()
+    mfma = flops / (a.elapsed_time(b) * 1e-3) / 1e12
+    src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(10):
+        dst.copy_(src)
+    b.record()
+    torch.cuda.synchronize()
+    copy = 10 * 2.0 * src.numel() * 4 / (a.elapsed_time(b) * 1e-3) / 1e9
+    return {"mfma_bf16_stream_TFLOPs": mfma, "mfma_frac_of_published": mfma / PEAK_BF16_TFLOPS,
+            "copy_1GiB_GBps_read_plus_write": copy, "copy_frac_of_published": copy / PEAK_HBM_GBS}
 
 
 def measure_widening(torch, vxl, w, lay, gl, desc, dk, dv, dqd):

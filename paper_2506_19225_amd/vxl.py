@@ -93,6 +93,8 @@ def lib() -> C.CDLL:
     L.vxl_debug_prefill_variant.argtypes = [C.c_int]
     L.vxl_debug_prefill_events.argtypes = [vp, vp]
     L.vxl_debug_flags.argtypes = [C.c_int]
+    L.vxl_debug_mfma_stream.argtypes = [vp, C.c_int, C.c_int, vp]
+    L.vxl_debug_mfma_stream.restype = C.c_double
     _lib = L
     return L
 
@@ -299,6 +301,11 @@ class KvStore:
 def debug_force_simple(on: bool) -> None:
     """Route BF16 calls through the plain vector-ALU kernels (on-device cross-check)."""
     lib().vxl_debug_force_simple(int(bool(on)))
+
+
+def debug_mfma_stream(out, n_workgroups: int, iters: int, stream=None) -> float:
+    """Measurement only: launches a register-resident matrix-instruction stream; returns its FLOP count."""
+    return float(lib().vxl_debug_mfma_stream(_ptr(out), int(n_workgroups), int(iters), _stream(stream)))
 
 
 def debug_prefill_variant(variant: int) -> None:
