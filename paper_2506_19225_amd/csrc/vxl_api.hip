@@ -61,6 +61,9 @@ PrefillWorkspace prefill_workspace(const vxl_layout* L, const vxl_attn_desc* d) 
     return w;
 }
 
+static int g_decode_step_waves = 0;     // measurement hook: 0 = choose, 4 or 8 = force
+extern "C" void vxl_debug_decode_step_waves(int w) { g_decode_step_waves = (w == 4 || w == 8) ? w : 0; }
+
 DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
     DecodePlan p{};
     if (d->dtype != VXL_BF16) { p.n_split = 1; p.split_len = l_cap; p.total = 0; return p; }
@@ -69,13 +72,15 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
     const int n_rtile = (rows + row_tile - 1) / row_tile;
     const int tiles = (l_cap + kKeyTile - 1) / kKeyTile;
     if (rows <= kRowBlock) {
-        // Step mode: every wave of an 8-wave workgroup owns whole 32-key tiles; one workgroup per
-        // compute unit (its tile pairs fill the LDS), tiles spread evenly over at most ~256
-        // workgroups.
-        constexpr int kWaves = 8, kTile = 32;
+        // Step mode: every wave of a workgroup owns whole 32-key tiles; one workgroup per compute
+        // unit (its tile pairs fill the LDS), tiles spread evenly over at most ~256 workgroups.
+        constexpr int kTile = 32;
         const int tiles32 = (l_cap + kTile - 1) / kTile;
         const long units = (long)batch * d->n_kv_heads;
         const long max_split = std::max<long>(1, 256 / units);
+        // four double-buffered waves (measured equal or faster than eight single-buffered ones at every size)
+        const int kWaves = g_decode_step_waves == 8 ? 8 : 4;
+        p.step_waves = kWaves;
         long n_split = std::min<long>((tiles32 + kWaves - 1) / kWaves, max_split);
         const int tpw = (int)((tiles32 + kWaves * n_split - 1) / (kWaves * n_split));
         n_split = (tiles32 + kWaves * tpw - 1) / (kWaves * tpw);

@@ -294,33 +294,63 @@ __global__ __launch_bounds__(512, 2) void decode_ring_kernel(
 // ------------------------------------------------------------------------------------------
 // Step-mode kernel for at most 32 stacked query rows (e.g. T = 1..4 at G = 7): the work is pure
 // streaming, so every WAVE owns its own 32-key tiles (tile = NW*(split*tpw + i) + wave) and its
-// own LDS tile pair, filled by direct global->LDS loads; there is no workgroup barrier in the
-// loop.  Eight waves per workgroup (two per SIMD) overlap one wave's loads with another's
-// arithmetic and keep 128 KiB of loads in flight per compute unit.  The waves' running
-// (reference, sum, O) are merged through LDS in wave order and the workgroup writes one
-// normalised partial + base-2 LSE per row.
-// ------------------------------------------------------------------------------------------
-constexpr int kStepWaves = 8;       // waves per workgroup of the step-mode kernel
+// own LDS tile pairs, filled by direct global->LDS loads; there is no workgroup barrier in the
+// loop.  The waves' running (reference, sum, O) are merged through LDS in wave order and the
+// workgroup writes one normalised partial + base-2 LSE per row.
+// Two forms, both filling 128 KiB of LDS: NW = 4 waves with two tile pairs each -- the next tile
+// is requested before the current one is worked on, so a wave waits for memory once, not once per
+// tile (the default: 3-8 % faster on long streams, 5 % at a single tile per wave, where it spreads
+// over twice as many compute units) -- and NW = 8 waves with one tile pair each (cross-check).
 constexpr int kStepTile = 32;       // keys per wave tile
 
-template <int D>
-__global__ __launch_bounds__(64 * kStepWaves, 2) void decode_wave_kernel(
+template <int D, int NW, int NBUF>
+__global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
     const uint16_t* __restrict__ Qd, const uint16_t* __restrict__ Kmix, const uint16_t* __restrict__ Vmix,
     const int32_t* __restrict__ mix_len, float* __restrict__ part_o, float* __restrict__ part_lse, int T_q,
     int n_q_heads, int n_kv_heads, int group, int l_cap, int tiles_per_wave, float scale) {
-    constexpr int NW = kStepWaves, TK = kStepTile;
+    constexpr int TK = kStepTile;
     constexpr int TILE_ELEMS = TK * D;                         // one unpadded tile
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
     __shared__ float stats[NW][32][2];                         // per wave and row: reference logit, sum
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    uint16_t* Kw = lds + wave * 2 * TILE_ELEMS;                // this wave's K tile, then its V tile
+    uint16_t* Kw = lds + wave * NBUF * 2 * TILE_ELEMS;         // this wave's K tile, then its V tile (NBUF times)
     uint16_t* Vw = Kw + TILE_ELEMS;
     const int split = blockIdx.x, n_split = gridDim.x, g = blockIdx.y, b = blockIdx.z;
     const int n_rows = group * T_q;                            // <= 32
     const int len = min(max(mix_len[b], 0), l_cap);
     const int n_tiles = (len + TK - 1) / TK;
     const size_t part_base = (((size_t)b * n_kv_heads + g) * n_split + split) * (size_t)n_rows;
+
+    const float c2 = scale * kLog2e;
+    const char* kbase = (const char*)(Kmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
+    const char* vbase = (const char*)(Vmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
+    const int tile0 = split * tiles_per_wave * NW + wave;      // this wave's tiles: tile0, tile0 + NW, ...
+
+    // NBUF == 2: direct loads issued from inline assembly and counted by hand (a later request
+    // must be allowed to stay in flight while an earlier tile is read).
+    constexpr int PPR = D / 8, RPI = 64 / PPR, NL = TK / RPI;  // pieces per row; rows, 1 KiB lines per tile
+    const uint32_t lds_w = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)Kw;
+    auto request = [&](int tile_, int buf) {
+        const int key0_ = tile_ * TK;
+        const int rlim_ = min(TK - 1, len - 1 - key0_);
+        const char* kb = kbase + (size_t)key0_ * (D * 2);
+        const char* vb = vbase + (size_t)key0_ * (D * 2);
+        const int r_in = lane / PPR, pp = lane % PPR;
+#pragma unroll
+        for (int x = 0; x < NL; ++x) {
+            const int row = x * RPI + r_in;
+            const uint32_t roff = (uint32_t)min(row, rlim_) * (D * 2);
+            const int kp = pp ^ ((row / (16 / PPR)) & (PPR - 1));
+            constexpr int CPR = D * 2 / 64, RPL = D == 128 ? 1 : 2;
+            const int vp = (((pp >> 2) ^ ((row / RPL) & (CPR - 1))) << 2) | (pp & 3);
+            dma16(kb, roff + kp * 16, lds_w + (uint32_t)buf * (4 * TILE_ELEMS) + x * 1024);
+            dma16(vb, roff + vp * 16, lds_w + (uint32_t)buf * (4 * TILE_ELEMS) + 2 * TILE_ELEMS + x * 1024);
+        }
+    };
+    if constexpr (NBUF == 2) {
+        if (tile0 < n_tiles) request(tile0, 0);
+    }
 
     bf16x8 qreg[1][D / 16];
     {
@@ -329,38 +359,64 @@ __global__ __launch_bounds__(64 * kStepWaves, 2) void decode_wave_kernel(
         const uint4* src = (const uint4*)(Qd + (((size_t)b * T_q + t) * n_q_heads + g * group + hg) * D);
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) qreg[0][ks] = __builtin_bit_cast(bf16x8, src[ks * 2 + hi]);
+        if constexpr (NBUF == 2) {
+            // forced complete here: the compiler's wait for them covers the older request of tile 0
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ++ks) {
+                typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+                asm volatile("" :: "v"(__builtin_bit_cast(u32x4, qreg[0][ks])));
+            }
+        }
     }
     f32x16 o[1][D / 32];
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) o[0][db] = zero16();
     float m_run = -INFINITY, l_run = 0.f;
-    const float c2 = scale * kLog2e;
-    const char* kbase = (const char*)(Kmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
-    const char* vbase = (const char*)(Vmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
 
-    for (int i = 0; i < tiles_per_wave; ++i) {
-        const int tile = (split * tiles_per_wave + i) * NW + wave;
-        if (tile >= n_tiles) break;
-        const int key0 = tile * TK;
-        const int rlim = min(TK - 1, len - 1 - key0);
-        dma_tile_wave<D, TK>(kbase + (size_t)key0 * (D * 2), vbase + (size_t)key0 * (D * 2), Kw, Vw, lane, rlim);
-        __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): the tile is in LDS
-        __builtin_amdgcn_wave_barrier();
+    auto work = [&](const uint16_t* kt, const uint16_t* vt, int rlim) {
         f32x16 s[1][1];
-        qk_tile<D, 1, D, 1>(Kw, qreg, l32, hi, s);
+        qk_tile<D, 1, D, 1>(kt, qreg, l32, hi, s);
         if (rlim < TK - 1) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[0][0][r] = acc_key(0, r, hi) <= rlim ? s[0][0][r] : -INFINITY;
         }
         bf16x8 pb[1][1][2];
         softmax_tile<D / 32, 1>(s[0], c2, m_run, l_run, o[0], pb[0]);
-        pv_tile<D, 1, D, 1>(Vw, pb, lane, o);
-        __builtin_amdgcn_wave_barrier();
+        pv_tile<D, 1, D, 1>(vt, pb, lane, o);
+    };
+    if constexpr (NBUF == 1) {
+        for (int i = 0; i < tiles_per_wave; ++i) {
+            const int tile = tile0 + i * NW;
+            if (tile >= n_tiles) break;
+            const int key0 = tile * TK;
+            const int rlim = min(TK - 1, len - 1 - key0);
+            dma_tile_wave<D, TK>(kbase + (size_t)key0 * (D * 2), vbase + (size_t)key0 * (D * 2), Kw, Vw, lane, rlim);
+            __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): the tile is in LDS
+            __builtin_amdgcn_wave_barrier();
+            work(Kw, Vw, rlim);
+            __builtin_amdgcn_wave_barrier();
+        }
+    } else {
+        // tile i lives in pair i & 1; tile i + 1 is requested as soon as tile i - 1 has been worked on
+        if (tiles_per_wave > 1 && tile0 + NW < n_tiles) request(tile0 + NW, 1);
+        for (int i = 0; i < tiles_per_wave; ++i) {
+            const int tile = tile0 + i * NW;
+            if (tile >= n_tiles) break;
+            if (i >= 1) {
+                const bool more = i + 1 < tiles_per_wave && tile + NW < n_tiles;
+                if (more) request(tile + NW, (i + 1) & 1);
+                if (more) wait_vmcnt<2 * NL>(); else wait_vmcnt<0>();      // tile i has landed
+            }
+            __builtin_amdgcn_wave_barrier();
+            const uint16_t* kt = Kw + (i & 1) * 2 * TILE_ELEMS;
+            work(kt, kt + TILE_ELEMS, min(TK - 1, len - 1 - tile * TK));
+            __builtin_amdgcn_wave_barrier();
+        }
     }
 
     // ---- merge the waves (their tile buffers are free now): area [32 rows][D] floats per wave ----
     static_assert(32 * D * 4 <= 2 * TILE_ELEMS * 2, "merge area must fit a wave's tile pair");
-    float* red = (float*)(lds + wave * 2 * TILE_ELEMS);
+    float* red = (float*)Kw;
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     if (l32 < n_rows) {
 #pragma unroll
@@ -375,7 +431,7 @@ __global__ __launch_bounds__(64 * kStepWaves, 2) void decode_wave_kernel(
         if (hi == 0) { stats[wave][l32][0] = m_run; stats[wave][l32][1] = l_tot; }
     }
     __syncthreads();
-    constexpr int WSTRIDE = 2 * TILE_ELEMS / 2;                // floats between the waves' areas
+    constexpr int WSTRIDE = NBUF * 2 * TILE_ELEMS / 2;         // floats between the waves' areas
     const float* red0 = (const float*)lds;
     for (int e = tid; e < n_rows * D; e += 64 * NW) {
         const int row = e / D, dd = e % D;
@@ -530,17 +586,25 @@ static vxl_status run_decode_wave(const vxl_attn_desc* d, float scale, const voi
     float* part_lse = (float*)((char*)ws + p.part_ml);
     const int group = d->n_q_heads / d->n_kv_heads;
     const int n_rows = group * T;
-    constexpr int lds_bytes = kStepWaves * 2 * kStepTile * D * 2;
+    constexpr int lds_bytes = 8 * 2 * kStepTile * D * 2;      // 8 tile pairs in either form
     static bool attr_done = false;
     if (!attr_done) {
-        VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_wave_kernel<D>,
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_wave_kernel<D, 8, 1>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_wave_kernel<D, 4, 2>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
         attr_done = true;
     }
-    hipLaunchKernelGGL((decode_wave_kernel<D>), dim3(p.n_split, d->n_kv_heads, batch), dim3(64 * kStepWaves),
-                       lds_bytes, s, (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix, mix_len,
-                       part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap,
-                       p.split_len / (kStepWaves * kStepTile), scale);
+    if (p.step_waves == 8)
+        hipLaunchKernelGGL((decode_wave_kernel<D, 8, 1>), dim3(p.n_split, d->n_kv_heads, batch), dim3(512),
+                           lds_bytes, s, (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix,
+                           mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap,
+                           p.split_len / (8 * kStepTile), scale);
+    else
+        hipLaunchKernelGGL((decode_wave_kernel<D, 4, 2>), dim3(p.n_split, d->n_kv_heads, batch), dim3(256),
+                           lds_bytes, s, (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix,
+                           mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap,
+                           p.split_len / (4 * kStepTile), scale);
     VXL_HIP_TRY(hipGetLastError());
     const size_t merge_lds = (size_t)(((p.n_split + 3) & ~3) + 256 / (D / 4) * D) * sizeof(float);
     hipLaunchKernelGGL((decode_merge_kernel<D>), dim3(n_rows, d->n_kv_heads, batch), dim3(256), merge_lds, s,

@@ -149,6 +149,7 @@ vxl_status launch_pool_sparse(const vxl_layout* L, const vxl_attn_desc* d, const
 struct DecodePlan {
     int n_split;        // key splits per (batch, kv head)
     int split_len;      // keys per split (multiple of 64)
+    int step_waves;     // step mode: waves per workgroup (8 single-buffered or 4 double-buffered), else 0
     size_t part_o;      // byte offsets into the workspace
     size_t part_ml;
     size_t total;

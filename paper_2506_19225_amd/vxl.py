@@ -93,6 +93,7 @@ def lib() -> C.CDLL:
     L.vxl_debug_prefill_variant.argtypes = [C.c_int]
     L.vxl_debug_prefill_events.argtypes = [vp, vp]
     L.vxl_debug_flags.argtypes = [C.c_int]
+    L.vxl_debug_decode_step_waves.argtypes = [C.c_int]
     L.vxl_debug_mfma_stream.argtypes = [vp, C.c_int, C.c_int, vp]
     L.vxl_debug_mfma_stream.restype = C.c_double
     _lib = L
@@ -306,6 +307,12 @@ def debug_force_simple(on: bool) -> None:
 def debug_mfma_stream(out, n_workgroups: int, iters: int, stream=None) -> float:
     """Measurement only: launches a register-resident matrix-instruction stream; returns its FLOP count."""
     return float(lib().vxl_debug_mfma_stream(_ptr(out), int(n_workgroups), int(iters), _stream(stream)))
+
+
+def debug_decode_step_waves(waves: int) -> None:
+    """Measurement / cross-check: 0 = the library chooses, 8 = single-buffered 8-wave step kernel,
+    4 = double-buffered 4-wave step kernel.  Size the workspace after setting it."""
+    lib().vxl_debug_decode_step_waves(int(waves))
 
 
 def debug_prefill_variant(variant: int) -> None:

@@ -471,8 +471,18 @@ def test_whole_path_on_a_side_stream_and_in_a_replayed_graph():
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), f"replay {rep} differs"
 
 
+@pytest.fixture
+def step_waves(request):
+    """Both forms of the step-mode kernel: 0 = the default (4 double-buffered waves), 8 = the
+    single-buffered 8-wave form."""
+    vxl.debug_decode_step_waves(request.param)
+    yield request.param
+    vxl.debug_decode_step_waves(0)
+
+
+@pytest.mark.parametrize("step_waves", [0, 8], indirect=True)
 @pytest.mark.parametrize("name,t_q", [("config1", 1), ("config1", 4), ("config2", 1)])
-def test_decode_step_mode_many_splits(name, t_q):
+def test_decode_step_mode_many_splits(name, t_q, step_waves):
     """Step mode (at most 32 stacked rows) at the mixed-set sizes of config1 / config2: many key
     splits, a workspace that starts with arbitrary bytes, repeated calls on one workspace, and
     replays of a captured graph with eager calls in between."""
