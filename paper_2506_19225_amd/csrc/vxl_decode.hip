@@ -461,7 +461,11 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float v) {
 
 // One workgroup per query row.  Weights w_s = exp2(lse_s - max) go to LDS; the thread grid
 // (split group sg, float4 column) accumulates the splits s = sg, sg + SG, ... in that order and
-// the SG partial sums are added in group order: a fixed summation tree.
+// the SG partial sums are added in group order; the weights are summed per wave by butterfly and
+// then over the four waves: fixed summation trees, so a call gives the same bits every time.
+// The first PRE partial rows of every thread are requested together with the LSEs, before the
+// weights exist, so the kernel waits for memory once rather than twice (its duration is
+// latency, not volume); rows of splits with weight 0 are loaded but never used.
 template <int D>
 __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restrict__ part_o,
                                                            const float* __restrict__ part_lse,
@@ -470,14 +474,22 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restri
                                                            int n_split) {
     constexpr int NV = D / 4;                       // float4 columns per row
     constexpr int SG = 256 / NV;                    // split groups
+    constexpr int PRE = 8;                          // partial rows per thread requested up front
     extern __shared__ float sm[];
     float* w = sm;                                  // [n_split]
     float* red = sm + ((n_split + 3) & ~3);         // [SG][D]
-    __shared__ float wave_max[4];
+    __shared__ float wave_max[4], wave_sum[4];
     const int n_rows = group * T_q;
     const int rho = blockIdx.x, g = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     const size_t base = ((size_t)b * n_kv_heads + g) * n_split;
+    const int sg = tid / NV, dq = tid % NV;
 
+    float4 pre[PRE];
+#pragma unroll
+    for (int i = 0; i < PRE; ++i) {
+        const int s = min(sg + i * SG, n_split - 1);          // clamped: always a row of this (b, g)
+        pre[i] = *(const float4*)(part_o + ((base + s) * n_rows + rho) * D + dq * 4);
+    }
     float mx = -INFINITY;
     for (int s = tid; s < n_split; s += 256) {
         const float v = part_lse[(base + s) * n_rows + rho];
@@ -488,12 +500,29 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restri
     if ((tid & 63) == 0) wave_max[tid >> 6] = mx;
     __syncthreads();
     mx = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
-    for (int s = tid; s < n_split; s += 256) w[s] = w[s] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(w[s] - mx);
+    float wpart = 0.f;                              // this thread's weights, then its wave's
+    for (int s = tid; s < n_split; s += 256) {
+        const float ws = w[s] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(w[s] - mx);
+        w[s] = ws;
+        wpart += ws;
+    }
+    for (int o = 32; o > 0; o >>= 1) wpart += __shfl_xor(wpart, o);
+    if ((tid & 63) == 0) wave_sum[tid >> 6] = wpart;
     __syncthreads();
 
-    const int sg = tid / NV, dq = tid % NV;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = sg; s < n_split; s += SG) {
+#pragma unroll
+    for (int i = 0; i < PRE; ++i) {
+        const int s = sg + i * SG;
+        const float ws = s < n_split ? w[s] : 0.f;
+        if (ws != 0.f) {
+            acc.x = fmaf(ws, pre[i].x, acc.x);
+            acc.y = fmaf(ws, pre[i].y, acc.y);
+            acc.z = fmaf(ws, pre[i].z, acc.z);
+            acc.w = fmaf(ws, pre[i].w, acc.w);
+        }
+    }
+    for (int s = sg + PRE * SG; s < n_split; s += SG) {
         const float ws = w[s];
         if (ws != 0.f) {
             const float4 v = *(const float4*)(part_o + ((base + s) * n_rows + rho) * D + dq * 4);
@@ -506,10 +535,10 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restri
     *(float4*)(red + sg * D + dq * 4) = acc;
     __syncthreads();
     if (tid < D) {
-        float a = 0.f, wsum = 0.f;
+        float a = 0.f;
 #pragma unroll
         for (int i = 0; i < SG; ++i) a += red[i * D + tid];
-        for (int s = 0; s < n_split; ++s) wsum += w[s];
+        const float wsum = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
         const int t = rho / group, hg = rho % group;
         const size_t row = ((size_t)b * T_q + t) * n_q_heads + g * group + hg;
         O[row * D + tid] = f32_to_bf16(a / wsum);
