@@ -96,11 +96,12 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
     }
     // Split the keys until every compute unit has its workgroups (one of the 8-wave ring kernel,
     // two of the 4-wave kernel), but keep the partial results (fp32 rows per split) below roughly
-    // twice the KV bytes they summarise.
+    // the KV bytes they summarise (measured at 224 rows over 4,096 keys: 16 splits 20.0 us per
+    // call, 32 splits 21.3, 22 splits 21.2, 8 splits 24.0).
     const long base_blocks = (long)batch * d->n_kv_heads * n_rtile;
     const long target = rows > 128 ? 256 : 512;
     long want = (target + base_blocks - 1) / base_blocks;
-    const long cap = std::max<long>(1, 2L * l_cap / rows);
+    const long cap = std::max<long>(1, (long)l_cap / rows);
     want = std::max<long>(1, std::min<long>(std::min<long>(want, cap), tiles));
     const int tiles_per = (int)((tiles + want - 1) / want);
     p.n_split = (tiles + tiles_per - 1) / tiles_per;
