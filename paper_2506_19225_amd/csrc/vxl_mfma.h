@@ -265,6 +265,12 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N >= 0 && N < 64, "vmcnt range");
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
 }
+// Wait until no vector-memory operation and no LDS (or scalar-memory) operation of this wave is
+// outstanding: what a wave owes the workgroup before a bare s_barrier when it has stored to LDS
+// something the others read right behind that barrier.  (The barrier instruction itself waits
+// for nothing; an LDS store still queued behind other traffic of its SIMD can be overtaken by
+// another SIMD's load.)
+__device__ __forceinline__ void wait_vmcnt0_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0x0070); }
 // 16 bytes per lane from (uniform base + per-lane offset) to LDS byte offset lds_off + 16*lane.
 // Issued from inline assembly so that the compiler neither counts it nor orders LDS reads of
 // other ring stages behind it.

@@ -467,7 +467,9 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
         }
     };
     for (int t0 = 0; t0 < n_t; t0 += TPB) {
-        wait_vmcnt<0>();                                      // this wave's parts of tiles t0, t0+1 have landed
+        // this wave's parts of tiles t0, t0+1 have landed -- and, at the item's first meeting, the
+        // next item's index (an LDS store of wave 0, read by everybody right behind the barrier)
+        wait_vmcnt0_lgkmcnt0();
         __builtin_amdgcn_s_barrier();                         // ... and everyone's; the other group is free
         if (t0 == 0) {                                        // the next item's index was written before this barrier
             const int jn = __builtin_amdgcn_readfirstlane(next_slot[par]);
