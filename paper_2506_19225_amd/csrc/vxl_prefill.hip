@@ -267,9 +267,9 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
 // outstanding while the ring runs: the query registers are forced complete before the first ring
 // load, and the kernel must not spill (the build refuses a compile of it that uses scratch).
 // ------------------------------------------------------------------------------------------
-template <int D, int NS>
+template <int D, int NS, int NW = 8>
 struct PrefillDmaCfg {
-    static constexpr int WAVES = 8;
+    static constexpr int WAVES = NW;                          // 8 (one workgroup per compute unit) or 4 (two)
     static constexpr int BM = 32 * WAVES;
     static constexpr int TILE = kKeyTile * D;                 // elements of one unpadded K (or V) tile
     static constexpr int STAGE = 2 * TILE;                    // K tile then V tile
@@ -287,14 +287,14 @@ struct PrefillDmaCfg {
 // scheduling without gaps between workgroups.  With xpg > 0 there is one queue per KV head group,
 // served by the xpg XCDs (blockIdx.x % 8, the order workgroups are dealt out in) whose L2 then
 // holds that group's K and V; otherwise a single queue.  The counters must be zero at launch.
-template <int D, int NS, bool STRIDED>
-__global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
+template <int D, int NS, bool STRIDED, int NW = 8>
+__global__ __launch_bounds__(NW * 64, 2) void prefill_dma_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     const uint16_t* __restrict__ Kctx, const uint16_t* __restrict__ Vctx, uint16_t* __restrict__ O,
     float* __restrict__ LSE, const Segment* __restrict__ segs, const WorkItem* __restrict__ work,
     int n_tokens, int n_q_heads, int group, int ctx_rows_pad, float scale, int n_items, int xpg,
     int* __restrict__ queue, long long q_head_arg, int q_tok_arg, long long kv_head_arg, int kv_tok_arg) {
-    using C = PrefillDmaCfg<D, NS>;
+    using C = PrefillDmaCfg<D, NS, NW>;
     // Element strides of Q/O and K/V rows: the arguments, or (STRIDED false, the dense head-major
     // layout) constants, so that the dense instance carries no stride arithmetic or registers.
     const long long q_head = STRIDED ? q_head_arg : (long long)n_tokens * D;
@@ -417,8 +417,8 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
     // another's matrix work).  Tile indices beyond the last are clamped to it, so that every wave
     // always issues the same number of loads; a clamped issue rewrites the last tile's own stage
     // with the same bytes, which is harmless.
-    constexpr int TPB = 2;                                    // tiles per workgroup barrier
-    static_assert(NS == 2 * TPB, "two groups of TPB stages");
+    constexpr int TPB = NS / 2;                               // tiles per workgroup barrier: 2, or 1 with a 2-stage ring
+    static_assert(NS == 2 * TPB && (TPB == 1 || TPB == 2), "two groups of TPB stages");
 #pragma unroll
     for (int t = 0; t < TPB; ++t) issue(min(t, n_t - 1));
 
@@ -480,8 +480,10 @@ __global__ __launch_bounds__(512, 2) void prefill_dma_kernel(
         }
         if (t0 + TPB < n_t) issue(t0 + TPB);                  // (all waits are vmcnt(0): nothing is issued past the last tile,
         process(t0);                                          //  so the item does not end waiting for loads nobody reads)
-        if (t0 + TPB + 1 < n_t) issue(t0 + TPB + 1);          // the second refill between the two tiles
-        if (t0 + 1 < n_t) process(t0 + 1);
+        if constexpr (TPB == 2) {
+            if (t0 + TPB + 1 < n_t) issue(t0 + TPB + 1);      // the second refill between the two tiles
+            if (t0 + 1 < n_t) process(t0 + 1);
+        }
     }
     wait_vmcnt<0>();                                          // nothing of the ring is in flight when the item ends
 
@@ -535,7 +537,9 @@ static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 // Cross-check and measurement only: 0 = the streaming kernel (default); 1, 2 = the 4-wave
 // register-staged kernel with one or two 32-row blocks per wave.
 // 3 = the software-pipelined 4-wave kernel with 64 rows per wave.
-extern "C" void vxl_debug_prefill_variant(int v) { g_prefill_variant = (v >= 1 && v <= 3) ? v : 0; }
+// 4 = the streaming kernel as two independent 4-wave workgroups per compute unit (128-row bands,
+// a 2-stage ring each, one meeting per tile).
+extern "C" void vxl_debug_prefill_variant(int v) { g_prefill_variant = (v >= 1 && v <= 4) ? v : 0; }
 // Measurement hook: when both events are set, every vxl_chunk_prefill records them on its stream
 // immediately before and after the main attention kernel (the pre-pass is outside the bracket).
 extern "C" void vxl_debug_prefill_events(void* start, void* stop) {
@@ -595,10 +599,10 @@ static vxl_status run_prefill(const vxl_layout* L, const vxl_attn_desc* d, float
     return VXL_OK;
 }
 
-template <int D, int NS>
+template <int D, int NS, int NW = 8>
 static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Q,
                                   const void* K, const void* V, void* O, float* LSE, void* ws, hipStream_t s) {
-    using C = PrefillDmaCfg<D, NS>;
+    using C = PrefillDmaCfg<D, NS, NW>;
     const TokStrides ts = tok_strides(d, L->n_tokens);
     // 32-bit byte offsets inside a segment's rows (longest segment plus its look-back)
     long long max_rows = 0;
@@ -621,8 +625,8 @@ static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, f
     VXL_HIP_TRY(hipGetLastError());
     static bool attr_done = false;
     if (!attr_done) {
-        vxl_status st = enable_big_lds(prefill_dma_kernel<D, NS, false>, C::LDS_BYTES);
-        if (st == VXL_OK) st = enable_big_lds(prefill_dma_kernel<D, NS, true>, C::LDS_BYTES);
+        vxl_status st = enable_big_lds(prefill_dma_kernel<D, NS, false, NW>, C::LDS_BYTES);
+        if (st == VXL_OK) st = enable_big_lds(prefill_dma_kernel<D, NS, true, NW>, C::LDS_BYTES);
         if (st != VXL_OK) return st;
         attr_done = true;
     }
@@ -644,14 +648,18 @@ static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, f
     }
     const int group = d->n_q_heads / d->n_kv_heads;
     const int xpg = (!(g_prefill_dbg & 2) && 8 % d->n_kv_heads == 0) ? 8 / d->n_kv_heads : 0;
-    const long long n_pairs = (long long)L->n_work[1] * d->n_q_heads;
+    constexpr int wl_i = NW == 8 ? 1 : 0;                     // the work list cut in bands of 32 * NW rows
+    constexpr int per_cu = 8 / NW;                            // workgroups per compute unit
+    const long long n_pairs = (long long)L->n_work[wl_i] * d->n_q_heads;
     // no more workgroups than pairs (rounded up to whole rounds over the 8 XCDs when queues are per XCD group)
-    const unsigned n_blocks = (unsigned)std::min<long long>(n_cus / 8 * 8, xpg ? (n_pairs + 7) / 8 * 8 : n_pairs);
+    const unsigned n_blocks = (unsigned)std::min<long long>((long long)per_cu * (n_cus / 8 * 8),
+                                                            xpg ? (n_pairs + 7) / 8 * 8 : n_pairs);
 #define VXL_LAUNCH(STRIDED_)                                                                             \
-    hipLaunchKernelGGL((prefill_dma_kernel<D, NS, STRIDED_>), dim3(n_blocks), dim3(512), C::LDS_BYTES, s, \
-                       (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V, kctx, vctx,           \
-                       (uint16_t*)O, LSE, L->d_segs, L->d_work[1], L->n_tokens, d->n_q_heads, group,      \
-                       n_rows_pad, scale, L->n_work[1], xpg, queue, ts.qh, (int)ts.qt, ts.kh, (int)ts.kt)
+    hipLaunchKernelGGL((prefill_dma_kernel<D, NS, STRIDED_, NW>), dim3(n_blocks), dim3(NW * 64),          \
+                       C::LDS_BYTES, s, (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V, kctx,  \
+                       vctx, (uint16_t*)O, LSE, L->d_segs, L->d_work[wl_i], L->n_tokens, d->n_q_heads,     \
+                       group, n_rows_pad, scale, L->n_work[wl_i], xpg, queue, ts.qh, (int)ts.qt, ts.kh,    \
+                       (int)ts.kt)
     if (dense_layout(d)) VXL_LAUNCH(false); else VXL_LAUNCH(true);
 #undef VXL_LAUNCH
     VXL_HIP_TRY(hipGetLastError());
@@ -696,6 +704,9 @@ extern "C" double vxl_debug_mfma_stream(float* out, int n_workgroups, int iters,
 
 vxl_status launch_prefill_bf16(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Q,
                                const void* K, const void* V, void* O, float* LSE, void* ws, hipStream_t s) {
+    if (g_prefill_variant == 4)
+        return d->head_dim == 128 ? run_prefill_dma<128, 2, 4>(L, d, scale, Q, K, V, O, LSE, ws, s)
+                                  : run_prefill_dma<64, 2, 4>(L, d, scale, Q, K, V, O, LSE, ws, s);
     if (g_prefill_variant == 0 || g_prefill_variant == 3)
         return d->head_dim == 128 ? run_prefill_dma<128, 4>(L, d, scale, Q, K, V, O, LSE, ws, s)
                                   : run_prefill_dma<64, 4>(L, d, scale, Q, K, V, O, LSE, ws, s);

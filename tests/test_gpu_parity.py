@@ -48,7 +48,7 @@ TINY_CASES = [
 
 
 @pytest.mark.parametrize("case", TINY_CASES, ids=lambda c: f"{c[0]}-h{c[1]}-d{c[3]}-p{c[4]}-s{c[8]}")
-@pytest.mark.parametrize("qb", [0, 1, 2, 3])
+@pytest.mark.parametrize("qb", [0, 1, 2, 3, 4])
 def test_prefill_ragged_layouts(case, qb):
     dtype, hq, hkv, d, p, nc, lo, hi, seed = case
     if dtype == "f32" and qb != 0:
@@ -86,7 +86,7 @@ def test_prefill_edge_layouts_bf16():
         assert_close(got, oracle_prefill(q, k, v, lay), "bf16", what="edge layout")
 
 
-@pytest.mark.parametrize("qb", [0, 1, 2, 3])
+@pytest.mark.parametrize("qb", [0, 1, 2, 3, 4])
 def test_prefill_medium_bf16_sharp_softmax(qb):
     """Several 256-token chunks at GQA 14/2, with logits of std ~3 so that the running maximum
     moves and the rescaling path is exercised."""
@@ -138,7 +138,7 @@ def sample_rows(lay, rng, n_full_chunks=3):
     return np.array(sorted(rows), dtype=np.int64)
 
 
-@pytest.mark.parametrize("qb", [0, 1, 2, 3])
+@pytest.mark.parametrize("qb", [0, 1, 2, 3, 4])
 def test_prefill_config1_sampled_rows(qb):
     w = wl.WORKLOADS["config1"]
     lay = wl.make_layout(w)
@@ -187,7 +187,7 @@ WINDOW_CASES = [
 
 
 @pytest.mark.parametrize("case", WINDOW_CASES, ids=lambda c: f"{c[0]}-d{c[3]}-p{c[4]}-w{c[8]}")
-@pytest.mark.parametrize("qb", [0, 1, 2, 3])
+@pytest.mark.parametrize("qb", [0, 1, 2, 3, 4])
 def test_prefill_sliding_window(case, qb):
     dtype, hq, hkv, d, p, nc, lo, hi, window, seed = case
     if dtype == "f32" and qb != 0:
@@ -225,6 +225,24 @@ def test_prefill_window_config1_sampled_rows():
     rows = sample_rows(lay, np.random.default_rng(0))
     want = oracle_prefill(q, k, v, lay, rows=rows, window=64)
     assert_close(got[:, rows], want, "bf16", what="config1 windowed prefill")
+
+
+def test_prefill_two_workgroups_per_unit_instance_is_reproducible():
+    """The instance of the streaming kernel that runs as two independent 4-wave workgroups per
+    compute unit walks the same tiles in the same order as the default one, so on config1 with a
+    look-back window it must give the default's bits, run after run."""
+    w = wl.WORKLOADS["config1"]
+    lay = wl.make_layout(w)
+    q, k, v = wl.make_qkv(w, lay)
+    gl = make_layout(lay, window=64)
+    ref = gpu_prefill(w, lay, q, k, v, gl=gl)
+    vxl.debug_prefill_variant(4)
+    try:
+        runs = [gpu_prefill(w, lay, q, k, v, gl=gl) for _ in range(3)]
+    finally:
+        vxl.debug_prefill_variant(0)
+    for r in runs:
+        assert np.array_equal(r, ref)
 
 
 # --------------------------------------------------------------------------------- score / top-k
