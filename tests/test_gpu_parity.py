@@ -489,6 +489,27 @@ def test_whole_path_on_a_side_stream_and_in_a_replayed_graph():
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), f"replay {rep} differs"
 
 
+@pytest.mark.parametrize("d,lens", [(128, [40001, 711]), (64, [40001]), (64, [711])],
+                         ids=["d128-long+short", "d64-long", "d64-short"])
+def test_decode_step_mode_more_splits_than_the_merge_prefetches(d, lens):
+    """One KV head and a long mixed-set capacity: 105 (two queries) or 157 (one query) key splits,
+    more than the merge kernel requests up front (64 at D = 128, 128 at D = 64), so it goes on
+    into its loop; a short set leaves most splits empty (weight 0, LSE -inf) and ends in a ragged
+    tile."""
+    rng = np.random.default_rng(500 + d + len(lens) + lens[0])
+    hq, hkv, l_cap, bsz = 4, 1, 40037, len(lens)
+    w = wl.tiny_workload("bf16", hq, hkv, d, T=1, B=bsz, k=1, seed=500 + d)
+    kmix = wl.round_to_bf16(rng.standard_normal((bsz, hkv, l_cap, d)).astype(np.float32) * np.float32(0.5))
+    vmix = wl.round_to_bf16(rng.standard_normal((bsz, hkv, l_cap, d)).astype(np.float32) * np.float32(0.5))
+    qd = wl.round_to_bf16(rng.standard_normal((bsz, 1, hq, d)).astype(np.float32) * np.float32(0.5))
+    mix_len = np.array(lens, dtype=np.int32)
+    got, lse = gpu_decode(w, qd, vxl.to_device(kmix, "bf16"), vxl.to_device(vmix, "bf16"),
+                          torch.from_numpy(mix_len).cuda(), want_lse=True)
+    want, wlse = oracle.decode_lse(qd, kmix, vmix, mix_len)
+    assert_close(got, want, "bf16", head_axis=2, what=f"long single-head step decode d={d}")
+    assert np.abs(lse - wlse).max() < 2e-2
+
+
 @pytest.fixture
 def step_waves(request):
     """Both forms of the step-mode kernel: 0 = the default (4 double-buffered waves), 8 = the
