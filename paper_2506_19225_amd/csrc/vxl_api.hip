@@ -68,9 +68,22 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
     DecodePlan p{};
     if (d->dtype != VXL_BF16) { p.n_split = 1; p.split_len = l_cap; p.total = 0; return p; }
     const int rows = (d->n_q_heads / d->n_kv_heads) * T;
-    const int row_tile = rows > 128 ? 256 : 128;
-    const int n_rtile = (rows + row_tile - 1) / row_tile;
     const int tiles = (l_cap + kKeyTile - 1) / kKeyTile;
+    // 129-256 stacked rows fit one 256-row workgroup of the ring kernel or two 128-row workgroups
+    // of the 4-wave kernel.  The ring kernel streams better, but only when its launch covers the
+    // chip; at short mixed sets the split cap below leaves it a fraction of the compute units
+    // (measured at 224 rows: 64 and 120 workgroups, 4-wave kernel 9 % and 5 % faster; 176 and
+    // 256 workgroups, ring kernel 5 % and 8 % faster).
+    bool ring = rows > 128;
+    if (ring && rows <= 256) {
+        const long blocks = (long)batch * d->n_kv_heads;
+        const long splits = std::max<long>(1, std::min<long>(std::min<long>((256 + blocks - 1) / blocks, (long)l_cap / rows), tiles));
+        const int per = (int)((tiles + splits - 1) / splits);
+        ring = blocks * ((tiles + per - 1) / per) >= 150;
+    }
+    p.use_ring = ring ? 1 : 0;
+    const int row_tile = ring ? 256 : 128;
+    const int n_rtile = (rows + row_tile - 1) / row_tile;
     if (rows <= kRowBlock) {
         // Step mode: every wave of a workgroup owns whole 32-key tiles; one workgroup per compute
         // unit (its tile pairs fill the LDS), tiles spread evenly over at most ~256 workgroups.
@@ -99,7 +112,7 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
     // the KV bytes they summarise (measured at 224 rows over 4,096 keys: 16 splits 20.0 us per
     // call, 32 splits 21.3, 22 splits 21.2, 8 splits 24.0).
     const long base_blocks = (long)batch * d->n_kv_heads * n_rtile;
-    const long target = rows > 128 ? 256 : 512;
+    const long target = ring ? 256 : 512;
     long want = (target + base_blocks - 1) / base_blocks;
     const long cap = std::max<long>(1, (long)l_cap / rows);
     want = std::max<long>(1, std::min<long>(std::min<long>(want, cap), tiles));

@@ -650,7 +650,7 @@ vxl_status launch_decode_bf16(const vxl_attn_desc* d, float scale, const void* Q
         return d->head_dim == 128
                    ? run_decode_wave<128>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s)
                    : run_decode_wave<64>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s);
-    const bool big = n_rows > 128;
+    const bool big = decode_plan(d, batch, T, l_cap).use_ring != 0;
     if (d->head_dim == 128)
         return big ? run_decode_ring<128>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s)
                    : run_decode<128, 1>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s);

@@ -149,6 +149,7 @@ vxl_status launch_pool_sparse(const vxl_layout* L, const vxl_attn_desc* d, const
 struct DecodePlan {
     int n_split;        // key splits per (batch, kv head)
     int split_len;      // keys per split (multiple of 64)
+    int use_ring;          // 129+ stacked rows: 1 = the 256-row ring kernel, 0 = the 128-row 4-wave kernel
     int step_waves;     // step mode: waves per workgroup (8 single-buffered or 4 double-buffered), else 0
     size_t part_o;      // byte offsets into the workspace
     size_t part_ml;
