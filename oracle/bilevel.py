@@ -67,11 +67,13 @@ def chunk_scores_mass(qd, k, n_prefix, chunk_bounds, scale=None, row_block=64):
     return out / (t * hq)
 
 
-def select_topk(scores, k, decide_dtype=np.float32):
+def select_topk(scores, k, decide_dtype=np.float64):
     """(topk_idx [B, k'], dense_mask [B, C] uint8) with k' = min(k, C).
 
-    The comparison is made on the scores rounded to `decide_dtype` (the precision in which the
-    device takes the same decision); order is score descending, ties by ascending chunk id."""
+    Full sort of the chunk ids by (score descending, chunk id ascending) on the scores as given
+    (float64 by default); the first k' are the dense chunks.  `decide_dtype` is a test option: a
+    caller that wants to see what the decision would be on scores rounded to a narrower type (the
+    device scores in fp32) passes it explicitly."""
     scores = np.asarray(scores)
     bsz, c_n = scores.shape
     kk = max(0, min(int(k), c_n))
