@@ -112,7 +112,6 @@ def main():
     out = torch.empty_like(dq)
     ws_pre = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_PREFILL, gl, desc))
     ws_sc = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_SCORE_TOPK, gl, desc, B, T))
-    ws_ga = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_GATHER, gl, desc, B))
     ws_de = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_DECODE, None, desc, B, T, l_cap))
     idx = torch.zeros((B, min(top_k, C)), dtype=torch.int32, device="cuda")
     mask = torch.zeros((B, C), dtype=torch.uint8, device="cuda")
@@ -124,7 +123,7 @@ def main():
     def step():
         vxl.chunk_prefill(gl, desc, dq, dk, dv, out, None, ws_pre)
         vxl.chunk_score_topk(gl, desc, dqd, dk, top_k, idx, mask, workspace=ws_sc)
-        vxl.gather_bilevel_kv(gl, desc, dk, dv, mask, kmix, vmix, mix_len, None, ws_ga)
+        vxl.gather_bilevel_kv(gl, desc, dk, dv, mask, kmix, vmix, mix_len)
         vxl.bilevel_decode(desc, dqd, kmix, vmix, mix_len, od, None, ws_de)
 
     if args.calibrate_copy:
@@ -315,7 +314,6 @@ def measure_bilevel(torch, vxl, w, gl, desc, dk, dv, dqd, mask, l_cap, mixlen):
     kmixes = [torch.zeros((B, Hkv, l_cap, D), dtype=dk.dtype, device="cuda") for _ in range(n_rot)]
     vmixes = [torch.zeros_like(kmixes[0]) for _ in range(n_rot)]
     mix_len = torch.zeros((B,), dtype=torch.int32, device="cuda")
-    ws_ga = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_GATHER, gl, desc, B))
 
     def timed(fn, iters):
         """us per call of fn(i), i = 0..iters-1, replayed from one captured HIP graph (the calls
@@ -340,7 +338,7 @@ def measure_bilevel(torch, vxl, w, gl, desc, dk, dv, dqd, mask, l_cap, mixlen):
 
     iters = 2 * n_rot
     us_gather = timed(lambda i: vxl.gather_bilevel_kv(gl, desc, dk, dv, mask, kmixes[i % n_rot],
-                                                      vmixes[i % n_rot], mix_len, None, ws_ga), iters)
+                                                      vmixes[i % n_rot], mix_len), iters)
     gather_bytes = 2 * kv_bytes                             # read + write, K and V
     res = {"mixed_kv_bytes": kv_bytes, "rotating_buffers": n_rot, "timing": "HIP graph replay",
            "gather": {"us": us_gather, "GBps": gather_bytes / us_gather / 1e3,

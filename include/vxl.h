@@ -23,7 +23,8 @@
  *     inputs.  Base pointers must be 16-byte aligned.
  *   - Every call returns a vxl_status.  Argument errors are detected on the host before
  *     anything is launched; a failing HIP call is reported as VXL_ERR_HIP (the text of the
- *     last one is available from vxl_last_error).
+ *     last one is available from vxl_last_error).  The cross-check and measurement hooks of the
+ *     library are declared in vxl_debug.h, not here.
  *   - Supported: dtype F32 or BF16; head_dim 64 or 128; n_q_heads a multiple of n_kv_heads;
  *     n_chunks <= VXL_MAX_CHUNKS.  BF16 runs on the matrix cores with fp32 accumulation; F32
  *     runs on the vector ALUs in fp32.
@@ -45,7 +46,8 @@ typedef enum {
     VXL_ERR_INVALID_ARG = 1,   /* null pointer, inconsistent sizes, malformed layout */
     VXL_ERR_UNSUPPORTED = 2,   /* dtype / head_dim / chunk count outside the supported set */
     VXL_ERR_WORKSPACE = 3,     /* workspace missing or smaller than vxl_workspace_bytes */
-    VXL_ERR_HIP = 4            /* a HIP runtime call failed */
+    VXL_ERR_HIP = 4,           /* a HIP runtime call failed */
+    VXL_ERR_ALLOC = 5          /* host or device memory could not be allocated (handle-creating calls only) */
 } vxl_status;
 
 typedef enum { VXL_F32 = 0, VXL_BF16 = 1 } vxl_dtype;
@@ -97,7 +99,8 @@ typedef void* vxl_stream;               /* a hipStream_t */
  * The handle owns device copies of these arrays and the pre-filling tile schedule derived from
  * them; creating it allocates device memory and synchronises `stream`.  n_chunks may be 0.
  * Errors: VXL_ERR_INVALID_ARG for any violated condition above, VXL_ERR_UNSUPPORTED for
- * n_chunks > VXL_MAX_CHUNKS, VXL_ERR_HIP.
+ * n_chunks > VXL_MAX_CHUNKS, VXL_ERR_ALLOC when the handle or its device memory cannot be
+ * allocated, VXL_ERR_HIP for any other failing runtime call.
  */
 vxl_status vxl_layout_create(int32_t n_tokens, int32_t n_prefix, int32_t n_chunks,
                              const int32_t* chunk_bounds, const int32_t* sparse_offsets,
@@ -117,9 +120,12 @@ vxl_status vxl_layout_create_windowed(int32_t n_tokens, int32_t n_prefix, int32_
                                       vxl_layout** out);
 vxl_status vxl_layout_destroy(vxl_layout* layout);
 
-/* Bytes of workspace the given hot call needs (0 on invalid arguments).  batch, n_q_tokens
- * and l_cap are read by the ops that take them (SCORE_TOPK, GATHER: batch; SCORE_MASS: batch,
- * n_q_tokens; DECODE: batch, n_q_tokens, l_cap); layout may be NULL for VXL_OP_DECODE. */
+/* Bytes of workspace the given hot call needs (0 on invalid arguments, and for VXL_OP_GATHER,
+ * which needs none).  batch, n_q_tokens and l_cap are read by the ops that take them (SCORE_TOPK:
+ * batch; SCORE_MASS: batch, n_q_tokens; DECODE: batch, n_q_tokens, l_cap).  The decode call is
+ * sized by the capacity of the mixed buffers it will be given, l_cap, and not by the number k of
+ * dense chunks, because it takes no layout: l_cap = vxl_mixed_kv_capacity(layout, k) for the
+ * caller's k, or anything larger.  layout may be NULL for VXL_OP_DECODE. */
 size_t vxl_workspace_bytes(vxl_op op, const vxl_layout* layout, const vxl_attn_desc* desc,
                            int32_t batch, int32_t n_q_tokens, int32_t l_cap);
 
@@ -195,15 +201,18 @@ vxl_status vxl_chunk_score_topk_mass(const vxl_layout* layout, const vxl_attn_de
  *               untouched
  *   mix_len     device int32 [batch] (written)
  *   src_idx     device int32 [batch, l_cap] source token id of every mixed row, or NULL
- * l_cap must be at least vxl_mixed_kv_capacity(layout, k) for the k that produced the mask;
- * the host cannot see the mask, so it checks l_cap >= capacity for k = 0 and the kernel never
- * writes beyond l_cap (mix_len is clamped to l_cap; a clamped value signals the overflow).
+ * No workspace.  l_cap must be at least vxl_mixed_kv_capacity(layout, k) for the k that produced
+ * the mask.  The mask lives on the device, so the host can only check l_cap >= the capacity for
+ * k = 0 (VXL_ERR_INVALID_ARG otherwise); a query whose mask selects more rows than l_cap holds is
+ * reported on the device, never truncated: none of its rows is copied and mix_len[b] is set to
+ * MINUS the number of rows it needs.  vxl_bilevel_decode treats a length <= 0 as an empty set
+ * (O = 0, LSE = -inf), so the chain score -> gather -> decode needs no host check in between and
+ * a caller finds the overflow in mix_len whenever it next looks.
  */
 vxl_status vxl_gather_bilevel_kv(const vxl_layout* layout, const vxl_attn_desc* desc,
                                  const void* K, const void* V, const uint8_t* dense_mask,
                                  int32_t batch, void* Kmix, void* Vmix, int32_t l_cap,
-                                 int32_t* mix_len, int32_t* src_idx,
-                                 void* workspace, size_t workspace_bytes, vxl_stream stream);
+                                 int32_t* mix_len, int32_t* src_idx, vxl_stream stream);
 
 /*
  * Pooled sparse KVs ("Bi-level KVs Decoding": the dense KVs are chunked and a pooling operation on
@@ -231,8 +240,7 @@ vxl_status vxl_gather_bilevel_kv_pooled(const vxl_layout* layout, const vxl_attn
                                         const void* K, const void* V, const void* Ksp,
                                         const void* Vsp, const uint8_t* dense_mask, int32_t batch,
                                         void* Kmix, void* Vmix, int32_t l_cap, int32_t* mix_len,
-                                        int32_t* src_idx, void* workspace, size_t workspace_bytes,
-                                        vxl_stream stream);
+                                        int32_t* src_idx, vxl_stream stream);
 
 /*
  * GQA decode attention over the mixed KV set ("Bi-level KVs Decoding"): every query token
@@ -240,7 +248,8 @@ vxl_status vxl_gather_bilevel_kv_pooled(const vxl_layout* layout, const vxl_attn
  * partial results are merged by log-sum-exp in a fixed order (deterministic).
  *   Qd, O    device [batch, n_q_tokens, n_q_heads, head_dim];  LSE device float
  *            [batch, n_q_tokens, n_q_heads] or NULL
- *   mix_len  device int32 [batch]; entries must be in [1, l_cap]
+ *   mix_len  device int32 [batch]; entries above l_cap are read as l_cap, entries <= 0 (an empty
+ *            set, or the overflow report of vxl_gather_bilevel_kv) give O = 0 and LSE = -inf
  */
 vxl_status vxl_bilevel_decode(const vxl_attn_desc* desc, const void* Qd, int32_t batch,
                               int32_t n_q_tokens, const void* Kmix, const void* Vmix,
@@ -265,11 +274,11 @@ vxl_status vxl_bilevel_decode(const vxl_attn_desc* desc, const void* Qd, int32_t
  *       dense_mask     HOST uint8 [batch, n_chunks] (the caller has brought the selection back)
  *       Kmix, Vmix     device [batch, n_kv_heads, l_cap, head_dim]; rows >= length untouched
  *       mix_len_host   host int32 [batch] written before the call returns, or NULL
- *       mix_len        device int32 [batch] written by a copy on `stream`, or NULL (batch <= 256;
- *                      its pinned staging array belongs to the store: reloads of one store that
- *                      write mix_len must be ordered, e.g. by using one stream)
+ *       mix_len        device int32 [batch] written by a one-block kernel on `stream` that carries
+ *                      the lengths as launch arguments, or NULL (batch <= 256); reloads of one
+ *                      store may be issued back to back, on one stream or on several
  *   Errors: VXL_ERR_INVALID_ARG (null pointers; a query whose mixed length exceeds l_cap --
- *   nothing is copied then), VXL_ERR_UNSUPPORTED, VXL_ERR_HIP.
+ *   nothing is copied then), VXL_ERR_UNSUPPORTED, VXL_ERR_ALLOC (create), VXL_ERR_HIP.
  * The reload moves 2 * n_kv_heads * mix_len * head_dim * elem bytes per query over the host link;
  * on a side stream it overlaps the decode of another query.
  */

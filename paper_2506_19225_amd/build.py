@@ -3,6 +3,7 @@ from __future__ import annotations
 
 import concurrent.futures as cf
 import os
+import re
 import subprocess
 import sys
 
@@ -12,7 +13,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libvxl.so")
 
-SOURCES = ["vxl_api.hip", "vxl_simple.hip", "vxl_bilevel.hip", "vxl_prefill.hip", "vxl_decode.hip", "vxl_mass.hip", "vxl_prefill_pipe.hip", "vxl_store.hip"]
+SOURCES = ["vxl_api.hip", "vxl_simple.hip", "vxl_bilevel.hip", "vxl_prefill.hip", "vxl_decode.hip", "vxl_mass.hip", "vxl_store.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=default",
@@ -33,13 +34,8 @@ def _hipcc() -> str:
 # loads issued from inline assembly, waited for with hand-written vmcnt values): a register spill
 # would add scratch loads and stores to that count behind the kernel's back, so the build refuses
 # a compile in which one of them uses scratch memory.
-NO_SCRATCH = {"vxl_prefill.hip": ("prefill_dma_kernel",), "vxl_decode.hip": ("decode_ring_kernel",),
-              "vxl_prefill_pipe.hip": ("prefill_pipe_kernel",)}
-
-# Per-file compiler options.  The software-pipelined pre-filling kernel runs one wave per SIMD with
-# more than 256 registers; its score products must land in ordinary vector registers (the vector
-# ALU reads them), its output accumulators are placed in the accumulation registers by hand.
-EXTRA_FLAGS = {"vxl_prefill_pipe.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+NO_SCRATCH = {"vxl_prefill.hip": ("prefill_dma_kernel",),
+              "vxl_decode.hip": ("decode_ring_kernel", "decode_wave_kernel")}
 
 
 def _check_no_scratch(src: str, remarks: str) -> None:
@@ -54,12 +50,39 @@ def _check_no_scratch(src: str, remarks: str) -> None:
                                    "its hand-kept vmcnt bookkeeping needs a spill-free compile")
 
 
+def _check_no_compiler_m0(src: str) -> None:
+    """The hand-issued direct loads of these kernels overwrite m0 inside inline assembly, behind
+    the compiler's back; that is only sound while the compiler itself never reads or writes m0 in
+    the same kernel.  Scan the device assembly (kept by --save-temps) outside the inline blocks."""
+    stem = os.path.splitext(src)[0]
+    asm = [f for f in os.listdir(OBJ) if f.startswith(stem + "-hip-amdgcn") and f.endswith(".s")]
+    if not asm:
+        raise RuntimeError(f"{src}: device assembly not found for the m0 check")
+    name, in_asm = None, False
+    hand, own = {}, {}            # per kernel: m0 written inside inline assembly / by the compiler
+    for ln in open(os.path.join(OBJ, asm[0])):
+        st = ln.strip()
+        if st.startswith("_Z") and ":" in st and st.split(":")[0].isidentifier():
+            name = st.split(":")[0]
+        elif st.startswith(".Lfunc_end"):
+            name = None
+        elif st.startswith(";;#ASMSTART"):
+            in_asm = True
+        elif st.startswith(";;#ASMEND"):
+            in_asm = False
+        elif name and any(k in name for k in NO_SCRATCH[src]):
+            code = st.split(";")[0]
+            if re.search(r"\bm0\b", code):
+                (hand if in_asm else own).setdefault(name, code.strip())
+    for name in hand:             # (an instance without hand-issued loads may use m0 as it likes)
+        if name in own:
+            raise RuntimeError(f"{src}: kernel {name} has a compiler-generated use of m0 ({own[name]}) "
+                               "beside inline-assembly direct loads that overwrite m0")
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    extra = ["-Rpass-analysis=kernel-resource-usage"] if src in NO_SCRATCH else []
-    extra += EXTRA_FLAGS.get(src, [])
-    if os.environ.get("VXL_PIPE_ABL") and src == "vxl_prefill_pipe.hip":     # measurement builds only
-        extra += ["-DVXL_PIPE_ABL=" + os.environ["VXL_PIPE_ABL"]]
+    extra = ["-Rpass-analysis=kernel-resource-usage", "--save-temps=obj"] if src in NO_SCRATCH else []
     cmd = [_hipcc(), *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
@@ -68,6 +91,7 @@ def _compile(src: str) -> str:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
     if src in NO_SCRATCH:
         _check_no_scratch(src, err)
+        _check_no_compiler_m0(src)
         keep, skip = [], 0                                   # drop the remarks (and their source echo)
         for ln in err.splitlines():
             if "[-Rpass-analysis=kernel-resource-usage]" in ln:

@@ -1,6 +1,7 @@
 // Host side of the C ABI: argument validation, the layout handle (device copies of the
 // chunking and the pre-filling tile schedule), workspace planning and kernel dispatch.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -12,7 +13,7 @@
 namespace vxl {
 
 static thread_local char g_last_error[512] = "";
-static int g_force_simple = 0;
+static std::atomic<int> g_force_simple{0};
 
 void set_last_error(const char* what, hipError_t e) {
     snprintf(g_last_error, sizeof(g_last_error), "%s: %s", what, hipGetErrorString(e));
@@ -61,7 +62,7 @@ PrefillWorkspace prefill_workspace(const vxl_layout* L, const vxl_attn_desc* d) 
     return w;
 }
 
-static int g_decode_step_waves = 0;     // measurement hook: 0 = choose, 4 or 8 = force
+static std::atomic<int> g_decode_step_waves{0};     // cross-check hook (vxl_debug.h): 0 = choose, 4 or 8 = force
 extern "C" void vxl_debug_decode_step_waves(int w) { g_decode_step_waves = (w == 4 || w == 8) ? w : 0; }
 
 DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
@@ -143,14 +144,15 @@ const char* vxl_status_string(vxl_status s) {
         case VXL_ERR_UNSUPPORTED: return "unsupported dtype, head_dim or chunk count";
         case VXL_ERR_WORKSPACE: return "workspace missing or too small";
         case VXL_ERR_HIP: return "HIP runtime error";
+        case VXL_ERR_ALLOC: return "host or device memory allocation failed";
     }
     return "unknown status";
 }
 
 const char* vxl_last_error(void) { return g_last_error; }
 
-// Test hook: route BF16 calls through the plain vector-ALU kernels (an on-device cross-check
-// of the matrix-core kernels).  Not part of the public header.
+// Test hook (vxl_debug.h): route BF16 calls through the plain vector-ALU kernels (an on-device
+// cross-check of the matrix-core kernels).
 void vxl_debug_force_simple(int on) { g_force_simple = on; }
 
 vxl_status vxl_layout_create(int32_t n_tokens, int32_t n_prefix, int32_t n_chunks,
@@ -188,7 +190,7 @@ vxl_status vxl_layout_create_windowed(int32_t n_tokens, int32_t n_prefix, int32_
     }
 
     vxl_layout* L = new (std::nothrow) vxl_layout();
-    if (!L) return VXL_ERR_INVALID_ARG;
+    if (!L) return VXL_ERR_ALLOC;
     L->n_tokens = n_tokens; L->n_prefix = n_prefix; L->n_chunks = n_chunks; L->s_total = s_total;
     L->window = window;
     L->bounds.assign(chunk_bounds, chunk_bounds + n_chunks + 1);
@@ -293,7 +295,7 @@ vxl_status vxl_layout_create_windowed(int32_t n_tokens, int32_t n_prefix, int32_
         set_last_error("vxl_layout_create", e);
         if (L->d_blob) (void)hipFree(L->d_blob);
         delete L;
-        return VXL_ERR_HIP;
+        return e == hipErrorOutOfMemory ? VXL_ERR_ALLOC : VXL_ERR_HIP;
     }
     char* base = (char*)L->d_blob;
     L->d_bounds = (int32_t*)(base + o_bounds);
@@ -346,9 +348,8 @@ size_t vxl_workspace_bytes(vxl_op op, const vxl_layout* L, const vxl_attn_desc* 
             if (!L || batch <= 0) return 0;
             return align_up((size_t)batch * d->n_kv_heads * d->head_dim * 4, 256) +
                    align_up((size_t)d->n_kv_heads * std::max(1, L->n_chunks) * d->head_dim * 4, 256);
-        case VXL_OP_GATHER:
-            if (!L || batch <= 0) return 0;
-            return align_up((size_t)batch * (L->n_chunks + 2) * 4, 256);
+        case VXL_OP_GATHER:          // the gather keeps its per-query offsets in LDS: no workspace
+            return 0;
         case VXL_OP_DECODE:
             if (batch <= 0 || n_q_tokens <= 0 || l_cap <= 0) return 0;
             return std::max<size_t>(256, decode_plan(d, batch, n_q_tokens, l_cap).total);
@@ -426,8 +427,7 @@ vxl_status vxl_chunk_score_topk_mass(const vxl_layout* L, const vxl_attn_desc* d
 vxl_status vxl_gather_bilevel_kv(const vxl_layout* L, const vxl_attn_desc* d, const void* K,
                                  const void* V, const uint8_t* dense_mask, int32_t batch,
                                  void* Kmix, void* Vmix, int32_t l_cap, int32_t* mix_len,
-                                 int32_t* src_idx, void* workspace, size_t workspace_bytes,
-                                 vxl_stream stream) {
+                                 int32_t* src_idx, vxl_stream stream) {
     vxl_status st;
     if (!L) return VXL_ERR_INVALID_ARG;
     if (!desc_ok(d, &st)) return st;
@@ -435,10 +435,8 @@ vxl_status vxl_gather_bilevel_kv(const vxl_layout* L, const vxl_attn_desc* d, co
     if (L->n_chunks > 0 && !dense_mask) return VXL_ERR_INVALID_ARG;
     if (!aligned16(K) || !aligned16(V) || !aligned16(Kmix) || !aligned16(Vmix)) return VXL_ERR_INVALID_ARG;
     if (l_cap < vxl_mixed_kv_capacity(L, 0)) return VXL_ERR_INVALID_ARG;
-    const size_t need = vxl_workspace_bytes(VXL_OP_GATHER, L, d, batch, 0, 0);
-    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return VXL_ERR_WORKSPACE;
     return launch_gather(L, d, K, V, nullptr, nullptr, dense_mask, batch, Kmix, Vmix, l_cap, mix_len, src_idx,
-                         (int32_t*)workspace, (hipStream_t)stream);
+                         (hipStream_t)stream);
 }
 
 vxl_status vxl_pool_sparse_kv(const vxl_layout* L, const vxl_attn_desc* d, const void* K, const void* V,
@@ -455,8 +453,8 @@ vxl_status vxl_pool_sparse_kv(const vxl_layout* L, const vxl_attn_desc* d, const
 vxl_status vxl_gather_bilevel_kv_pooled(const vxl_layout* L, const vxl_attn_desc* d, const void* K,
                                         const void* V, const void* Ksp, const void* Vsp,
                                         const uint8_t* dense_mask, int32_t batch, void* Kmix, void* Vmix,
-                                        int32_t l_cap, int32_t* mix_len, int32_t* src_idx, void* workspace,
-                                        size_t workspace_bytes, vxl_stream stream) {
+                                        int32_t l_cap, int32_t* mix_len, int32_t* src_idx,
+                                        vxl_stream stream) {
     vxl_status st;
     if (!L) return VXL_ERR_INVALID_ARG;
     if (!desc_ok(d, &st)) return st;
@@ -465,12 +463,10 @@ vxl_status vxl_gather_bilevel_kv_pooled(const vxl_layout* L, const vxl_attn_desc
     if (L->s_total > 0 && (!Ksp || !Vsp || !aligned16(Ksp) || !aligned16(Vsp))) return VXL_ERR_INVALID_ARG;
     if (!aligned16(K) || !aligned16(V) || !aligned16(Kmix) || !aligned16(Vmix)) return VXL_ERR_INVALID_ARG;
     if (l_cap < vxl_mixed_kv_capacity(L, 0)) return VXL_ERR_INVALID_ARG;
-    const size_t need = vxl_workspace_bytes(VXL_OP_GATHER, L, d, batch, 0, 0);
-    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return VXL_ERR_WORKSPACE;
     // (a layout without sparse rows never reads the pooled buffers; the kernel takes the pooled
     // path only when they are given)
     return launch_gather(L, d, K, V, L->s_total > 0 ? Ksp : nullptr, L->s_total > 0 ? Vsp : nullptr, dense_mask,
-                         batch, Kmix, Vmix, l_cap, mix_len, src_idx, (int32_t*)workspace, (hipStream_t)stream);
+                         batch, Kmix, Vmix, l_cap, mix_len, src_idx, (hipStream_t)stream);
 }
 
 vxl_status vxl_bilevel_decode(const vxl_attn_desc* d, const void* Qd, int32_t batch,

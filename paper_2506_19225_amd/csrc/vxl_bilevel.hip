@@ -318,7 +318,8 @@ __global__ __launch_bounds__(256) void pool_sparse_kernel(const T* __restrict__ 
 // share of the mixed rows: a group of LPR lanes per row (all KV heads, K and V, 16-byte
 // accesses), the source row found by binary search in the scanned offsets.  A block handles
 // `groups` consecutive passes of 256 / LPR rows (chosen by the host so that small gathers still
-// fill the chip and large ones amortise the scan).  Block 0 of a query writes mix_len.
+// fill the chip and large ones amortise the scan).  Block 0 of a query writes mix_len; a query whose
+// mixed set does not fit l_cap gets mix_len = -(rows needed) and none of its rows is copied.
 // ------------------------------------------------------------------------------------------
 template <int ROW_BYTES>
 __global__ __launch_bounds__(256) void gather_kernel(
@@ -357,10 +358,11 @@ __global__ __launch_bounds__(256) void gather_kernel(
     }
     if (tid == 0) {
         off[n_chunks] = carry;
-        if (blockIdx.x == 0) mix_len[b] = min(carry, l_cap);
+        // a mixed set that does not fit l_cap is reported, not truncated: minus the rows it needs
+        if (blockIdx.x == 0) mix_len[b] = carry <= l_cap ? carry : -carry;
     }
     __syncthreads();
-    const int len = min(off[n_chunks], l_cap);
+    const int len = off[n_chunks] <= l_cap ? off[n_chunks] : 0;
     const int part = tid % LPR;
     for (int gi = 0; gi < groups; ++gi) {
         const int r = (blockIdx.x * groups + gi) * ROWS + tid / LPR;
@@ -465,9 +467,7 @@ vxl_status launch_pool_sparse(const vxl_layout* L, const vxl_attn_desc* d, const
 
 vxl_status launch_gather(const vxl_layout* L, const vxl_attn_desc* d, const void* K, const void* V,
                          const void* Ksp, const void* Vsp, const uint8_t* dense_mask, int batch, void* Kmix,
-                         void* Vmix, int l_cap, int32_t* mix_len, int32_t* src_idx, int32_t* ws_offsets,
-                         hipStream_t s) {
-    (void)ws_offsets;                                         // (the offsets live in LDS)
+                         void* Vmix, int l_cap, int32_t* mix_len, int32_t* src_idx, hipStream_t s) {
     const int row_bytes = d->head_dim * (d->dtype == VXL_BF16 ? 2 : 4);
     const size_t smem = (size_t)(L->n_chunks + 1) * sizeof(int);
     const TokStrides ts = tok_strides(d, L->n_tokens);

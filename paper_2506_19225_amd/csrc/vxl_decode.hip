@@ -541,8 +541,10 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restri
         const float wsum = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
         const int t = rho / group, hg = rho % group;
         const size_t row = ((size_t)b * T_q + t) * n_q_heads + g * group + hg;
-        O[row * D + tid] = f32_to_bf16(a / wsum);
-        if (LSE && tid == 0) LSE[row] = (mx + __builtin_amdgcn_logf(wsum)) * kLn2;
+        // an empty mixed set (every split recorded weight 0): O = 0, LSE = -inf
+        const bool empty = !(wsum > 0.f);
+        O[row * D + tid] = empty ? (uint16_t)0 : f32_to_bf16(a / wsum);
+        if (LSE && tid == 0) LSE[row] = empty ? -INFINITY : (mx + __builtin_amdgcn_logf(wsum)) * kLn2;
     }
 }
 
@@ -559,12 +561,13 @@ static vxl_status run_decode(const vxl_attn_desc* d, float scale, const void* Qd
     const int group = d->n_q_heads / d->n_kv_heads;
     const int n_rows = group * T;
     const int n_rtile = (n_rows + C::RT - 1) / C::RT;
-    static bool attr_done = false;
-    if (!attr_done) {
+    static PerDeviceOnce attr;
+    const vxl_status ast = attr.run([] {
         VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_split_kernel<D, QB>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
-        attr_done = true;
-    }
+        return VXL_OK;
+    });
+    if (ast != VXL_OK) return ast;
     hipLaunchKernelGGL((decode_split_kernel<D, QB>), dim3(p.n_split, n_rtile * d->n_kv_heads, batch), dim3(256),
                        C::LDS_BYTES, s, (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix,
                        mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap, n_rtile,
@@ -588,12 +591,13 @@ static vxl_status run_decode_ring(const vxl_attn_desc* d, float scale, const voi
     const int group = d->n_q_heads / d->n_kv_heads;
     const int n_rows = group * T;
     const int n_rtile = (n_rows + C::RT - 1) / C::RT;
-    static bool attr_done = false;
-    if (!attr_done) {
+    static PerDeviceOnce attr;
+    const vxl_status ast = attr.run([] {
         VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_ring_kernel<D, 4>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
-        attr_done = true;
-    }
+        return VXL_OK;
+    });
+    if (ast != VXL_OK) return ast;
     hipLaunchKernelGGL((decode_ring_kernel<D, 4>), dim3(p.n_split, n_rtile * d->n_kv_heads, batch), dim3(512),
                        C::LDS_BYTES, s, (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix,
                        mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap, n_rtile,
@@ -616,14 +620,15 @@ static vxl_status run_decode_wave(const vxl_attn_desc* d, float scale, const voi
     const int group = d->n_q_heads / d->n_kv_heads;
     const int n_rows = group * T;
     constexpr int lds_bytes = 8 * 2 * kStepTile * D * 2;      // 8 tile pairs in either form
-    static bool attr_done = false;
-    if (!attr_done) {
+    static PerDeviceOnce attr;
+    const vxl_status ast = attr.run([] {
         VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_wave_kernel<D, 8, 1>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
         VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_wave_kernel<D, 4, 2>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
-        attr_done = true;
-    }
+        return VXL_OK;
+    });
+    if (ast != VXL_OK) return ast;
     if (p.step_waves == 8)
         hipLaunchKernelGGL((decode_wave_kernel<D, 8, 1>), dim3(p.n_split, d->n_kv_heads, batch), dim3(512),
                            lds_bytes, s, (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix,

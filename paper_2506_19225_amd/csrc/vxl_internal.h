@@ -4,9 +4,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <vector>
 
 #include "vxl.h"
+#include "vxl_debug.h"
 
 namespace vxl {
 
@@ -85,6 +87,30 @@ void set_last_error(const char* what, hipError_t e);
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// One-time set-up per device (kernel attributes, device properties), safe to reach from several
+// host threads: `run(f)` calls f() once for the current device, under a lock, and remembers a
+// success; a failure is returned and tried again by the next call.
+constexpr int kMaxDevices = 64;
+class PerDeviceOnce {
+    std::mutex mu_;
+    bool done_[kMaxDevices] = {};
+
+  public:
+    template <typename F>
+    vxl_status run(F&& f) {
+        int dev = 0;
+        VXL_HIP_TRY(hipGetDevice(&dev));
+        if (dev < 0 || dev >= kMaxDevices) return VXL_ERR_UNSUPPORTED;
+        std::lock_guard<std::mutex> lock(mu_);
+        if (done_[dev]) return VXL_OK;
+        const vxl_status st = f();
+        if (st == VXL_OK) done_[dev] = true;
+        return st;
+    }
+};
+// Compute units of the current device (at least 8), cached per device.
+vxl_status device_cu_count(int* n_cus);
+
 // ---- pre-filling ----
 // Element strides of the per-layer tensors (the descriptor's, or the dense head-major default).
 struct TokStrides {
@@ -108,10 +134,6 @@ PrefillWorkspace prefill_workspace(const vxl_layout* L, const vxl_attn_desc* d);
 vxl_status launch_prefill_bf16(const vxl_layout* L, const vxl_attn_desc* d, float scale,
                                const void* Q, const void* K, const void* V, void* O, float* LSE,
                                void* ws, hipStream_t s);
-// main kernel of the software-pipelined form (4 waves x 64 rows); pre-pass done by the caller
-vxl_status launch_prefill_pipe_main(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Q,
-                                    const void* K, const void* V, const uint16_t* kctx, const uint16_t* vctx,
-                                    void* O, float* LSE, int* queue, hipStream_t s);
 vxl_status launch_prefill_simple(const vxl_layout* L, const vxl_attn_desc* d, float scale,
                                  const void* Q, const void* K, const void* V, void* O, float* LSE,
                                  hipStream_t s);
@@ -140,8 +162,7 @@ vxl_status launch_score_mass(const vxl_layout* L, const vxl_attn_desc* d, float 
 // Ksp / Vsp: pooled sparse rows [Hkv, S_total, D] read instead of the kept rows, or null
 vxl_status launch_gather(const vxl_layout* L, const vxl_attn_desc* d, const void* K, const void* V,
                          const void* Ksp, const void* Vsp, const uint8_t* dense_mask, int batch, void* Kmix,
-                         void* Vmix, int l_cap, int32_t* mix_len, int32_t* src_idx, int32_t* ws_offsets,
-                         hipStream_t s);
+                         void* Vmix, int l_cap, int32_t* mix_len, int32_t* src_idx, hipStream_t s);
 vxl_status launch_pool_sparse(const vxl_layout* L, const vxl_attn_desc* d, const void* K, const void* V,
                               void* Ksp, void* Vsp, hipStream_t s);
 

@@ -273,7 +273,9 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 __device__ __forceinline__ void wait_vmcnt0_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0x0070); }
 // 16 bytes per lane from (uniform base + per-lane offset) to LDS byte offset lds_off + 16*lane.
 // Issued from inline assembly so that the compiler neither counts it nor orders LDS reads of
-// other ring stages behind it.
+// other ring stages behind it.  The statement overwrites m0 (the LDS base of the load), which the
+// compiler reserves and does not accept on a clobber list: kernels that use dma16 must therefore
+// contain no m0 use of the compiler's own, which the build checks in their generated assembly.
 __device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t lds_off) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(lds_off), "v"(off), "s"(base) : "memory");

@@ -4,16 +4,16 @@
 // followed by the kept rows of all chunks in chunk order -- are compacted into two contiguous
 // buffers, so the history of chunk c is simply their first P + sparse_offsets[c] rows.
 //
-// Main kernel: one workgroup = one query-row tile of one query head of one segment (the prefix
-// or a chunk).  It walks 64-key tiles  history[0, ctx_len)  then  own segment[0, diagonal]  with
-// an online softmax; the arithmetic is in vxl_mfma.h.  Two kernels do this:
-//   prefill_dma_kernel   (default)  256 rows and 8 waves per workgroup, tiles streamed into an LDS
-//                                   ring by direct global-to-LDS loads;
-//   prefill_mfma_kernel  (cross-check) 128 or 256 rows and 4 waves per workgroup, tiles staged
-//                                   through registers into a double buffer.
+// Main kernel (prefill_dma_kernel): a persistent workgroup takes bands of query rows of one
+// segment (the prefix or a chunk) and walks 64-key tiles  history[0, ctx_len)  then  own
+// segment[0, diagonal]  with an online softmax; the arithmetic is in vxl_mfma.h.  256 rows and 8
+// waves per workgroup, tiles streamed into an LDS ring by direct global-to-LDS loads.  A second
+// instance of the same template (128 rows, 4 waves, two workgroups per compute unit) is kept as
+// an on-device cross-check.
 #include <math.h>
 
 #include <algorithm>
+#include <atomic>
 
 #include "vxl_internal.h"
 #include "vxl_mfma.h"
@@ -47,218 +47,10 @@ __global__ __launch_bounds__(256) void compact_kv_kernel(const uint4* __restrict
 }
 
 // ------------------------------------------------------------------------------------------
-// Main kernel.
-// ------------------------------------------------------------------------------------------
-template <int D, int QB>
-struct PrefillCfg {
-    static constexpr int BM = 128 * QB;          // query rows per workgroup (4 waves x QB x 32)
-    static constexpr int KROW = LdsRows<D>::K;   // LDS row strides (elements)
-    static constexpr int VROW = LdsRows<D>::V;
-    static constexpr int K_ELEMS = kKeyTile * KROW;
-    static constexpr int V_ELEMS = kKeyTile * VROW;
-    static constexpr int LDS_BYTES = 2 * (K_ELEMS + V_ELEMS) * 2;
-    static constexpr int LD = D / 32;            // 16-byte loads per thread per K (and per V) tile
-};
-
-template <int D, int QB, bool PROF = false>
-__global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void prefill_mfma_kernel(
-    const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-    const uint16_t* __restrict__ Kctx, const uint16_t* __restrict__ Vctx, uint16_t* __restrict__ O,
-    float* __restrict__ LSE, const Segment* __restrict__ segs, const WorkItem* __restrict__ work,
-    int n_tokens, int n_q_heads, int group, int ctx_rows_pad, float scale, int n_items, int xpg, int dbg,
-    unsigned long long* __restrict__ prof = nullptr) {
-    using C = PrefillCfg<D, QB>;
-    // PROF instances (measurement only) accumulate per-wave cycle counts of the loop phases.
-    unsigned long long pt[6] = {0, 0, 0, 0, 0, 0};
-    auto tick = [&]() -> unsigned long long { return PROF ? (unsigned long long)clock64() : 0ull; };
-    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-    uint16_t* Ks = lds;                          // [2][64][KROW]
-    uint16_t* Vs = lds + 2 * C::K_ELEMS;         // [2][64][VROW]
-
-    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: scalar control flow
-    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  With xpg XCDs per KV
-    // head, all workgroups that read the K/V of one KV head land on the same xpg XCDs.
-    int item, h;
-    if (xpg > 0) {
-        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-        const int j = slot * xpg + xcd % xpg;
-        if (j >= n_items * group) return;
-        item = j / group;
-        h = (xcd / xpg) * group + j % group;
-    } else {
-        item = blockIdx.x / n_q_heads;
-        h = blockIdx.x % n_q_heads;
-    }
-    item = __builtin_amdgcn_readfirstlane(item);                   // uniform: scalar loads and branches
-    h = __builtin_amdgcn_readfirstlane(h);
-    const int g = h / group;
-    const WorkItem wi = work[item];
-    const Segment sg = segs[wi.seg];
-    const int m0 = wi.m_tile * C::BM;
-    const int wrow0 = m0 + wave * 32 * QB;       // first query row (segment-relative) of this wave
-
-    const int n_ctx_t = (sg.ctx_len + kKeyTile - 1) / kKeyTile;
-    const int last_row = min(m0 + C::BM, sg.q_len) - 1;
-    const int n_t = n_ctx_t + (last_row + sg.back) / kKeyTile + 1;      // own keys start `back` rows early
-
-    // ---- this wave's queries, in B-operand layout: lane (l32, hi) holds 8 consecutive d ----
-    bf16x8 qreg[QB][D / 16];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const int row = sg.q_start + min(wrow0 + qb * 32 + l32, sg.q_len - 1);
-        const uint4* src = (const uint4*)(Q + ((size_t)h * n_tokens + row) * D);
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) qreg[qb][ks] = __builtin_bit_cast(bf16x8, src[ks * 2 + hi]);
-    }
-
-    f32x16 o[QB][D / 32];
-    float m_run[QB], l_run[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        m_run[qb] = -INFINITY;
-        l_run[qb] = 0.f;
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db) o[qb][db] = zero16();
-    }
-    const float c2 = scale * kLog2e;
-
-    // Tile ti lives either in the compacted history (rows ti*64 .., zero padded to whole tiles) or
-    // in the segment itself (rows clamped to the segment end: clamped rows are masked by causality).
-    const uint16_t* kctx_g = Kctx + (size_t)g * ctx_rows_pad * D;
-    const uint16_t* vctx_g = Vctx + (size_t)g * ctx_rows_pad * D;
-    const uint16_t* kown = K + ((size_t)g * n_tokens + sg.q_start - sg.back) * D;
-    const uint16_t* vown = V + ((size_t)g * n_tokens + sg.q_start - sg.back) * D;
-    const int ld_r = tid / (D / 8), ld_part = tid % (D / 8);        // this thread's row / 16-byte piece
-    constexpr int ROWS_PER_PASS = 256 / (D / 8);
-    // Prefetch registers as named scalars (LD = 4 pairs for D = 128, 2 for D = 64): they must stay
-    // in VGPRs across the scheduling fence below.
-    uint4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
-    kr2 = kr3 = vr2 = vr3 = zero4();
-
-#define VXL_FETCH1(i_, kr_, vr_)                                                                    \
-    do {                                                                                            \
-        const uint32_t off_ = (uint32_t)min(ld_r + (i_) * ROWS_PER_PASS, rlim_) * (D * 2) + ld_part * 16; \
-        kr_ = *(const uint4*)(kb_ + off_);                                                          \
-        vr_ = *(const uint4*)(vb_ + off_);                                                          \
-    } while (0)
-#define VXL_FETCH(ti_)                                                                              \
-    do {                                                                                            \
-        const int t_ = (dbg & 1) ? 0 : (ti_);                                                       \
-        const bool ctx_ = t_ < n_ctx_t;                                                             \
-        const int row0_ = ctx_ ? t_ * kKeyTile : (t_ - n_ctx_t) * kKeyTile;                         \
-        /* rows of the tile beyond the segment end are clamped to its last row */                   \
-        const int rlim_ = ctx_ ? kKeyTile - 1 : min(kKeyTile - 1, sg.back + sg.q_len - 1 - row0_);  \
-        const char* kb_ = (const char*)(ctx_ ? kctx_g : kown) + (size_t)row0_ * (D * 2);            \
-        const char* vb_ = (const char*)(ctx_ ? vctx_g : vown) + (size_t)row0_ * (D * 2);            \
-        VXL_FETCH1(0, kr0, vr0);                                                                    \
-        VXL_FETCH1(1, kr1, vr1);                                                                    \
-        if constexpr (C::LD > 2) {                                                                  \
-            VXL_FETCH1(2, kr2, vr2);                                                                \
-            VXL_FETCH1(3, kr3, vr3);                                                                \
-        }                                                                                           \
-    } while (0)
-#define VXL_STAGE1(buf_, i_, kr_, vr_)                                                              \
-    do {                                                                                            \
-        const int r_ = ld_r + (i_) * ROWS_PER_PASS;                                                 \
-        *(uint4*)(Ks + (buf_) * C::K_ELEMS + k_tile_off<D>(r_, ld_part)) = kr_;                     \
-        *(uint4*)(Vs + (buf_) * C::V_ELEMS + r_ * C::VROW + ld_part * 8) = vr_;                     \
-    } while (0)
-#define VXL_STAGE(buf_)                                                                             \
-    do {                                                                                            \
-        VXL_STAGE1(buf_, 0, kr0, vr0);                                                              \
-        VXL_STAGE1(buf_, 1, kr1, vr1);                                                              \
-        if constexpr (C::LD > 2) {                                                                  \
-            VXL_STAGE1(buf_, 2, kr2, vr2);                                                          \
-            VXL_STAGE1(buf_, 3, kr3, vr3);                                                          \
-        }                                                                                           \
-    } while (0)
-
-    VXL_FETCH(0);
-    VXL_STAGE(0);
-    __syncthreads();
-
-    for (int ti = 0; ti < n_t; ++ti) {
-        const int buf = ti & 1;
-        const unsigned long long t0 = tick();
-        VXL_FETCH(min(ti + 1, n_t - 1));          // unconditional: the loads stay in flight below
-        __builtin_amdgcn_sched_barrier(0);        // keep them ahead of the arithmetic
-        unsigned long long t1 = t0, t2 = t0, t3 = t0;
-
-        const bool is_ctx = ti < n_ctx_t;
-        const int key0 = is_ctx ? ti * kKeyTile : (ti - n_ctx_t) * kKeyTile;   // tile start in its space
-        // own tiles entirely above this wave's rows contribute nothing
-        const bool skip = !is_ctx && key0 > wrow0 + sg.back + 32 * QB - 1;
-        if (!skip) {
-            f32x16 s[QB][2];
-            qk_tile<D, QB, C::KROW>(Ks + buf * C::K_ELEMS, qreg, l32, hi, s);
-            if (PROF) { __builtin_amdgcn_sched_barrier(0); asm volatile("s_nop 0" :: "v"(s[0][0][15]), "v"(s[0][1][15])); t1 = tick(); }
-            // ---- mask (ragged last history tile, causal own tiles) ----
-            const bool need_mask = is_ctx ? (key0 + kKeyTile > sg.ctx_len) : (key0 + kKeyTile - 1 > wrow0 + sg.back);
-            if (need_mask) {
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    // tile-relative key kt is visible iff kt <= lim
-                    const int lim = is_ctx ? sg.ctx_len - key0 - 1 : wrow0 + sg.back + qb * 32 + l32 - key0;
-#pragma unroll
-                    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            s[qb][kb][r] = acc_key(kb, r, hi) <= lim ? s[qb][kb][r] : -INFINITY;
-                }
-            }
-            bf16x8 pb[QB][2][2];
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-                softmax_tile<D / 32>(s[qb], c2, m_run[qb], l_run[qb], o[qb], pb[qb]);
-            if (PROF) { __builtin_amdgcn_sched_barrier(0); asm volatile("s_nop 0" :: "v"(pb[0][1][1])); t2 = tick(); }
-            pv_tile<D, QB, C::VROW>(Vs + buf * C::V_ELEMS, pb, lane, o);
-            if (PROF) { __builtin_amdgcn_sched_barrier(0); asm volatile("s_nop 0" :: "v"(o[0][0][15]), "v"(o[0][D / 32 - 1][15])); t3 = tick(); }
-        }
-        VXL_STAGE(buf ^ 1);
-        const unsigned long long t4 = tick();
-        __syncthreads();
-        if (PROF) {
-            const unsigned long long t5 = tick();
-            pt[0] += t1 - t0; pt[1] += t2 - t1; pt[2] += t3 - t2; pt[3] += t4 - t3; pt[4] += t5 - t4; pt[5] += 1;
-        }
-    }
-    if (PROF && prof && lane == 0) {
-        for (int i = 0; i < 6; ++i) prof[((size_t)blockIdx.x * 4 + wave) * 6 + i] = pt[i];
-    }
-#undef VXL_FETCH
-#undef VXL_FETCH1
-#undef VXL_STAGE
-#undef VXL_STAGE1
-
-    // ---- normalise and store: lane owns query column l32; 4 consecutive d per register quad ----
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const int q_off = wrow0 + qb * 32 + l32;
-        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
-        if (q_off >= sg.q_len) continue;
-        const float inv = 1.f / l_tot;
-        const size_t tok = (size_t)h * n_tokens + sg.q_start + q_off;
-        uint16_t* orow = O + tok * D;
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                bf16x4 v;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (__bf16)(o[qb][db][rq * 4 + e] * inv);
-                *(bf16x4*)(orow + db * 32 + rq * 8 + hi * 4) = v;
-            }
-        if (LSE && hi == 0) LSE[tok] = m_run[qb] * scale + logf(l_tot);
-    }
-}
-
-// ------------------------------------------------------------------------------------------
-// Main kernel, streaming variant: 8 waves = 256 query rows per workgroup (one workgroup per
+// Main kernel: 8 waves = 256 query rows per workgroup (one workgroup per
 // compute unit, two waves per SIMD), K/V tiles brought in by direct global->LDS loads into a ring
-// of NS stages, two tiles ahead of the arithmetic.  Against the 4-wave kernel this halves the
-// tile traffic, the barriers and the LDS fills per FLOP, takes the staging out of the VALU/VGPR
-// budget, and hides the memory latency behind several tiles of arithmetic.
+// of NS stages, two tiles ahead of the arithmetic: the staging stays out of the VALU/VGPR budget
+// and the memory latency hides behind several tiles of arithmetic.
 //
 // The loads are issued from inline assembly: the compiler cannot see them, so it neither orders
 // them against the LDS reads of other stages nor counts them in its own vmcnt bookkeeping; the
@@ -526,77 +318,18 @@ vxl_status enable_big_lds(F kernel, int bytes) {
 
 }  // namespace
 
-static int g_prefill_variant = 0;
-static int g_prefill_dbg = 0;
-static unsigned long long* g_prof_buf = nullptr;
-extern "C" void vxl_debug_flags(int flags) { g_prefill_dbg = flags; }
-// Measurement only: a device buffer of 6 counters per wave (4 per workgroup) makes the next
-// vxl_chunk_prefill calls run the instrumented instance of the kernel (D = 128, one row block).
-extern "C" void vxl_debug_prefill_profile(void* buf) { g_prof_buf = (unsigned long long*)buf; }
-static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
-// Cross-check and measurement only: 0 = the streaming kernel (default); 1, 2 = the 4-wave
-// register-staged kernel with one or two 32-row blocks per wave.
-// 3 = the software-pipelined 4-wave kernel with 64 rows per wave.
-// 4 = the streaming kernel as two independent 4-wave workgroups per compute unit (128-row bands,
-// a 2-stage ring each, one meeting per tile).
-extern "C" void vxl_debug_prefill_variant(int v) { g_prefill_variant = (v >= 1 && v <= 4) ? v : 0; }
-// Measurement hook: when both events are set, every vxl_chunk_prefill records them on its stream
-// immediately before and after the main attention kernel (the pre-pass is outside the bracket).
+static std::atomic<int> g_prefill_variant{0};
+static std::atomic<hipEvent_t> g_ev_start{nullptr}, g_ev_stop{nullptr};
+// Cross-check only (declared in vxl_debug.h): 0 = the default instance (8 waves, 256-row bands, one
+// workgroup per compute unit); 1 = the same kernel as two independent 4-wave workgroups per compute
+// unit (128-row bands, a 2-stage ring each, one meeting per tile).
+extern "C" void vxl_debug_prefill_variant(int v) { g_prefill_variant = v == 1 ? 1 : 0; }
+// Measurement hook (declared in vxl_debug.h): when both events are set, every vxl_chunk_prefill
+// records them on its stream immediately before and after the main attention kernel (the pre-pass
+// is outside the bracket).
 extern "C" void vxl_debug_prefill_events(void* start, void* stop) {
     g_ev_start = (hipEvent_t)start;
     g_ev_stop = (hipEvent_t)stop;
-}
-
-template <int D, int QB>
-static vxl_status run_prefill(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Q,
-                              const void* K, const void* V, void* O, float* LSE, void* ws, hipStream_t s) {
-    using C = PrefillCfg<D, QB>;
-    if (!dense_layout(d)) return VXL_ERR_UNSUPPORTED;          // (the cross-check kernels read dense tensors only)
-    const TokStrides ts = tok_strides(d, L->n_tokens);
-    const PrefillWorkspace w = prefill_workspace(L, d);
-    uint16_t* kctx = (uint16_t*)((char*)ws + w.kctx);
-    uint16_t* vctx = (uint16_t*)((char*)ws + w.vctx);
-    const int n_rows_pad = L->n_ctx_tiles * kKeyTile;
-    if (L->n_ctx_tiles > 0) {
-        constexpr int rows = 256 / (D * 2 / 16);
-        hipLaunchKernelGGL((compact_kv_kernel<D>), dim3((n_rows_pad + rows - 1) / rows, d->n_kv_heads),
-                           dim3(256), 0, s, (const uint4*)K, (const uint4*)V, L->d_tile_src, (uint4*)kctx,
-                           (uint4*)vctx, n_rows_pad, ts.kh / 8, ts.kt / 8, (int*)nullptr);
-        VXL_HIP_TRY(hipGetLastError());
-    }
-    static bool attr_done = false;
-    if (!attr_done) {
-        vxl_status st = enable_big_lds(prefill_mfma_kernel<D, QB, false>, C::LDS_BYTES);
-        if (st != VXL_OK) return st;
-        attr_done = true;
-    }
-    const int v = QB - 1;
-    const bool timed = g_ev_start && g_ev_stop;
-    if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_start, s));
-    const int group = d->n_q_heads / d->n_kv_heads;
-    const int xpg = (!(g_prefill_dbg & 2) && 8 % d->n_kv_heads == 0) ? 8 / d->n_kv_heads : 0;
-    const unsigned n_blocks = xpg ? 8u * (unsigned)((L->n_work[v] * group + xpg - 1) / xpg)
-                                  : (unsigned)L->n_work[v] * (unsigned)d->n_q_heads;
-    if (g_prof_buf) {
-        static bool attr2 = false;
-        if (!attr2) {
-            vxl_status st = enable_big_lds(prefill_mfma_kernel<D, QB, true>, C::LDS_BYTES);
-            if (st != VXL_OK) return st;
-            attr2 = true;
-        }
-        hipLaunchKernelGGL((prefill_mfma_kernel<D, QB, true>), dim3(n_blocks), dim3(256), C::LDS_BYTES, s,
-                           (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V, kctx, vctx, (uint16_t*)O,
-                           LSE, L->d_segs, L->d_work[v], L->n_tokens, d->n_q_heads, group, n_rows_pad, scale,
-                           L->n_work[v], xpg, g_prefill_dbg, g_prof_buf);
-    } else {
-        hipLaunchKernelGGL((prefill_mfma_kernel<D, QB, false>), dim3(n_blocks), dim3(256), C::LDS_BYTES, s,
-                           (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V, kctx, vctx, (uint16_t*)O,
-                           LSE, L->d_segs, L->d_work[v], L->n_tokens, d->n_q_heads, group, n_rows_pad, scale,
-                           L->n_work[v], xpg, g_prefill_dbg, (unsigned long long*)nullptr);
-    }
-    VXL_HIP_TRY(hipGetLastError());
-    if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_stop, s));
-    return VXL_OK;
 }
 
 template <int D, int NS, int NW = 8>
@@ -623,31 +356,20 @@ static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, f
         hipLaunchKernelGGL(reset_queue_kernel, dim3(1), dim3(64), 0, s, queue);
     }
     VXL_HIP_TRY(hipGetLastError());
-    static bool attr_done = false;
-    if (!attr_done) {
-        vxl_status st = enable_big_lds(prefill_dma_kernel<D, NS, false, NW>, C::LDS_BYTES);
-        if (st == VXL_OK) st = enable_big_lds(prefill_dma_kernel<D, NS, true, NW>, C::LDS_BYTES);
-        if (st != VXL_OK) return st;
-        attr_done = true;
-    }
-    static int n_cus = 0;                                     // one persistent workgroup per compute unit
-    if (n_cus == 0) {
-        int dev = 0;
-        VXL_HIP_TRY(hipGetDevice(&dev));
-        VXL_HIP_TRY(hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
-        if (n_cus < 8) n_cus = 8;
-    }
-    const bool timed = g_ev_start && g_ev_stop;
-    if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_start, s));
-    if (g_prefill_variant == 3) {
-        if (!dense_layout(d)) return VXL_ERR_UNSUPPORTED;
-        const vxl_status st = launch_prefill_pipe_main(L, d, scale, Q, K, V, kctx, vctx, O, LSE, queue, s);
-        if (st != VXL_OK) return st;
-        if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_stop, s));
-        return VXL_OK;
-    }
+    static PerDeviceOnce attr;
+    vxl_status st = attr.run([] {
+        const vxl_status a = enable_big_lds(prefill_dma_kernel<D, NS, false, NW>, C::LDS_BYTES);
+        return a != VXL_OK ? a : enable_big_lds(prefill_dma_kernel<D, NS, true, NW>, C::LDS_BYTES);
+    });
+    if (st != VXL_OK) return st;
+    int n_cus = 0;                                            // one persistent workgroup per compute unit
+    st = device_cu_count(&n_cus);
+    if (st != VXL_OK) return st;
+    hipEvent_t ev_start = g_ev_start, ev_stop = g_ev_stop;
+    const bool timed = ev_start && ev_stop;
+    if (timed) VXL_HIP_TRY(hipEventRecord(ev_start, s));
     const int group = d->n_q_heads / d->n_kv_heads;
-    const int xpg = (!(g_prefill_dbg & 2) && 8 % d->n_kv_heads == 0) ? 8 / d->n_kv_heads : 0;
+    const int xpg = 8 % d->n_kv_heads == 0 ? 8 / d->n_kv_heads : 0;
     constexpr int wl_i = NW == 8 ? 1 : 0;                     // the work list cut in bands of 32 * NW rows
     constexpr int per_cu = 8 / NW;                            // workgroups per compute unit
     const long long n_pairs = (long long)L->n_work[wl_i] * d->n_q_heads;
@@ -663,7 +385,7 @@ static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, f
     if (dense_layout(d)) VXL_LAUNCH(false); else VXL_LAUNCH(true);
 #undef VXL_LAUNCH
     VXL_HIP_TRY(hipGetLastError());
-    if (timed) VXL_HIP_TRY(hipEventRecord(g_ev_stop, s));
+    if (timed) VXL_HIP_TRY(hipEventRecord(ev_stop, s));
     return VXL_OK;
 }
 
@@ -702,19 +424,29 @@ extern "C" double vxl_debug_mfma_stream(float* out, int n_workgroups, int iters,
     return (double)n_workgroups * 8.0 * iters * 4.0 * 2.0 * 32 * 32 * 16;
 }
 
+vxl_status device_cu_count(int* n_cus) {
+    static std::mutex mu;
+    static int count[kMaxDevices] = {};
+    int dev = 0;
+    VXL_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return VXL_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (count[dev] == 0) {
+        int n = 0;
+        VXL_HIP_TRY(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+        count[dev] = n < 8 ? 8 : n;
+    }
+    *n_cus = count[dev];
+    return VXL_OK;
+}
+
 vxl_status launch_prefill_bf16(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Q,
                                const void* K, const void* V, void* O, float* LSE, void* ws, hipStream_t s) {
-    if (g_prefill_variant == 4)
+    if (g_prefill_variant == 1)
         return d->head_dim == 128 ? run_prefill_dma<128, 2, 4>(L, d, scale, Q, K, V, O, LSE, ws, s)
                                   : run_prefill_dma<64, 2, 4>(L, d, scale, Q, K, V, O, LSE, ws, s);
-    if (g_prefill_variant == 0 || g_prefill_variant == 3)
-        return d->head_dim == 128 ? run_prefill_dma<128, 4>(L, d, scale, Q, K, V, O, LSE, ws, s)
-                                  : run_prefill_dma<64, 4>(L, d, scale, Q, K, V, O, LSE, ws, s);
-    if (d->head_dim == 128)
-        return g_prefill_variant == 2 ? run_prefill<128, 2>(L, d, scale, Q, K, V, O, LSE, ws, s)
-                                      : run_prefill<128, 1>(L, d, scale, Q, K, V, O, LSE, ws, s);
-    return g_prefill_variant == 2 ? run_prefill<64, 2>(L, d, scale, Q, K, V, O, LSE, ws, s)
-                                  : run_prefill<64, 1>(L, d, scale, Q, K, V, O, LSE, ws, s);
+    return d->head_dim == 128 ? run_prefill_dma<128, 4>(L, d, scale, Q, K, V, O, LSE, ws, s)
+                              : run_prefill_dma<64, 4>(L, d, scale, Q, K, V, O, LSE, ws, s);
 }
 
 }  // namespace vxl

@@ -23,15 +23,21 @@ struct vxl_kv_store {
     bool strided = false;                  // the device K, V are not dense [Hkv, N, D]
     long long kv_head = 0, kv_tok = 0;     // their strides, in elements
     std::vector<int32_t> bounds, soff;
-    // pinned host memory (one allocation): dense K, dense V, sparse K, sparse V, mix_len staging
+    // pinned host memory (one allocation): dense K, dense V, sparse K, sparse V
     void* h_blob = nullptr;
     size_t blob_bytes = 0;
     char *h_k = nullptr, *h_v = nullptr, *h_ksp = nullptr, *h_vsp = nullptr;
-    int32_t* h_len = nullptr;
 };
 
 namespace {
-constexpr int kMaxReloadBatch = 256;     // entries of the pinned mix_len staging array
+// The mixed lengths reach the device as launch arguments of a one-block kernel: the values are
+// copied when the call is made, so reloads issued back to back (on one stream or on several) never
+// share a host staging buffer.
+constexpr int kMaxReloadBatch = 256;     // lengths per launch (1 KiB of kernel arguments)
+struct LenArgs { int32_t v[kMaxReloadBatch]; };
+__global__ void write_lens_kernel(int32_t* __restrict__ dst, LenArgs a, int n) {
+    if ((int)threadIdx.x < n) dst[threadIdx.x] = a.v[threadIdx.x];
+}
 }
 
 using namespace vxl;
@@ -47,7 +53,7 @@ vxl_status vxl_kv_store_create(const vxl_layout* L, const vxl_attn_desc* d, vxl_
         return VXL_ERR_UNSUPPORTED;
     if (!dense_layout(d) && (d->kv_stride_head <= 0 || d->kv_stride_tok < d->head_dim)) return VXL_ERR_INVALID_ARG;
     vxl_kv_store* S = new (std::nothrow) vxl_kv_store();
-    if (!S) return VXL_ERR_INVALID_ARG;
+    if (!S) return VXL_ERR_ALLOC;
     S->n_tokens = L->n_tokens; S->n_prefix = L->n_prefix; S->n_chunks = L->n_chunks; S->s_total = L->s_total;
     S->n_kv_heads = d->n_kv_heads; S->head_dim = d->head_dim;
     S->elem = d->dtype == VXL_BF16 ? 2 : 4;
@@ -57,19 +63,18 @@ vxl_status vxl_kv_store_create(const vxl_layout* L, const vxl_attn_desc* d, vxl_
     S->bounds = L->bounds; S->soff = L->soff;
     const size_t dense = align_up((size_t)S->n_kv_heads * S->n_tokens * S->head_dim * S->elem, 256);
     const size_t sparse = align_up((size_t)S->n_kv_heads * std::max(1, S->s_total) * S->head_dim * S->elem, 256);
-    S->blob_bytes = 2 * dense + 2 * sparse + align_up(kMaxReloadBatch * sizeof(int32_t), 256);
+    S->blob_bytes = 2 * dense + 2 * sparse;
     hipError_t e = hipHostMalloc(&S->h_blob, S->blob_bytes, hipHostMallocDefault);
     if (e != hipSuccess) {
         set_last_error("hipHostMalloc", e);
         delete S;
-        return VXL_ERR_HIP;
+        return e == hipErrorOutOfMemory ? VXL_ERR_ALLOC : VXL_ERR_HIP;
     }
     char* p = (char*)S->h_blob;
     S->h_k = p; p += dense;
     S->h_v = p; p += dense;
     S->h_ksp = p; p += sparse;
-    S->h_vsp = p; p += sparse;
-    S->h_len = (int32_t*)p;
+    S->h_vsp = p;
     *out = S;
     return VXL_OK;
 }
@@ -167,10 +172,10 @@ vxl_status vxl_kv_store_reload(vxl_kv_store* S, const uint8_t* dense_mask, int32
         if (mix_len_host) mix_len_host[b] = lens[b];
     }
     if (mix_len) {
-        // NOTE: the staging array is shared by the reloads of one store; a second reload must not be
-        // issued before the first one's copy of it has run (same stream, or an event in between)
-        memcpy(S->h_len, lens.data(), (size_t)batch * sizeof(int32_t));
-        VXL_HIP_TRY(hipMemcpyAsync(mix_len, S->h_len, (size_t)batch * sizeof(int32_t), hipMemcpyHostToDevice, s));
+        LenArgs a{};
+        std::copy(lens.begin(), lens.end(), a.v);
+        hipLaunchKernelGGL(write_lens_kernel, dim3(1), dim3(kMaxReloadBatch), 0, s, mix_len, a, (int)batch);
+        VXL_HIP_TRY(hipGetLastError());
     }
     return VXL_OK;
 }

@@ -14,7 +14,7 @@ import torch  # imported before the library so that both use the one HIP runtime
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libvxl.so")
 
-VXL_OK, VXL_ERR_INVALID_ARG, VXL_ERR_UNSUPPORTED, VXL_ERR_WORKSPACE, VXL_ERR_HIP = range(5)
+VXL_OK, VXL_ERR_INVALID_ARG, VXL_ERR_UNSUPPORTED, VXL_ERR_WORKSPACE, VXL_ERR_HIP, VXL_ERR_ALLOC = range(6)
 VXL_F32, VXL_BF16 = 0, 1
 OP_PREFILL, OP_SCORE_TOPK, OP_GATHER, OP_DECODE, OP_SCORE_MASS = range(5)
 MAX_CHUNKS = 4096
@@ -72,11 +72,11 @@ def lib() -> C.CDLL:
     L.vxl_chunk_score_topk_mass.restype = C.c_int
     L.vxl_chunk_score_topk_mass.argtypes = [vp, dp, vp, i32, i32, vp, i32, vp, vp, vp, vp, sz, vp]
     L.vxl_gather_bilevel_kv.restype = C.c_int
-    L.vxl_gather_bilevel_kv.argtypes = [vp, dp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, sz, vp]
+    L.vxl_gather_bilevel_kv.argtypes = [vp, dp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp]
     L.vxl_pool_sparse_kv.restype = C.c_int
     L.vxl_pool_sparse_kv.argtypes = [vp, dp, vp, vp, vp, vp, vp]
     L.vxl_gather_bilevel_kv_pooled.restype = C.c_int
-    L.vxl_gather_bilevel_kv_pooled.argtypes = [vp, dp, vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, sz, vp]
+    L.vxl_gather_bilevel_kv_pooled.argtypes = [vp, dp, vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp]
     L.vxl_kv_store_create.restype = C.c_int
     L.vxl_kv_store_create.argtypes = [vp, dp, C.POINTER(vp)]
     L.vxl_kv_store_destroy.restype = C.c_int
@@ -92,7 +92,6 @@ def lib() -> C.CDLL:
     L.vxl_debug_force_simple.argtypes = [C.c_int]
     L.vxl_debug_prefill_variant.argtypes = [C.c_int]
     L.vxl_debug_prefill_events.argtypes = [vp, vp]
-    L.vxl_debug_flags.argtypes = [C.c_int]
     L.vxl_debug_decode_step_waves.argtypes = [C.c_int]
     L.vxl_debug_mfma_stream.argtypes = [vp, C.c_int, C.c_int, vp]
     L.vxl_debug_mfma_stream.restype = C.c_double
@@ -221,12 +220,11 @@ def chunk_score_topk_mass(layout: Layout, desc: AttnDesc, qd, k, top_k: int, top
 
 
 def gather_bilevel_kv(layout: Layout, desc: AttnDesc, k, v, dense_mask, kmix, vmix, mix_len,
-                      src_idx=None, workspace=None, stream=None):
+                      src_idx=None, stream=None):
     """vxl_gather_bilevel_kv: kmix/vmix [B,Hkv,Lcap,D]; mix_len int32 [B]; src_idx int32 [B,Lcap]."""
     b, l_cap = int(kmix.shape[0]), int(kmix.shape[2])
     st = lib().vxl_gather_bilevel_kv(layout.handle, C.byref(desc), _ptr(k), _ptr(v), _ptr(dense_mask), b,
                                      _ptr(kmix), _ptr(vmix), l_cap, _ptr(mix_len), _ptr(src_idx),
-                                     _ptr(workspace), workspace.numel() if workspace is not None else 0,
                                      _stream(stream))
     _check(st, "vxl_gather_bilevel_kv")
 
@@ -239,13 +237,12 @@ def pool_sparse_kv(layout: Layout, desc: AttnDesc, k, v, ksp, vsp, stream=None):
 
 
 def gather_bilevel_kv_pooled(layout: Layout, desc: AttnDesc, k, v, ksp, vsp, dense_mask, kmix, vmix, mix_len,
-                             src_idx=None, workspace=None, stream=None):
+                             src_idx=None, stream=None):
     """vxl_gather_bilevel_kv_pooled: as gather_bilevel_kv, sparse rows taken from ksp/vsp."""
     b, l_cap = int(kmix.shape[0]), int(kmix.shape[2])
     st = lib().vxl_gather_bilevel_kv_pooled(layout.handle, C.byref(desc), _ptr(k), _ptr(v), _ptr(ksp), _ptr(vsp),
                                             _ptr(dense_mask), b, _ptr(kmix), _ptr(vmix), l_cap, _ptr(mix_len),
-                                            _ptr(src_idx), _ptr(workspace),
-                                            workspace.numel() if workspace is not None else 0, _stream(stream))
+                                            _ptr(src_idx), _stream(stream))
     _check(st, "vxl_gather_bilevel_kv_pooled")
 
 
@@ -316,9 +313,8 @@ def debug_decode_step_waves(waves: int) -> None:
 
 
 def debug_prefill_variant(variant: int) -> None:
-    """Cross-check and measurement only: 0 = the streaming kernel (default); 1, 2 = the 4-wave
-    register-staged kernel with one or two 32-row blocks per wave; 3 = the software-pipelined
-    4-wave kernel with 64 rows per wave."""
+    """Cross-check only: 0 = the default instance (8 waves, one workgroup per compute unit);
+    1 = the same kernel as two independent 4-wave workgroups per compute unit."""
     lib().vxl_debug_prefill_variant(int(variant))
 
 

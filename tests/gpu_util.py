@@ -6,10 +6,17 @@ import torch
 from paper_2506_19225_amd import vxl, workloads as wl
 
 # Matching rules: fp32 storage -- max abs error <= 1e-5; bf16 storage with fp32 accumulation --
-# max abs error <= 2e-2 and relative Frobenius error <= 1e-2, per query head.
+# max abs error <= 2e-2 and relative Frobenius error <= 1e-2, per query head.  With outputs of
+# magnitude 1e-3..1e-2 the absolute bound is vacuous and a head-wide Frobenius ratio averages
+# thousands of rows, so one row that lost a key tile would pass both; every output row (the D
+# values of one query token and head) is therefore bounded on its own as well:
+# ||row error|| <= 3e-2 * ||row||.  A correct row sits at 2e-3..6e-3 (one bf16 rounding of the
+# output, 2^-9 relative per element, plus the bf16 rounding of the softmax weights); a row that
+# misses a 64-key tile out of the few hundred to few thousand it attends to is off by >= 5e-2.
 TOL_F32_ABS = 1e-5
 TOL_BF16_ABS = 2e-2
 TOL_BF16_REL = 1e-2
+TOL_BF16_ROW = 3e-2
 
 
 def assert_close(got, want, dtype, head_axis=0, what=""):
@@ -26,6 +33,15 @@ def assert_close(got, want, dtype, head_axis=0, what=""):
     w = np.moveaxis(want, head_axis, 0).reshape(want.shape[head_axis], -1)
     rel = np.linalg.norm(g - w, axis=1) / np.maximum(np.linalg.norm(w, axis=1), 1e-30)
     assert rel.max() <= TOL_BF16_REL, f"{what}: rel Frobenius err {rel.max():.3e} (per head {rel})"
+    # per output row (last axis); rows whose norm is far below the typical one (cancellation) are
+    # measured against a floor of a twentieth of the median row norm
+    row_err = np.linalg.norm(got - want, axis=-1)
+    row_ref = np.linalg.norm(want, axis=-1)
+    floor = 0.05 * float(np.median(row_ref)) if row_ref.size else 0.0
+    ratio = row_err / np.maximum(np.maximum(row_ref, floor), 1e-30)
+    worst = np.unravel_index(int(np.argmax(ratio)), ratio.shape) if ratio.size else ()
+    assert ratio.size == 0 or ratio.max() <= TOL_BF16_ROW, \
+        f"{what}: worst row {worst} has ||err||/||row|| = {ratio.max():.3e} (bound {TOL_BF16_ROW})"
 
 
 def make_layout(lay: wl.Layout, window: int = 0) -> vxl.Layout:
@@ -76,8 +92,7 @@ def gpu_gather(w, lay, k, v, dense_mask, l_cap, gl=None, dev=None):
     vmix = torch.full_like(kmix, 7.0)
     mix_len = torch.full((bsz,), -1, dtype=torch.int32, device="cuda")
     src = torch.full((bsz, l_cap), -5, dtype=torch.int32, device="cuda")
-    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_GATHER, gl, desc, bsz))
-    vxl.gather_bilevel_kv(gl, desc, dk, dv, dm, kmix, vmix, mix_len, src, ws)
+    vxl.gather_bilevel_kv(gl, desc, dk, dv, dm, kmix, vmix, mix_len, src)
     torch.cuda.synchronize()
     return kmix, vmix, mix_len, src
 

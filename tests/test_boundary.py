@@ -12,10 +12,20 @@ from paper_2506_19225_amd import vxl
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "vxl.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(vxl_[a-z0-9_]+)\s*\(", text)))
+def declared_symbols(headers=("vxl.h", "vxl_debug.h")):
+    names = set()
+    for h in headers:
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(vxl_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
+
+
+def exported_symbols():
+    """Dynamic symbols of libvxl.so whose names start with vxl_ (the C ABI; C++ names are mangled)."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", vxl.LIB_PATH], capture_output=True, text=True, check=True)
+    return sorted({ln.split()[-1] for ln in out.stdout.splitlines() if ln.split() and ln.split()[-1].startswith("vxl_")})
 
 
 def test_library_exports_every_declared_symbol():
@@ -29,6 +39,27 @@ def test_library_exports_every_declared_symbol():
     assert lib.vxl_version() >= 100
     assert lib.vxl_status_string(0) == b"ok"
     assert b"workspace" in lib.vxl_status_string(vxl.VXL_ERR_WORKSPACE)
+    assert b"allocat" in lib.vxl_status_string(vxl.VXL_ERR_ALLOC)
+
+
+def test_library_exports_nothing_that_no_header_declares():
+    undeclared = set(exported_symbols()) - set(declared_symbols())
+    assert not undeclared, f"exported but declared in no header under include/: {sorted(undeclared)}"
+    debug = set(declared_symbols(("vxl_debug.h",)))
+    assert debug and all(n.startswith("vxl_debug_") for n in debug)
+    assert not any(n.startswith("vxl_debug_") for n in declared_symbols(("vxl.h",)))
+
+
+def test_failing_runtime_call_is_reported_as_hip_error():
+    """Without a GPU the first runtime call of vxl_layout_create (well-formed arguments) fails: the
+    call must return VXL_ERR_HIP, leave the handle null and keep the text of the failing call."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible: no runtime call fails here")
+    st, h = create(10, 2, [2, 6, 10], [0, 1, 2], [2, 6])
+    assert st == vxl.VXL_ERR_HIP and not h.value
+    assert len(vxl.lib().vxl_last_error()) > 0
+    assert b"HIP" in vxl.lib().vxl_status_string(st)
 
 
 def create(n_tokens, n_prefix, bounds, soff, sidx):

@@ -48,11 +48,11 @@ TINY_CASES = [
 
 
 @pytest.mark.parametrize("case", TINY_CASES, ids=lambda c: f"{c[0]}-h{c[1]}-d{c[3]}-p{c[4]}-s{c[8]}")
-@pytest.mark.parametrize("qb", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("qb", [0, 1])
 def test_prefill_ragged_layouts(case, qb):
     dtype, hq, hkv, d, p, nc, lo, hi, seed = case
     if dtype == "f32" and qb != 0:
-        pytest.skip("row-block count only applies to the matrix-core kernel")
+        pytest.skip("kernel instances only exist for the matrix-core path")
     rng = np.random.default_rng(seed)
     lay = wl.random_layout(rng, p, nc, lo, hi)
     w = wl.tiny_workload(dtype, hq, hkv, d, T=2, B=1, k=1, seed=seed)
@@ -86,7 +86,7 @@ def test_prefill_edge_layouts_bf16():
         assert_close(got, oracle_prefill(q, k, v, lay), "bf16", what="edge layout")
 
 
-@pytest.mark.parametrize("qb", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("qb", [0, 1])
 def test_prefill_medium_bf16_sharp_softmax(qb):
     """Several 256-token chunks at GQA 14/2, with logits of std ~3 so that the running maximum
     moves and the rescaling path is exercised."""
@@ -125,33 +125,28 @@ def test_prefill_matrix_core_kernel_agrees_with_vector_kernel_on_device():
     assert_close(b, want, "bf16", what="simple")
 
 
-def sample_rows(lay, rng, n_full_chunks=3):
-    """First/last row of every segment plus all rows of a few chunks (first, middle, last)."""
-    rows = set(range(min(lay.n_prefix, 4))) | ({lay.n_prefix - 1} if lay.n_prefix else set())
-    c_n = lay.n_chunks
-    for c in range(c_n):
-        rows.add(int(lay.chunk_bounds[c]))
-        rows.add(int(lay.chunk_bounds[c + 1]) - 1)
-    picks = sorted(set([0, 1, c_n // 2, c_n - 2, c_n - 1][:n_full_chunks + 2]) & set(range(c_n)))
-    for c in picks:
-        rows |= set(range(int(lay.chunk_bounds[c]), int(lay.chunk_bounds[c + 1])))
-    return np.array(sorted(rows), dtype=np.int64)
+_CONFIG1_ORACLE = {}
 
 
-@pytest.mark.parametrize("qb", [0, 1, 2, 3, 4])
-def test_prefill_config1_sampled_rows(qb):
-    w = wl.WORKLOADS["config1"]
-    lay = wl.make_layout(w)
-    q, k, v = wl.make_qkv(w, lay)
+def config1_oracle(window=0):
+    """config1 in full -- every row of every head -- from the oracle, computed once per window."""
+    if window not in _CONFIG1_ORACLE:
+        w = wl.WORKLOADS["config1"]
+        lay = wl.make_layout(w)
+        q, k, v = wl.make_qkv(w, lay)
+        _CONFIG1_ORACLE[window] = (w, lay, q, k, v, oracle_prefill(q, k, v, lay, window=window))
+    return _CONFIG1_ORACLE[window]
+
+
+@pytest.mark.parametrize("qb", [0, 1])
+def test_prefill_config1_all_rows(qb):
+    w, lay, q, k, v, want = config1_oracle()
     vxl.debug_prefill_variant(qb)
     try:
         got = gpu_prefill(w, lay, q, k, v)
     finally:
         vxl.debug_prefill_variant(0)
-    rows = sample_rows(lay, np.random.default_rng(0))
-    want = oracle_prefill(q, k, v, lay, rows=rows)
-    assert_close(got[:, rows], want, "bf16", what="config1 prefill")
-    assert np.isfinite(got).all()
+    assert_close(got, want, "bf16", what="config1 prefill, all rows")
 
 
 def test_prefill_locality_and_determinism_bit_exact():
@@ -187,7 +182,7 @@ WINDOW_CASES = [
 
 
 @pytest.mark.parametrize("case", WINDOW_CASES, ids=lambda c: f"{c[0]}-d{c[3]}-p{c[4]}-w{c[8]}")
-@pytest.mark.parametrize("qb", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("qb", [0, 1])
 def test_prefill_sliding_window(case, qb):
     dtype, hq, hkv, d, p, nc, lo, hi, window, seed = case
     if dtype == "f32" and qb != 0:
@@ -216,15 +211,11 @@ def test_prefill_sliding_window(case, qb):
         assert_close(alt, want, dtype, what=f"windowed prefill, vector kernel {case}")
 
 
-def test_prefill_window_config1_sampled_rows():
-    """config1 with a look-back of one frame group (64 tokens): full size, sampled rows."""
-    w = wl.WORKLOADS["config1"]
-    lay = wl.make_layout(w)
-    q, k, v = wl.make_qkv(w, lay)
+def test_prefill_window_config1_all_rows():
+    """config1 with a look-back of one frame group (64 tokens): full size, every row."""
+    w, lay, q, k, v, want = config1_oracle(window=64)
     got = gpu_prefill(w, lay, q, k, v, gl=make_layout(lay, window=64))
-    rows = sample_rows(lay, np.random.default_rng(0))
-    want = oracle_prefill(q, k, v, lay, rows=rows, window=64)
-    assert_close(got[:, rows], want, "bf16", what="config1 windowed prefill")
+    assert_close(got, want, "bf16", what="config1 windowed prefill, all rows")
 
 
 def test_prefill_two_workgroups_per_unit_instance_is_reproducible():
@@ -236,7 +227,7 @@ def test_prefill_two_workgroups_per_unit_instance_is_reproducible():
     q, k, v = wl.make_qkv(w, lay)
     gl = make_layout(lay, window=64)
     ref = gpu_prefill(w, lay, q, k, v, gl=gl)
-    vxl.debug_prefill_variant(4)
+    vxl.debug_prefill_variant(1)
     try:
         runs = [gpu_prefill(w, lay, q, k, v, gl=gl) for _ in range(3)]
     finally:
@@ -246,6 +237,24 @@ def test_prefill_two_workgroups_per_unit_instance_is_reproducible():
 
 
 # --------------------------------------------------------------------------------- score / top-k
+def check_topk_order(idx, want_idx, scores, want_s, tol=None):
+    """topk_idx lists the selected chunks best first.  Position i must hold the oracle's chunk
+    wherever that chunk's float64 score is separated from both neighbours in the oracle's order
+    by more than twice the score tolerance (closer than that, fp32 scores may order them either
+    way); and the device's order is always the (score descending, id ascending) order of the
+    device's own scores."""
+    tol = (2e-5 * np.abs(want_s).max() + 1e-7) if tol is None else tol
+    for b in range(idx.shape[0]):
+        key = [(-scores[b, c], c) for c in idx[b]]
+        assert key == sorted(key)
+        sw = want_s[b, want_idx[b]]
+        for i in range(idx.shape[1]):
+            left_ok = i == 0 or sw[i - 1] - sw[i] > 2 * tol
+            right_ok = i + 1 == idx.shape[1] or sw[i] - sw[i + 1] > 2 * tol
+            if left_ok and right_ok:
+                assert idx[b, i] == want_idx[b, i], (b, i, idx[b], want_idx[b])
+
+
 def check_topk(w, lay, qd, k, top_k):
     idx, mask, scores = gpu_score_topk(w, lay, qd, k, top_k)
     want_s = oracle.chunk_scores(qd, k, lay.chunk_bounds)
@@ -259,10 +268,7 @@ def check_topk(w, lay, qd, k, top_k):
         assert margin > 1e-6 * np.abs(want_s).max(), "degenerate seed: rank-k margin too small"
     assert np.array_equal(mask, want_mask)
     assert np.array_equal(np.sort(idx, axis=1), np.sort(want_idx, axis=1))
-    # the device's own order is consistent with its own scores (descending, ties by id)
-    for b in range(idx.shape[0]):
-        key = [(-scores[b, c], c) for c in idx[b]]
-        assert key == sorted(key)
+    check_topk_order(idx, want_idx, scores, want_s)
     return idx, mask
 
 
@@ -333,7 +339,59 @@ def test_gather_bit_exact():
     check_gather(w, lay, k, v, masks, lay.n_tokens + 11)
 
 
+def test_gather_overflow_is_reported_not_truncated():
+    """A mask that selects more rows than the mixed buffers hold: mix_len = -(rows needed), no row
+    of that query is written (Kmix, Vmix, src_idx keep their sentinels); the other queries of the
+    call are gathered as usual; decode reads the negative length as an empty set."""
+    rng = np.random.default_rng(63)
+    w = wl.tiny_workload("bf16", 4, 2, 128, T=2, B=3, k=1, seed=63)
+    lay = wl.random_layout(rng, 6, 9, 20, 60)
+    _, k, v = wl.make_qkv(w, lay, with_q=False)
+    gl = make_layout(lay)
+    l_cap = gl.mixed_kv_capacity(1)                       # room for one dense chunk
+    masks = np.zeros((3, lay.n_chunks), np.uint8)
+    masks[0, int(np.argmax(np.diff(lay.chunk_bounds)))] = 1        # fits exactly or with room
+    masks[1, :] = 1                                        # every chunk dense: does not fit
+    kmix, vmix, mix_len, src = gpu_gather(w, lay, k, v, masks, l_cap, gl=gl)
+    _, _, wlen, wsrc = oracle.gather_bilevel(k, v, masks[[0, 2]], *lay_args(lay))
+    lens = mix_len.cpu().numpy()
+    assert lay.n_tokens > l_cap
+    assert list(lens) == [wlen[0], -lay.n_tokens, wlen[1]]
+    hk, hv, hsrc = vxl.to_host(kmix), vxl.to_host(vmix), src.cpu().numpy()
+    assert (hk[1] == 7.0).all() and (hv[1] == 7.0).all() and (hsrc[1] == -5).all()
+    for b, ob in ((0, 0), (2, 1)):
+        n = wlen[ob]
+        assert np.array_equal(hsrc[b, :n], wsrc[ob, :n]) and (hsrc[b, n:] == -5).all()
+        assert np.array_equal(hk[b, :, :n], k[:, wsrc[ob, :n]])
+    qd = wl.make_decode_queries(w)
+    got, lse = gpu_decode(w, qd, kmix, vmix, mix_len, want_lse=True)
+    assert (got[1] == 0).all() and np.isneginf(lse[1]).all()
+    wk, wv, _, _ = oracle.gather_bilevel(k, v, masks[[0, 2]], *lay_args(lay), l_cap=l_cap)
+    want = oracle.decode_mixed(qd[[0, 2]], wk, wv, wlen)
+    assert_close(got[[0, 2]], want, "bf16", head_axis=2, what="decode beside an overflowed query")
+
+
 # --------------------------------------------------------------------------------- decode
+@pytest.mark.parametrize("dtype,t_q", [("f32", 2), ("bf16", 1), ("bf16", 8), ("bf16", 40)])
+def test_decode_empty_mixed_set(dtype, t_q):
+    """mix_len = 0 (no prefix, nothing kept, nothing dense) beside a non-empty query: the empty
+    one gives O = 0 and LSE = -inf on every decode kernel, the other is unaffected."""
+    rng = np.random.default_rng(70 + t_q)
+    d, hq, hkv, l_cap = 128, 14, 2, 300
+    w = wl.tiny_workload(dtype, hq, hkv, d, T=t_q, B=2, k=1, seed=70 + t_q)
+    rnd = lambda *shape: (rng.standard_normal(shape).astype(np.float32) * np.float32(0.5))
+    kmix, vmix, qd = rnd(2, hkv, l_cap, d), rnd(2, hkv, l_cap, d), rnd(2, t_q, hq, d)
+    if dtype == "bf16":
+        kmix, vmix, qd = (wl.round_to_bf16(x) for x in (kmix, vmix, qd))
+    mix_len = np.array([0, 217], dtype=np.int32)
+    got, lse = gpu_decode(w, qd, vxl.to_device(kmix, dtype), vxl.to_device(vmix, dtype),
+                          torch.from_numpy(mix_len).cuda(), want_lse=True)
+    assert (got[0] == 0).all() and np.isneginf(lse[0]).all()
+    want, wlse = oracle.decode_lse(qd[1:], kmix[1:], vmix[1:], mix_len[1:])
+    assert_close(got[1:], want, dtype, head_axis=2, what=f"decode beside an empty set T={t_q}")
+    assert np.abs(lse[1:] - wlse).max() < (1e-4 if dtype == "f32" else 2e-2)
+
+
 def test_decode_config0_fp32_and_tiny_bf16():
     rng = np.random.default_rng(71)
     w = wl.WORKLOADS["config0"]
@@ -377,10 +435,9 @@ def run_bilevel_chain(w, lay, k, v, qd, top_k):
     mix_len = torch.zeros((bsz,), dtype=torch.int32, device="cuda")
     out = torch.zeros_like(dqd)
     ws1 = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_SCORE_TOPK, gl, desc, bsz, t))
-    ws2 = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_GATHER, gl, desc, bsz))
     ws3 = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_DECODE, None, desc, bsz, t, l_cap))
     vxl.chunk_score_topk(gl, desc, dqd, dk, top_k, idx, mask, workspace=ws1)
-    vxl.gather_bilevel_kv(gl, desc, dk, dv, mask, kmix, vmix, mix_len, None, ws2)
+    vxl.gather_bilevel_kv(gl, desc, dk, dv, mask, kmix, vmix, mix_len)
     vxl.bilevel_decode(desc, dqd, kmix, vmix, mix_len, out, None, ws3)
     torch.cuda.synchronize()
     return vxl.to_host(out), mask.cpu().numpy(), mix_len.cpu().numpy(), l_cap
@@ -427,8 +484,8 @@ def _whole_path(w, lay, gl, desc, dq, dk, dv, dqd, bufs):
     out, idx, mask, kmix, vmix, mix_len, od, ws = bufs
     vxl.chunk_prefill(gl, desc, dq, dk, dv, out, None, ws[0])
     vxl.chunk_score_topk(gl, desc, dqd, dk, w.k, idx, mask, workspace=ws[1])
-    vxl.gather_bilevel_kv(gl, desc, dk, dv, mask, kmix, vmix, mix_len, None, ws[2])
-    vxl.bilevel_decode(desc, dqd, kmix, vmix, mix_len, od, None, ws[3])
+    vxl.gather_bilevel_kv(gl, desc, dk, dv, mask, kmix, vmix, mix_len)
+    vxl.bilevel_decode(desc, dqd, kmix, vmix, mix_len, od, None, ws[2])
 
 
 def test_whole_path_on_a_side_stream_and_in_a_replayed_graph():
@@ -456,7 +513,6 @@ def test_whole_path_on_a_side_stream_and_in_a_replayed_graph():
                 torch.full_like(dqd, float("nan")),
                 [vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_PREFILL, gl, desc)),
                  vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_SCORE_TOPK, gl, desc, w.B, w.T)),
-                 vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_GATHER, gl, desc, w.B)),
                  vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_DECODE, None, desc, w.B, w.T, l_cap))])
 
     eager = buffers()

@@ -83,8 +83,7 @@ def test_pooled_chain(name):
     vmix = torch.full_like(kmix, 7.0)
     mix_len = torch.full((bsz,), -1, dtype=torch.int32, device="cuda")
     src = torch.full((bsz, l_cap), -5, dtype=torch.int32, device="cuda")
-    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_GATHER, gl, desc, bsz))
-    vxl.gather_bilevel_kv_pooled(gl, desc, dk, dv, ksp, vsp, dm, kmix, vmix, mix_len, src, ws)
+    vxl.gather_bilevel_kv_pooled(gl, desc, dk, dv, ksp, vsp, dm, kmix, vmix, mix_len, src)
     torch.cuda.synchronize()
     # oracle structure (lengths, source codes) -- pooled values taken from the oracle's own pooling
     ok, ov = oracle.pool_sparse_kv(k, v, lay.chunk_bounds, lay.sparse_offsets)
@@ -123,8 +122,7 @@ def test_pooled_gather_without_sparse_rows_and_all_dense():
     kmix = torch.zeros((1, 2, l_cap, 128), dtype=dk.dtype, device="cuda")
     vmix = torch.zeros_like(kmix)
     mix_len = torch.zeros((1,), dtype=torch.int32, device="cuda")
-    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_GATHER, gl, desc, 1))
-    vxl.gather_bilevel_kv_pooled(gl, desc, dk, dv, None, None, dm, kmix, vmix, mix_len, None, ws)
+    vxl.gather_bilevel_kv_pooled(gl, desc, dk, dv, None, None, dm, kmix, vmix, mix_len, None)
     torch.cuda.synchronize()
     assert int(mix_len[0]) == 44
     assert np.array_equal(vxl.to_host(kmix)[0, :, :44], k[:, :44])

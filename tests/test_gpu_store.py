@@ -133,3 +133,38 @@ def test_reload_on_a_side_stream_beside_a_decode():
                                                 lay.sparse_offsets, lay.sparse_idx, l_cap=l_cap)
         want = oracle.decode_mixed(qd, wk, wv, wlen)
         assert_close(vxl.to_host(out), want, w.dtype, head_axis=2, what=f"decode of query {b} after reload")
+
+
+def test_two_reloads_back_to_back_keep_their_own_lengths():
+    """Two reloads of one store with different selections, issued one after the other on one stream
+    without a synchronisation in between, and a third on a side stream: every device mix_len holds
+    the lengths of its own reload (the lengths travel as launch arguments, not through a staging
+    buffer that the next call could overwrite)."""
+    w = wl.WORKLOADS["config1"]
+    lay = wl.make_layout(w)
+    _, k, v = wl.make_qkv(w, lay, with_q=False)
+    c_n = lay.n_chunks
+    m_a = np.zeros((2, c_n), dtype=np.uint8)
+    m_a[0, :3] = 1
+    m_a[1, :1] = 1
+    m_b = np.zeros((2, c_n), dtype=np.uint8)
+    m_b[0, :8] = 1
+    m_c = np.zeros((2, c_n), dtype=np.uint8)
+    m_c[:, :5] = 1
+    store, gl, desc, _, _, _ = reload_and_check(w, lay, k, v, m_a)
+    l_cap = gl.mixed_kv_capacity(8)
+    bufs = [(torch.zeros((2, w.n_kv_heads, l_cap, w.head_dim), dtype=torch.bfloat16, device="cuda"),
+             torch.zeros((2, w.n_kv_heads, l_cap, w.head_dim), dtype=torch.bfloat16, device="cuda"),
+             torch.full((2,), -1, dtype=torch.int32, device="cuda")) for _ in range(3)]
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    la = store.reload(m_a, *bufs[0])
+    lb = store.reload(m_b, *bufs[1])
+    with torch.cuda.stream(side):
+        lc = store.reload(m_c, *bufs[2], stream=side)
+    torch.cuda.synchronize()
+    for masks, lens, (_, _, dev_len) in ((m_a, la, bufs[0]), (m_b, lb, bufs[1]), (m_c, lc, bufs[2])):
+        _, _, wlen, _ = oracle.gather_bilevel(k[:, :, :1], v[:, :, :1], masks, lay.n_prefix, lay.chunk_bounds,
+                                              lay.sparse_offsets, lay.sparse_idx)
+        assert np.array_equal(lens, wlen) and np.array_equal(dev_len.cpu().numpy(), wlen)
+    assert not np.array_equal(la, lb)

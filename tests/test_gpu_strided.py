@@ -99,11 +99,10 @@ def test_scores_gather_pool_store_token_major(case):
             vmix = torch.full_like(kmix, 7.0)
             mix_len = torch.full((bsz,), -1, dtype=torch.int32, device="cuda")
             src = torch.full((bsz, l_cap), -5, dtype=torch.int32, device="cuda")
-            ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_GATHER, gl, desc, bsz))
             if pooled:
-                vxl.gather_bilevel_kv_pooled(gl, desc, kdev, vdev, ksp, vsp, mask, kmix, vmix, mix_len, src, ws)
+                vxl.gather_bilevel_kv_pooled(gl, desc, kdev, vdev, ksp, vsp, mask, kmix, vmix, mix_len, src)
             else:
-                vxl.gather_bilevel_kv(gl, desc, kdev, vdev, mask, kmix, vmix, mix_len, src, ws)
+                vxl.gather_bilevel_kv(gl, desc, kdev, vdev, mask, kmix, vmix, mix_len, src)
             out += [kmix, vmix, mix_len, src]
         torch.cuda.synchronize()
         return [ksp, vsp] + out
