@@ -257,6 +257,29 @@ vxl_status vxl_bilevel_decode(const vxl_attn_desc* desc, const void* Qd, int32_t
                               void* workspace, size_t workspace_bytes, vxl_stream stream);
 
 /*
+ * vxl_bilevel_decode for callers that cannot allocate device memory or carry a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels and bit-for-bit the same results as vxl_bilevel_decode, without the workspace pair:
+ * the split-KV partial results go to an array of VXL_STATIC_SCRATCH_BYTES bytes that the library
+ * holds in device memory (one per GPU it runs on, from the first call on that GPU until the
+ * process ends).  The call allocates nothing and frees nothing; its first call on a device looks
+ * up the array's address and sets kernel attributes.
+ *   - A call whose partial results need more than VXL_STATIC_SCRATCH_BYTES (what
+ *     vxl_workspace_bytes(VXL_OP_DECODE, ...) reports for the same arguments) is rejected with
+ *     VXL_ERR_WORKSPACE before anything is launched; vxl_last_error says how much it needed.
+ *   - Every call on a GPU shares that GPU's array: calls that may overlap (different streams,
+ *     different threads) race on it; order them on one stream or use vxl_bilevel_decode with
+ *     separate workspaces.  Nothing in the array has to start at zero (each call writes every
+ *     value it later reads), so it is not cleared between calls.
+ * Other errors as vxl_bilevel_decode.
+ */
+#define VXL_STATIC_SCRATCH_BYTES (32u << 20)
+vxl_status vxl_bilevel_decode_static(const vxl_attn_desc* desc, const void* Qd, int32_t batch,
+                                     int32_t n_q_tokens, const void* Kmix, const void* Vmix,
+                                     int32_t l_cap, const int32_t* mix_len, void* O, float* LSE,
+                                     vxl_stream stream);
+
+/*
  * Offline (host-memory) bi-level KV store of one layer ("Bi-level KVs Decoding": both the dense
  * and the sparse KVs are stored in an offline memory and selectively reloaded for a query).
  * The store owns pinned host copies of the dense K/V [n_kv_heads, n_tokens, head_dim] and of the

@@ -489,4 +489,31 @@ vxl_status vxl_bilevel_decode(const vxl_attn_desc* d, const void* Qd, int32_t ba
                                 (hipStream_t)stream);
 }
 
+vxl_status vxl_bilevel_decode_static(const vxl_attn_desc* d, const void* Qd, int32_t batch,
+                                     int32_t n_q_tokens, const void* Kmix, const void* Vmix, int32_t l_cap,
+                                     const int32_t* mix_len, void* O, float* LSE, vxl_stream stream) {
+    vxl_status st;
+    if (!desc_ok(d, &st)) return st;
+    if (!Qd || !Kmix || !Vmix || !mix_len || !O || batch <= 0 || n_q_tokens <= 0 || l_cap <= 0)
+        return VXL_ERR_INVALID_ARG;
+    if (!aligned16(Qd) || !aligned16(Kmix) || !aligned16(Vmix) || !aligned16(O)) return VXL_ERR_INVALID_ARG;
+    const float scale = resolve_scale(d);
+    if (d->dtype == VXL_BF16 && !g_force_simple) {
+        const size_t need = decode_plan(d, batch, n_q_tokens, l_cap).total;
+        if (need > (size_t)VXL_STATIC_SCRATCH_BYTES) {
+            snprintf(g_last_error, sizeof(g_last_error),
+                     "vxl_bilevel_decode_static: the split-KV partial results of this call need %zu bytes, the "
+                     "static scratch holds %zu", need, (size_t)VXL_STATIC_SCRATCH_BYTES);
+            return VXL_ERR_WORKSPACE;
+        }
+        void* ws = nullptr;
+        st = decode_static_scratch(&ws);
+        if (st != VXL_OK) return st;
+        return launch_decode_bf16(d, scale, Qd, batch, n_q_tokens, Kmix, Vmix, l_cap, mix_len, O, LSE, ws,
+                                  (hipStream_t)stream);
+    }
+    return launch_decode_simple(d, scale, Qd, batch, n_q_tokens, Kmix, Vmix, l_cap, mix_len, O, LSE,
+                                (hipStream_t)stream);
+}
+
 }  // extern "C"

@@ -647,6 +647,28 @@ static vxl_status run_decode_wave(const vxl_attn_desc* d, float scale, const voi
     return VXL_OK;
 }
 
+// Scratch of the entry point that allocates nothing: one array per device, held until the process
+// ends.  In host code the name below is only a stand-in for the symbol; the device address is
+// asked for once per device (with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[VXL_STATIC_SCRATCH_BYTES];
+
+vxl_status decode_static_scratch(void** ptr) {
+    static std::mutex mu;
+    static void* addr[kMaxDevices] = {};
+    int dev = 0;
+    VXL_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return VXL_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void* p = nullptr;
+        VXL_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return VXL_ERR_HIP;
+        addr[dev] = p;
+    }
+    *ptr = addr[dev];
+    return VXL_OK;
+}
+
 vxl_status launch_decode_bf16(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
                               const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len, void* O,
                               float* LSE, void* ws, hipStream_t s) {

@@ -181,6 +181,8 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap);
 vxl_status launch_decode_bf16(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
                               const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len,
                               void* O, float* LSE, void* ws, hipStream_t s);
+// device address of this device's static decode scratch (VXL_STATIC_SCRATCH_BYTES bytes)
+vxl_status decode_static_scratch(void** ptr);
 vxl_status launch_decode_simple(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
                                 const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len,
                                 void* O, float* LSE, hipStream_t s);

@@ -89,6 +89,8 @@ def lib() -> C.CDLL:
     L.vxl_kv_store_reload.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp]
     L.vxl_bilevel_decode.restype = C.c_int
     L.vxl_bilevel_decode.argtypes = [dp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.vxl_bilevel_decode_static.restype = C.c_int
+    L.vxl_bilevel_decode_static.argtypes = [dp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp]
     L.vxl_debug_force_simple.argtypes = [C.c_int]
     L.vxl_debug_prefill_variant.argtypes = [C.c_int]
     L.vxl_debug_prefill_events.argtypes = [vp, vp]
@@ -254,6 +256,19 @@ def bilevel_decode(desc: AttnDesc, qd, kmix, vmix, mix_len, out, lse=None, works
                                   _ptr(mix_len), _ptr(out), _ptr(lse), _ptr(workspace),
                                   workspace.numel() if workspace is not None else 0, _stream(stream))
     _check(st, "vxl_bilevel_decode")
+    return out
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def bilevel_decode_static(desc: AttnDesc, qd, kmix, vmix, mix_len, out, lse=None, stream=None):
+    """vxl_bilevel_decode_static: vxl_bilevel_decode without a workspace (the library's static scratch)."""
+    b, t = int(qd.shape[0]), int(qd.shape[1])
+    l_cap = int(kmix.shape[2])
+    st = lib().vxl_bilevel_decode_static(C.byref(desc), _ptr(qd), b, t, _ptr(kmix), _ptr(vmix), l_cap,
+                                         _ptr(mix_len), _ptr(out), _ptr(lse), _stream(stream))
+    _check(st, "vxl_bilevel_decode_static")
     return out
 
 
