@@ -1,22 +1,29 @@
 #!/usr/bin/env python3
 """Benchmark of the whole hot path on one MI355X.
 
-One step = one pass of all hot-path calls over one batch of synthetic input (workload
-"config1": one 7B-class GQA layer, 256 prefix + 16,384 visual tokens in 64 chunks):
-    vxl_chunk_prefill -> vxl_chunk_score_topk (per-chunk mean keys recomputed) ->
-    vxl_gather_bilevel_kv -> vxl_bilevel_decode (the T query tokens in one call).
+Default workload: "config3", the 28-layer stack of 7B-class GQA attention over 10,240 frames
+(256 prefix + 163,840 visual tokens in 640 chunks), the largest configuration that one GPU holds.
+The K and V of all 28 layers (9.4 GB) and their Q and O stay resident in HBM.  One step = one
+pass of the whole hot path over that input:
+    28 x vxl_chunk_prefill (one call per layer)
+    vxl_chunk_score_topk at layer 0 (per-chunk mean keys recomputed; the selection is reused)
+    28 x (vxl_gather_bilevel_kv -> vxl_bilevel_decode, the T query tokens in one call).
+`--workload config1|config2|config4` runs the single-layer workloads the same way (one layer).
 Inputs are resident in HBM before the timed region.  `value` = effective pre-filling FLOPs
-(4 * D * Hq * allowed pairs) divided by the time of the WHOLE step.  The roofline object is for
-the dominant kernel (the matrix-core pre-filling kernel), timed with events recorded around it
-on the launch stream.  After the timed region the script also measures, separately, the
-bandwidth-bound calls (gather; decode in step mode T=1 and batched) on buffers rotated through
-more than the on-package cache, and times the CPU oracle on a bounded sample.
+(4 * D * Hq * allowed pairs, all layers) divided by the time of the WHOLE step.  The roofline
+object is for the dominant kernel (the matrix-core pre-filling kernel), timed live with events
+recorded around every launch of it on the launch stream.  After the timed region the script also
+measures, separately, the bandwidth-bound calls (gather; decode in step mode T=1 and batched) on
+buffers rotated through more than the on-package cache, the 28-layer decode step over the 28
+resident mixed KV sets, short pre-filling runs of the other workloads, and the CPU oracle on a
+bounded sample.
 
 Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -35,12 +42,12 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="config1", choices=["config1", "config2", "config4"])
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="config3", choices=["config1", "config2", "config3", "config4"])
+    ap.add_argument("--layers", type=int, default=0, help="config3 only: run this many of its 28 layers (0 = all)")
     ap.add_argument("--prefill-variant", type=int, default=0,
-                    help="debug: 1 or 2 = the 4-wave register-staged kernel with 1 or 2 row blocks per wave, "
-                         "3 = the software-pipelined 4-wave kernel with 64 rows per wave")
+                    help="cross-check: 1 = the pre-filling kernel as two 4-wave workgroups per compute unit")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the separate gather/decode measurements")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -49,15 +56,38 @@ def parse():
     return ap.parse_args()
 
 
+def kernel_source_hash():
+    """Hash of the sources the pre-filling kernel is built from; a stored HBM-traffic figure is
+    only reported while it was measured on these very sources."""
+    h = hashlib.sha256()
+    for f in ("vxl_prefill.hip", "vxl_mfma.h", "vxl_internal.h"):
+        h.update(open(os.path.join(ROOT, "paper_2506_19225_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def stored_traffic(workload, kernel_name):
+    """HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc runs summarised under
+    profiles/ (counters cannot be read inside this process), or None when no figure exists for
+    this workload or the kernel sources have changed since it was taken."""
+    try:
+        rec = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
+        ent = rec.get(workload, {}).get(kernel_name)
+        if isinstance(ent, dict) and ent.get("source_hash") == kernel_source_hash():
+            return float(ent["bytes_per_launch"])
+    except Exception:
+        pass
+    return None
+
+
 def cpu_baseline(w, lay, q, k, v):
-    """The float64 oracle, as it stands, on a bounded sample of the same workload."""
+    """The float64 oracle, as it stands, on a bounded sample of the same workload (one layer)."""
     import oracle
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    # sample: all rows of chunks {0, C/2, C-1}, every query head; grown until ~10 s are spent
+    # sample: all rows of chunks {0, C/2, C-1}, every query head; grown until ~12 s are spent
     c_n = lay.n_chunks
     order = [0, c_n // 2, c_n - 1] + [int(c) for c in np.random.default_rng(0).permutation(c_n)]
     pairs_done, t_spent, used = 0, 0.0, []
@@ -76,9 +106,25 @@ def cpu_baseline(w, lay, q, k, v):
             break
     flops = 4.0 * w.head_dim * w.n_q_heads * pairs_done
     return {"value": flops / t_spent / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"oracle.prefill_blk on all rows of {len(used)} of {c_n} chunks (first, middle, last, then a "
-                      f"seeded permutation) x all {w.n_q_heads} query heads: {pairs_done} allowed pairs in "
-                      f"{t_spent:.1f} s"}
+            "sample": f"oracle.prefill_blk on all rows of {len(used)} of {c_n} chunks of layer 0 (first, middle, "
+                      f"last, then a seeded permutation) x all {w.n_q_heads} query heads: {pairs_done} allowed "
+                      f"pairs in {t_spent:.1f} s"}
+
+
+def make_inputs(torch, vxl, wl, w, lay, n_layers):
+    """Device-resident Q, K, V and decode queries of every layer.  config3 is drawn on the device
+    (21 G elements); the single-layer workloads on the host, as the parity tests draw them."""
+    qs, ks, vs, qds = [], [], [], []
+    for layer in range(n_layers):
+        if w.name == "config3":
+            q, k, v = wl.make_qkv_device(w, lay, layer)
+            qd = wl.make_decode_queries_device(w, layer)
+        else:
+            hq, hk, hv = wl.make_qkv(w, lay, layer)
+            q, k, v = (vxl.to_device(x, w.dtype) for x in (hq, hk, hv))
+            qd = vxl.to_device(wl.make_decode_queries(w, layer), w.dtype)
+        qs.append(q); ks.append(k); vs.append(v); qds.append(qd)
+    return qs, ks, vs, qds
 
 
 def main():
@@ -100,31 +146,35 @@ def main():
 
     w = wl.WORKLOADS[args.workload]
     lay = wl.make_layout(w)
-    q, k, v = wl.make_qkv(w, lay)
-    qd = wl.make_decode_queries(w)
+    n_layers = w.n_layers if not args.layers else min(args.layers, w.n_layers)
     gl = vxl.Layout(lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx)
     desc = vxl.make_desc(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
-    dq, dk, dv, dqd = (vxl.to_device(x, w.dtype) for x in (q, k, v, qd))
+    dqs, dks, dvs, dqds = make_inputs(torch, vxl, wl, w, lay, n_layers)
     B, T, C, D, Hq, Hkv = w.B, w.T, lay.n_chunks, w.head_dim, w.n_q_heads, w.n_kv_heads
     top_k = w.k
     l_cap = gl.mixed_kv_capacity(top_k)
 
-    out = torch.empty_like(dq)
+    outs = [torch.empty_like(q) for q in dqs]
     ws_pre = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_PREFILL, gl, desc))
     ws_sc = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_SCORE_TOPK, gl, desc, B, T))
     ws_de = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_DECODE, None, desc, B, T, l_cap))
     idx = torch.zeros((B, min(top_k, C)), dtype=torch.int32, device="cuda")
     mask = torch.zeros((B, C), dtype=torch.uint8, device="cuda")
-    kmix = torch.zeros((B, Hkv, l_cap, D), dtype=dk.dtype, device="cuda")
-    vmix = torch.zeros_like(kmix)
-    mix_len = torch.zeros((B,), dtype=torch.int32, device="cuda")
-    od = torch.empty_like(dqd)
+    kmixes = [torch.zeros((B, Hkv, l_cap, D), dtype=dks[0].dtype, device="cuda") for _ in range(n_layers)]
+    vmixes = [torch.zeros_like(kmixes[0]) for _ in range(n_layers)]
+    mix_lens = [torch.zeros((B,), dtype=torch.int32, device="cuda") for _ in range(n_layers)]
+    ods = [torch.empty_like(qd) for qd in dqds]
 
-    def step():
-        vxl.chunk_prefill(gl, desc, dq, dk, dv, out, None, ws_pre)
-        vxl.chunk_score_topk(gl, desc, dqd, dk, top_k, idx, mask, workspace=ws_sc)
-        vxl.gather_bilevel_kv(gl, desc, dk, dv, mask, kmix, vmix, mix_len)
-        vxl.bilevel_decode(desc, dqd, kmix, vmix, mix_len, od, None, ws_de)
+    def step(events=None):
+        for l in range(n_layers):
+            if events is not None:
+                vxl.debug_prefill_events(*events[l])
+            vxl.chunk_prefill(gl, desc, dqs[l], dks[l], dvs[l], outs[l], None, ws_pre)
+        # the dense chunks are selected at layer 0 and the selection is reused by every layer
+        vxl.chunk_score_topk(gl, desc, dqds[0], dks[0], top_k, idx, mask, workspace=ws_sc)
+        for l in range(n_layers):
+            vxl.gather_bilevel_kv(gl, desc, dks[l], dvs[l], mask, kmixes[l], vmixes[l], mix_lens[l])
+            vxl.bilevel_decode(desc, dqds[l], kmixes[l], vmixes[l], mix_lens[l], ods[l], None, ws_de)
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB read + 1 GiB written
@@ -137,69 +187,138 @@ def main():
         step()
     torch.cuda.synchronize()
 
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    for a, b in ev:        # materialise the event handles
-        a.record()
-        b.record()
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_layers)]
+          for _ in range(args.steps)]
+    for per_step in ev:        # materialise the event handles
+        for a, b in per_step:
+            a.record()
+            b.record()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for a, b in ev:
-        vxl.debug_prefill_events(a, b)
-        step()
+    for per_step in ev:
+        step(per_step)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     vxl.debug_prefill_events(None, None)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kernel_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    kernel_ms = float(np.mean([a.elapsed_time(b) for per_step in ev for a, b in per_step]))   # per launch = per layer
     pairs = gl.pair_count()
-    eff_flops = 4.0 * D * Hq * pairs
+    flops_layer = 4.0 * D * Hq * pairs
+    eff_flops = flops_layer * n_layers
     value = eff_flops / (ms_per_step * 1e-3) / 1e12
-    achieved = eff_flops / (kernel_ms * 1e-3) / 1e12
-    mixlen = int(mix_len.cpu()[0])
+    achieved = flops_layer / (kernel_ms * 1e-3) / 1e12
+    mixlen = int(mix_lens[0].cpu()[0])
 
-    kernel_name = {0: "prefill_dma_kernel", 3: "prefill_pipe_kernel"}.get(args.prefill_variant, "prefill_mfma_kernel")
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(args.workload, {}).get(kernel_name)
-        except Exception:
-            traffic = None
-
+    kernel_name = "prefill_dma_kernel"
     result = {
         "metric": "chunk-prefill effective TFLOP/s over the whole hot-path step "
-                  "(prefill + score/top-k + gather + decode)",
+                  "(prefill + score/top-k + gather + decode, all layers)",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.workload, "n_tokens": lay.n_tokens, "n_prefix": lay.n_prefix,
-                   "n_chunks": C, "q_heads": Hq, "kv_heads": Hkv, "head_dim": D, "decode_tokens": T,
-                   "top_k": top_k, "mixed_kv_len": mixlen, "allowed_pairs": pairs,
-                   "effective_flops": eff_flops},
+        "config": {"workload": args.workload, "layers": n_layers, "n_tokens": lay.n_tokens,
+                   "n_prefix": lay.n_prefix, "n_chunks": C, "q_heads": Hq, "kv_heads": Hkv, "head_dim": D,
+                   "decode_tokens": T, "top_k": top_k, "mixed_kv_len": mixlen, "allowed_pairs_per_layer": pairs,
+                   "effective_flops": eff_flops,
+                   "resident_kv_bytes": int(sum(k.numel() + v.numel() for k, v in zip(dks, dvs)) * 2)},
         "roofline": {"bound": "mfma", "kernel": kernel_name, "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                     "traffic": traffic, "kernel_ms": kernel_ms},
+                     "traffic": stored_traffic(args.workload, kernel_name), "kernel_ms": kernel_ms,
+                     "launches_timed": args.steps * n_layers, "flops_per_launch": flops_layer},
     }
 
     if not args.no_extras:
-        result["bilevel"] = measure_bilevel(torch, vxl, w, gl, desc, dk, dv, dqd, mask, l_cap, mixlen)
-        # the same calls at the shapes on which the bandwidth-bound claim is made: config1's mixed KV
-        # (8 MB) is a launch-latency case, these two move 49 MB and 1.08 GB per decode call
-        result["bilevel_large"] = {
-            "config2": bilevel_case(torch, vxl, wl, "config2", wl.WORKLOADS["config2"].k),
-            "config4_k_all": bilevel_case(torch, vxl, wl, "config4", 1 << 30),
-        }
-        result["widening"] = measure_widening(torch, vxl, w, lay, gl, desc, dk, dv, dqd)
-        # one layer of the 28-layer workload: its 28 decode calls per token read 28 distinct mixed
-        # KV sets (1.04 GB), which is what the rotating buffers of the measurement stand for
-        c3 = bilevel_case(torch, vxl, wl, "config3", wl.WORKLOADS["config3"].k)
-        c3["us_per_token_28_layers"] = 28 * c3["decode_step"]["us_per_token"]
-        result["bilevel_large"]["config3_per_layer"] = c3
+        result["decode_all_layers"] = measure_layer_stack_decode(torch, vxl, w, desc, dqds, kmixes, vmixes,
+                                                                 mix_lens, l_cap, mixlen)
+        # the same calls per launch shape, on buffers rotated through > 1 GiB
+        shapes = {}
+        for name, kk in (("config1", None), ("config2", None), ("config3", None), ("config4_k_all", 1 << 30)):
+            wn = name.split("_")[0]
+            shapes[name] = bilevel_case(torch, vxl, wl, wn, wl.WORKLOADS[wn].k if kk is None else kk)
+        result["bilevel"] = shapes
+        result["prefill_other_workloads"] = {n: prefill_only(torch, vxl, wl, n) for n in ("config1", "config2", "config4")
+                                             if n != args.workload}
+        w1 = wl.WORKLOADS["config1"]
+        result["widening"] = measure_widening(torch, vxl, wl, w1)
         result["attained_peaks"] = measure_attained_peaks(torch, vxl)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, lay, q, k, v)
+        hq, hk, hv = (vxl.to_host(x) for x in (dqs[0], dks[0], dvs[0]))
+        result["cpu_baseline"] = cpu_baseline(w, lay, hq, hk, hv)
     print(json.dumps(result))
+
+
+def prefill_only(torch, vxl, wl, name, steps=10, warmup=3):
+    """vxl_chunk_prefill alone on another workload's layout (device-drawn values of its scale)."""
+    w = wl.WORKLOADS[name]
+    lay = wl.make_layout(w)
+    gl = vxl.Layout(lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx)
+    desc = vxl.make_desc(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
+    gen = torch.Generator(device="cuda").manual_seed(w.seed)
+    draw = lambda h: (torch.randn((h, lay.n_tokens, w.head_dim), device="cuda", generator=gen)
+                      * w.value_scale).to(torch.bfloat16)
+    q, k, v = draw(w.n_q_heads), draw(w.n_kv_heads), draw(w.n_kv_heads)
+    out = torch.empty_like(q)
+    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_PREFILL, gl, desc))
+    for _ in range(warmup):
+        vxl.chunk_prefill(gl, desc, q, k, v, out, None, ws)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in ev:
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    a0, b0 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a0.record()
+    for a, b in ev:
+        vxl.debug_prefill_events(a, b)
+        vxl.chunk_prefill(gl, desc, q, k, v, out, None, ws)
+    b0.record()
+    torch.cuda.synchronize()
+    vxl.debug_prefill_events(None, None)
+    kernel_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    flops = 4.0 * w.head_dim * w.n_q_heads * gl.pair_count()
+    return {"call_ms": a0.elapsed_time(b0) / steps, "kernel_ms": kernel_ms, "effective_flops": flops,
+            "kernel_TFLOPs": flops / kernel_ms / 1e9, "frac_mfma_peak": flops / kernel_ms / 1e9 / PEAK_BF16_TFLOPS,
+            "steps": steps, "warmup": warmup}
+
+
+def measure_layer_stack_decode(torch, vxl, w, desc, dqds, kmixes, vmixes, mix_lens, l_cap, mixlen):
+    """One generated token through every layer: n_layers decode calls (T = 1) over the n_layers
+    distinct resident mixed KV sets the timed step has built, replayed from one HIP graph."""
+    n_layers = len(kmixes)
+    B, D, Hkv, Hq = w.B, w.head_dim, w.n_kv_heads, w.n_q_heads
+    q1 = [qd[:, :1].contiguous() for qd in dqds]
+    o1 = [torch.empty_like(x) for x in q1]
+    ws1 = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_DECODE, None, desc, B, 1, l_cap))
+
+    def token():
+        for l in range(n_layers):
+            vxl.bilevel_decode(desc, q1[l], kmixes[l], vmixes[l], mix_lens[l], o1[l], None, ws1)
+
+    for _ in range(3):
+        token()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    reps_in_graph = max(1, 64 // n_layers)
+    with torch.cuda.graph(graph):
+        for _ in range(reps_in_graph):
+            token()
+    graph.replay()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 5
+    a.record()
+    for _ in range(reps):
+        graph.replay()
+    b.record()
+    torch.cuda.synchronize()
+    us_token = a.elapsed_time(b) * 1e3 / (reps * reps_in_graph)
+    bytes_token = n_layers * (2 * B * Hkv * mixlen * D * 2 + 2 * B * Hq * D * 2)
+    return {"layers": n_layers, "us_per_token": us_token, "us_per_layer": us_token / n_layers,
+            "bytes_per_token": bytes_token, "GBps": bytes_token / us_token / 1e3,
+            "frac_hbm": bytes_token / us_token / 1e3 / PEAK_HBM_GBS, "timing": "HIP graph replay",
+            "cache_note": "the mixed KV sets of all layers together exceed the on-package cache only when "
+                          "layers x bytes per layer > 256 MiB"}
 
 
 def measure_attained_peaks(torch, vxl):
@@ -230,10 +349,16 @@ def measure_attained_peaks(torch, vxl):
             "copy_1GiB_GBps_read_plus_write": copy, "copy_frac_of_published": copy / PEAK_HBM_GBS}
 
 
-def measure_widening(torch, vxl, w, lay, gl, desc, dk, dv, dqd):
-    """The calls beyond the four of the step, timed on their own on the step's workload: the
+def measure_widening(torch, vxl, wl, w):
+    """The calls beyond the four of the step, timed on their own on workload config1: the
     attention-mass relevance score (streams the dense K once) and the pooling of the dense KVs
     into sparse KVs (streams K and V once)."""
+    lay = wl.make_layout(w)
+    gl = vxl.Layout(lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx)
+    desc = vxl.make_desc(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
+    _, hk, hv = wl.make_qkv(w, lay, with_q=False)
+    dk, dv = vxl.to_device(hk, w.dtype), vxl.to_device(hv, w.dtype)
+    dqd = vxl.to_device(wl.make_decode_queries(w), w.dtype)
     B, T, C, D, Hkv = w.B, w.T, lay.n_chunks, w.head_dim, w.n_kv_heads
     e = 2
     idx = torch.zeros((B, min(w.k, C)), dtype=torch.int32, device="cuda")

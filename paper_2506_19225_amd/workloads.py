@@ -255,3 +255,53 @@ def tiny_workload(dtype: str, hq: int, hkv: int, d: int, T: int, B: int, k: int,
     """A free-form small workload for edge-case tests (layout supplied separately)."""
     return Workload(f"tiny{seed}", dtype, hq, hkv, d, 1, 0, 1, 0, T=T, B=B, k=k, seed=seed,
                     value_scale=value_scale)
+
+
+# --------------------------------------------------------------------------------------
+# device-side draws for the workloads that are too large to draw on the host
+# --------------------------------------------------------------------------------------
+def _device_normal(shape, scale: float, dtype: str, seed: int, device):
+    """N(0,1) * scale drawn by torch's counter-based generator on `device`, rounded once to the
+    storage dtype.  Drawn in slabs along the first axis to bound the fp32 temporary."""
+    import torch
+    gen = torch.Generator(device=device).manual_seed(int(seed))
+    out = torch.empty(shape, dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device=device)
+    for i in range(shape[0]):
+        x = torch.randn(shape[1:], dtype=torch.float32, device=device, generator=gen)
+        if scale != 1.0:
+            x *= scale
+        out[i].copy_(x)                     # bf16: round to nearest even, once
+    return out
+
+
+def _device_seed(w: Workload, layer: int, tag: int) -> int:
+    return ((w.seed * 1_000_003 + layer) << 8) + tag
+
+
+def make_qkv_device(w: Workload, layout: Layout, layer: int = 0, with_q: bool = True, device="cuda"):
+    """Q[Hq,N,D], K[Hkv,N,D], V[Hkv,N,D] as DEVICE tensors in the storage dtype, independent seeded
+    Gaussians per layer with the value scale of the workload (the 28-layer workload draws 21 G
+    elements: minutes on the host, a second on the device).  The values differ from make_qkv's
+    (another generator); a test hands the oracle a host copy of exactly these tensors, so both
+    sides still compute on the same bits.  Workloads with a planted signal are drawn on the host."""
+    assert w.planted_fraction == 0.0, "planted workloads are drawn by make_qkv"
+    n = layout.n_tokens
+    k = _device_normal((w.n_kv_heads, n, w.head_dim), w.value_scale, w.dtype, _device_seed(w, layer, 0x4B), device)
+    v = _device_normal((w.n_kv_heads, n, w.head_dim), w.value_scale, w.dtype, _device_seed(w, layer, 0x56), device)
+    q = None
+    if with_q:
+        q = _device_normal((w.n_q_heads, n, w.head_dim), w.value_scale, w.dtype, _device_seed(w, layer, 0x51), device)
+    return q, k, v
+
+
+def make_q_device(w: Workload, layout: Layout, layer: int = 0, device="cuda"):
+    """Q[Hq,N,D] of make_qkv_device alone (the same bits), for callers that keep K and V of many
+    layers resident and draw one layer's Q at a time."""
+    return _device_normal((w.n_q_heads, layout.n_tokens, w.head_dim), w.value_scale, w.dtype,
+                          _device_seed(w, layer, 0x51), device)
+
+
+def make_decode_queries_device(w: Workload, layer: int = 0, device="cuda"):
+    """Qd[B, T, Hq, D] as a device tensor in the storage dtype (see make_qkv_device)."""
+    return _device_normal((w.B, w.T, w.n_q_heads, w.head_dim), w.value_scale, w.dtype,
+                          _device_seed(w, layer, 0xDE), device)
