@@ -57,7 +57,8 @@ typedef enum {
     VXL_OP_SCORE_TOPK = 1,
     VXL_OP_GATHER = 2,
     VXL_OP_DECODE = 3,
-    VXL_OP_SCORE_MASS = 4
+    VXL_OP_SCORE_MASS = 4,
+    VXL_OP_DECODE_INPLACE = 5
 } vxl_op;
 
 /*
@@ -255,6 +256,43 @@ vxl_status vxl_bilevel_decode(const vxl_attn_desc* desc, const void* Qd, int32_t
                               int32_t n_q_tokens, const void* Kmix, const void* Vmix,
                               int32_t l_cap, const int32_t* mix_len, void* O, float* LSE,
                               void* workspace, size_t workspace_bytes, vxl_stream stream);
+
+/*
+ * Gather-free decode ("Bi-level KVs Decoding": generation attends to the dense KVs of the relevant
+ * chunks and the sparse KVs of the others): the result of vxl_gather_bilevel_kv[_pooled] followed
+ * by vxl_bilevel_decode, without building the mixed buffers.  A first pass writes only the row map
+ * of every query (4 bytes per mixed row) and the lengths; the split-KV kernels then read the dense
+ * rows from K / V and the sparse rows from Ksp / Vsp in place, through that map.  It saves the
+ * gather's write and the re-read of 2 * n_kv_heads * mix_len * head_dim elements per query, and the
+ * mixed buffers themselves.
+ *   K, V        device dense keys / values of the layer (layout of the descriptor)
+ *   Ksp, Vsp    device [n_kv_heads, S_total, head_dim] sparse rows in chunk order -- the pooled rows of
+ *               vxl_pool_sparse_kv, or the kept rows compacted (consecutive sparse chunks are then
+ *               contiguous, which is the fast case); both NULL: the kept rows are read where they
+ *               lie in K / V, through the kept-token ids of the layout
+ *   dense_mask  device uint8 [batch, n_chunks]
+ *   l_cap       capacity of the row map per query, at least vxl_mixed_kv_capacity(layout, k) for the
+ *               k that produced the mask; a query that needs more is reported as in
+ *               vxl_gather_bilevel_kv (length = -(rows needed), O = 0, LSE = -inf)
+ *   map_ready   0: build the row map and the lengths first (one more launch, a few microseconds);
+ *               != 0: reuse those an earlier call with the same layout, mask, l_cap, batch,
+ *               n_q_tokens and sparse source left in this workspace (and in mix_len, if given) --
+ *               the later tokens of a query, whose selection does not change
+ *   O, LSE      as vxl_bilevel_decode
+ *   mix_len     device int32 [batch] (the mixed lengths: written when map_ready == 0, read
+ *               otherwise) or NULL (they are then kept in the workspace)
+ *   workspace   sized by vxl_workspace_bytes(VXL_OP_DECODE_INPLACE, layout, desc, batch, n_q_tokens, l_cap)
+ * The set of rows a query attends to is exactly that of the gathered path; the summation order
+ * differs, so results agree with it within the tolerance of the path, not bit for bit.
+ * Errors: VXL_ERR_INVALID_ARG, VXL_ERR_UNSUPPORTED (also: a mixed set so long that one wave of the
+ * step-mode kernel would own more than 32 tiles of 32 rows), VXL_ERR_WORKSPACE, VXL_ERR_HIP.
+ */
+vxl_status vxl_bilevel_decode_inplace(const vxl_layout* layout, const vxl_attn_desc* desc, const void* Qd,
+                                      int32_t batch, int32_t n_q_tokens, const void* K, const void* V,
+                                      const void* Ksp, const void* Vsp, const uint8_t* dense_mask,
+                                      int32_t l_cap, int32_t map_ready, void* O, float* LSE,
+                                      int32_t* mix_len, void* workspace, size_t workspace_bytes,
+                                      vxl_stream stream);
 
 /*
  * vxl_bilevel_decode for callers that cannot allocate device memory or carry a workspace: code

@@ -65,7 +65,7 @@ PrefillWorkspace prefill_workspace(const vxl_layout* L, const vxl_attn_desc* d) 
 static std::atomic<int> g_decode_step_waves{0};     // cross-check hook (vxl_debug.h): 0 = choose, 4 or 8 = force
 extern "C" void vxl_debug_decode_step_waves(int w) { g_decode_step_waves = (w == 4 || w == 8) ? w : 0; }
 
-DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
+DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap, bool gathered) {
     DecodePlan p{};
     if (d->dtype != VXL_BF16) { p.n_split = 1; p.split_len = l_cap; p.total = 0; return p; }
     const int rows = (d->n_q_heads / d->n_kv_heads) * T;
@@ -75,7 +75,7 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
     // chip; at short mixed sets the split cap below leaves it a fraction of the compute units
     // (measured at 224 rows: 64 and 120 workgroups, 4-wave kernel 9 % and 5 % faster; 176 and
     // 256 workgroups, ring kernel 5 % and 8 % faster).
-    bool ring = rows > 128;
+    bool ring = gathered && rows > 128;
     if (ring && rows <= 256) {
         const long blocks = (long)batch * d->n_kv_heads;
         const long splits = std::max<long>(1, std::min<long>(std::min<long>((256 + blocks - 1) / blocks, (long)l_cap / rows), tiles));
@@ -93,7 +93,7 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
         const long units = (long)batch * d->n_kv_heads;
         const long max_split = std::max<long>(1, 256 / units);
         // four double-buffered waves (measured equal or faster than eight single-buffered ones at every size)
-        const int kWaves = g_decode_step_waves == 8 ? 8 : 4;
+        const int kWaves = gathered && g_decode_step_waves == 8 ? 8 : 4;
         p.step_waves = kWaves;
         long n_split = std::min<long>((tiles32 + kWaves - 1) / kWaves, max_split);
         const int tpw = (int)((tiles32 + kWaves * n_split - 1) / (kWaves * n_split));
@@ -127,6 +127,20 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap) {
     off += align_up((size_t)batch * d->n_kv_heads * p.n_split * rows * sizeof(float), 256);
     p.total = off;
     return p;
+}
+
+// Workspace of the in-place decode: split-KV partial results, then the row map and the lengths.
+InplaceWorkspace inplace_workspace(const vxl_attn_desc* d, int batch, int T, int l_cap) {
+    InplaceWorkspace w{};
+    size_t off = 0;
+    w.partials = off;
+    off += align_up(std::max<size_t>(256, decode_plan(d, batch, T, l_cap, false).total), 256);
+    w.src_idx = off;
+    off += align_up((size_t)batch * l_cap * sizeof(int32_t), 256);
+    w.mix_len = off;
+    off += align_up((size_t)batch * sizeof(int32_t), 256);
+    w.total = off;
+    return w;
 }
 
 }  // namespace vxl
@@ -356,6 +370,9 @@ size_t vxl_workspace_bytes(vxl_op op, const vxl_layout* L, const vxl_attn_desc* 
         case VXL_OP_SCORE_MASS:
             if (!L || batch <= 0 || n_q_tokens <= 0) return 0;
             return std::max<size_t>(256, mass_plan(L, d, batch, n_q_tokens).total);
+        case VXL_OP_DECODE_INPLACE:
+            if (batch <= 0 || n_q_tokens <= 0 || l_cap <= 0) return 0;
+            return inplace_workspace(d, batch, n_q_tokens, l_cap).total;
     }
     return 0;
 }
@@ -487,6 +504,39 @@ vxl_status vxl_bilevel_decode(const vxl_attn_desc* d, const void* Qd, int32_t ba
     }
     return launch_decode_simple(d, scale, Qd, batch, n_q_tokens, Kmix, Vmix, l_cap, mix_len, O, LSE,
                                 (hipStream_t)stream);
+}
+
+vxl_status vxl_bilevel_decode_inplace(const vxl_layout* L, const vxl_attn_desc* d, const void* Qd,
+                                      int32_t batch, int32_t n_q_tokens, const void* K, const void* V,
+                                      const void* Ksp, const void* Vsp, const uint8_t* dense_mask,
+                                      int32_t l_cap, int32_t map_ready, void* O, float* LSE, int32_t* mix_len,
+                                      void* workspace, size_t workspace_bytes, vxl_stream stream) {
+    vxl_status st;
+    if (!L) return VXL_ERR_INVALID_ARG;
+    if (!desc_ok(d, &st)) return st;
+    if (!Qd || !K || !V || !O || batch <= 0 || n_q_tokens <= 0 || l_cap <= 0) return VXL_ERR_INVALID_ARG;
+    if (L->n_chunks > 0 && !dense_mask) return VXL_ERR_INVALID_ARG;
+    if ((Ksp == nullptr) != (Vsp == nullptr)) return VXL_ERR_INVALID_ARG;
+    if (!aligned16(Qd) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(Ksp) || !aligned16(Vsp))
+        return VXL_ERR_INVALID_ARG;
+    if (l_cap < vxl_mixed_kv_capacity(L, 0)) return VXL_ERR_INVALID_ARG;
+    const InplaceWorkspace w = inplace_workspace(d, batch, n_q_tokens, l_cap);
+    if (!workspace || workspace_bytes < w.total || !aligned16(workspace)) return VXL_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    int32_t* src_idx = (int32_t*)((char*)workspace + w.src_idx);
+    int32_t* len = mix_len ? mix_len : (int32_t*)((char*)workspace + w.mix_len);
+    const bool pooled = Ksp != nullptr && L->s_total > 0;
+    if (!map_ready) {           // the row map and the lengths: the gather's index pass, no row is copied
+        st = launch_gather(L, d, K, V, pooled ? Ksp : nullptr, pooled ? Vsp : nullptr, dense_mask, batch, nullptr,
+                           nullptr, l_cap, len, src_idx, s);
+        if (st != VXL_OK) return st;
+    }
+    const float scale = resolve_scale(d);
+    if (d->dtype == VXL_BF16 && !g_force_simple)
+        return launch_decode_bf16_inplace(L, d, scale, Qd, batch, n_q_tokens, K, V, Ksp, Vsp, src_idx, l_cap, len, O,
+                                          LSE, (char*)workspace + w.partials, s);
+    return launch_decode_inplace_simple(L, d, scale, Qd, batch, n_q_tokens, K, V, Ksp, Vsp, src_idx, l_cap, len, O,
+                                        LSE, s);
 }
 
 vxl_status vxl_bilevel_decode_static(const vxl_attn_desc* d, const void* Qd, int32_t batch,

@@ -320,6 +320,8 @@ __global__ __launch_bounds__(256) void pool_sparse_kernel(const T* __restrict__ 
 // `groups` consecutive passes of 256 / LPR rows (chosen by the host so that small gathers still
 // fill the chip and large ones amortise the scan).  Block 0 of a query writes mix_len; a query whose
 // mixed set does not fit l_cap gets mix_len = -(rows needed) and none of its rows is copied.
+// With Kmix == nullptr nothing is copied at all: the call only writes mix_len and src_idx (the row
+// map the in-place decode reads the dense and sparse rows through).
 // ------------------------------------------------------------------------------------------
 template <int ROW_BYTES>
 __global__ __launch_bounds__(256) void gather_kernel(
@@ -381,6 +383,7 @@ __global__ __launch_bounds__(256) void gather_kernel(
             else src = Ksp ? -1 - (soff[lo] + o) : sidx[soff[lo] + o];
         }
         if (src_idx && part == 0) src_idx[(size_t)b * l_cap + r] = src;
+        if (!Kmix) continue;                                  // index-only call: no rows are copied
         const uint4* ks = src >= 0 ? K : Ksp;
         const uint4* vs = src >= 0 ? V : Vsp;
         // the pooled rows are dense [Hkv, S_total, D]; K and V have the caller's strides

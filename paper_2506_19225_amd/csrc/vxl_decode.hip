@@ -25,11 +25,24 @@ struct DecodeCfg {
     static constexpr int LDS_BYTES = 2 * (K_ELEMS + V_ELEMS) * 2;
 };
 
-template <int D, int QB>
+// Row map of the in-place form (IND instances of the kernels below): the mixed KV set is not a
+// buffer but a list of rows -- mixed row r of query b is token src_idx[b, r] of the dense K / V
+// (KV head g at kv_head elements, rows kv_tok elements apart) or, if negative, row -1 - src_idx of
+// the sparse buffers Ksp / Vsp [Hkv, S_total, D].
+struct RowMap {
+    const int32_t* src_idx;     // [B, l_cap]
+    const uint16_t* Ksp;        // may be null when no entry is negative
+    const uint16_t* Vsp;
+    long long kv_head;          // elements
+    long long kv_tok;           // elements
+    int s_total;
+};
+
+template <int D, int QB, bool IND = false>
 __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void decode_split_kernel(
     const uint16_t* __restrict__ Qd, const uint16_t* __restrict__ Kmix, const uint16_t* __restrict__ Vmix,
     const int32_t* __restrict__ mix_len, float* __restrict__ part_o, float* __restrict__ part_lse, int T_q,
-    int n_q_heads, int n_kv_heads, int group, int l_cap, int n_rtile, int split_len, float scale) {
+    int n_q_heads, int n_kv_heads, int group, int l_cap, int n_rtile, int split_len, float scale, RowMap rm) {
     using C = DecodeCfg<D, QB>;
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
     uint16_t* Ks = lds;
@@ -74,23 +87,33 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void decode_split_kernel(
     const float c2 = scale * kLog2e;
     const bool wave_active = wrow0 < n_rows;       // waves without rows only help with the copies
 
-    const char* kbase = (const char*)(Kmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
-    const char* vbase = (const char*)(Vmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
+    // (IND: Kmix / Vmix are the dense K / V of the layer, read through the row map)
+    const char* kbase = IND ? (const char*)(Kmix + (size_t)g * rm.kv_head)
+                            : (const char*)(Kmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
+    const char* vbase = IND ? (const char*)(Vmix + (size_t)g * rm.kv_head)
+                            : (const char*)(Vmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
+    const char* ksp_g = IND ? (const char*)(rm.Ksp + (size_t)g * rm.s_total * D) : nullptr;
+    const char* vsp_g = IND ? (const char*)(rm.Vsp + (size_t)g * rm.s_total * D) : nullptr;
+    const int32_t* src_b = IND ? rm.src_idx + (size_t)b * l_cap : nullptr;
     const int ld_r = tid / (D / 8), ld_part = tid % (D / 8);
     TileRegs<D, C::VROW> tr;
     const int n_t = (k_hi - k_lo + kKeyTile - 1) / kKeyTile;
     // rows past the end of the split are clamped to its last row (scores masked, V finite)
-    tr.fetch(kbase + (size_t)k_lo * (D * 2), vbase + (size_t)k_lo * (D * 2), ld_r, ld_part,
-             min(kKeyTile - 1, k_hi - 1 - k_lo));
+    auto fetch = [&](int key0_) {
+        const int rlim_ = min(kKeyTile - 1, k_hi - 1 - key0_);
+        if constexpr (IND)
+            tr.fetch_ind(src_b + key0_, kbase, vbase, ksp_g, vsp_g, rm.kv_tok * 2, ld_r, ld_part, rlim_);
+        else
+            tr.fetch(kbase + (size_t)key0_ * (D * 2), vbase + (size_t)key0_ * (D * 2), ld_r, ld_part, rlim_);
+    };
+    fetch(k_lo);
     tr.stage(Ks, Vs, ld_r, ld_part);
     __syncthreads();
     for (int ti = 0; ti < n_t; ++ti) {
         const int buf = ti & 1;
         const int key0 = k_lo + ti * kKeyTile;
         {   // next tile (the last iteration re-reads its own): unconditional, fenced, in flight below
-            const int nk0 = k_lo + min(ti + 1, n_t - 1) * kKeyTile;
-            tr.fetch(kbase + (size_t)nk0 * (D * 2), vbase + (size_t)nk0 * (D * 2), ld_r, ld_part,
-                     min(kKeyTile - 1, k_hi - 1 - nk0));
+            fetch(k_lo + min(ti + 1, n_t - 1) * kKeyTile);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (wave_active) {
@@ -302,12 +325,14 @@ __global__ __launch_bounds__(512, 2) void decode_ring_kernel(
 // tile (the default: 3-8 % faster on long streams, 5 % at a single tile per wave, where it spreads
 // over twice as many compute units) -- and NW = 8 waves with one tile pair each (cross-check).
 constexpr int kStepTile = 32;       // keys per wave tile
+constexpr int kMaxStepTpw = 32;     // in-place form: tiles per wave whose row map fits the wave's LDS area
 
-template <int D, int NW, int NBUF>
+template <int D, int NW, int NBUF, bool IND = false>
 __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
     const uint16_t* __restrict__ Qd, const uint16_t* __restrict__ Kmix, const uint16_t* __restrict__ Vmix,
     const int32_t* __restrict__ mix_len, float* __restrict__ part_o, float* __restrict__ part_lse, int T_q,
-    int n_q_heads, int n_kv_heads, int group, int l_cap, int tiles_per_wave, float scale) {
+    int n_q_heads, int n_kv_heads, int group, int l_cap, int tiles_per_wave, float scale, RowMap rm) {
+    static_assert(!IND || NBUF == 2, "the in-place form exists for the double-buffered kernel only");
     constexpr int TK = kStepTile;
     constexpr int TILE_ELEMS = TK * D;                         // one unpadded tile
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
@@ -323,15 +348,37 @@ __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
     const size_t part_base = (((size_t)b * n_kv_heads + g) * n_split + split) * (size_t)n_rows;
 
     const float c2 = scale * kLog2e;
-    const char* kbase = (const char*)(Kmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
-    const char* vbase = (const char*)(Vmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
+    // (IND: Kmix / Vmix are the dense K / V of the layer, read through the row map)
+    const char* kbase = IND ? (const char*)(Kmix + (size_t)g * rm.kv_head)
+                            : (const char*)(Kmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
+    const char* vbase = IND ? (const char*)(Vmix + (size_t)g * rm.kv_head)
+                            : (const char*)(Vmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
     const int tile0 = split * tiles_per_wave * NW + wave;      // this wave's tiles: tile0, tile0 + NW, ...
+    // IND: the source rows of this wave's tiles go to LDS first (ordinary loads, complete before the
+    // first hand-counted request), so that the requests depend on LDS reads only.
+    __shared__ int32_t row_src[IND ? NW * kMaxStepTpw * TK : 1];
+    int32_t* src_w = row_src + (IND ? wave * kMaxStepTpw * TK : 0);
+    const char* ksp_g = nullptr;
+    const char* vsp_g = nullptr;
+    if constexpr (IND) {
+        ksp_g = (const char*)(rm.Ksp + (size_t)g * rm.s_total * D);
+        vsp_g = (const char*)(rm.Vsp + (size_t)g * rm.s_total * D);
+        const int32_t* src_b = rm.src_idx + (size_t)b * l_cap;
+        for (int i = 0; i < tiles_per_wave; ++i) {
+            const int tile = tile0 + i * NW;
+            if (tile >= n_tiles) break;
+            if (lane < TK) src_w[i * TK + lane] = src_b[min(tile * TK + lane, len - 1)];
+        }
+        __builtin_amdgcn_s_waitcnt(0x0070);                    // vmcnt(0) lgkmcnt(0): the map is in LDS
+        __builtin_amdgcn_wave_barrier();
+    }
 
     // NBUF == 2: direct loads issued from inline assembly and counted by hand (a later request
     // must be allowed to stay in flight while an earlier tile is read).
     constexpr int PPR = D / 8, RPI = 64 / PPR, NL = TK / RPI;  // pieces per row; rows, 1 KiB lines per tile
     const uint32_t lds_w = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)Kw;
-    auto request = [&](int tile_, int buf) {
+    // i_ = position of the tile among this wave's tiles (its row map is src_w + i_ * TK)
+    auto request = [&](int i_, int tile_, int buf) {
         const int key0_ = tile_ * TK;
         const int rlim_ = min(TK - 1, len - 1 - key0_);
         const char* kb = kbase + (size_t)key0_ * (D * 2);
@@ -340,16 +387,25 @@ __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
 #pragma unroll
         for (int x = 0; x < NL; ++x) {
             const int row = x * RPI + r_in;
-            const uint32_t roff = (uint32_t)min(row, rlim_) * (D * 2);
             const int kp = pp ^ ((row / (16 / PPR)) & (PPR - 1));
             constexpr int CPR = D * 2 / 64, RPL = D == 128 ? 1 : 2;
             const int vp = (((pp >> 2) ^ ((row / RPL) & (CPR - 1))) << 2) | (pp & 3);
-            dma16(kb, roff + kp * 16, lds_w + (uint32_t)buf * (4 * TILE_ELEMS) + x * 1024);
-            dma16(vb, roff + vp * 16, lds_w + (uint32_t)buf * (4 * TILE_ELEMS) + 2 * TILE_ELEMS + x * 1024);
+            const uint32_t kdst = lds_w + (uint32_t)buf * (4 * TILE_ELEMS) + x * 1024;
+            const uint32_t vdst = kdst + 2 * TILE_ELEMS;
+            if constexpr (IND) {
+                const int t = src_w[i_ * TK + min(row, rlim_)];
+                const size_t o = t >= 0 ? (size_t)t * (size_t)(rm.kv_tok * 2) : (size_t)(-1 - t) * (D * 2);
+                dma16_addr((t >= 0 ? kbase : ksp_g) + o + kp * 16, kdst);
+                dma16_addr((t >= 0 ? vbase : vsp_g) + o + vp * 16, vdst);
+            } else {
+                const uint32_t roff = (uint32_t)min(row, rlim_) * (D * 2);
+                dma16(kb, roff + kp * 16, kdst);
+                dma16(vb, roff + vp * 16, vdst);
+            }
         }
     };
     if constexpr (NBUF == 2) {
-        if (tile0 < n_tiles) request(tile0, 0);
+        if (tile0 < n_tiles) request(0, tile0, 0);
     }
 
     bf16x8 qreg[1][D / 16];
@@ -398,13 +454,13 @@ __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
         }
     } else {
         // tile i lives in pair i & 1; tile i + 1 is requested as soon as tile i - 1 has been worked on
-        if (tiles_per_wave > 1 && tile0 + NW < n_tiles) request(tile0 + NW, 1);
+        if (tiles_per_wave > 1 && tile0 + NW < n_tiles) request(1, tile0 + NW, 1);
         for (int i = 0; i < tiles_per_wave; ++i) {
             const int tile = tile0 + i * NW;
             if (tile >= n_tiles) break;
             if (i >= 1) {
                 const bool more = i + 1 < tiles_per_wave && tile + NW < n_tiles;
-                if (more) request(tile + NW, (i + 1) & 1);
+                if (more) request(i + 1, tile + NW, (i + 1) & 1);
                 if (more) wait_vmcnt<2 * NL>(); else wait_vmcnt<0>();      // tile i has landed
             }
             __builtin_amdgcn_wave_barrier();
@@ -553,9 +609,9 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const float* __restri
 template <int D, int QB>
 static vxl_status run_decode(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
                              const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len, void* O,
-                             float* LSE, void* ws, hipStream_t s) {
+                             float* LSE, void* ws, hipStream_t s, const RowMap* rm = nullptr) {
     using C = DecodeCfg<D, QB>;
-    const DecodePlan p = decode_plan(d, batch, T, l_cap);
+    const DecodePlan p = decode_plan(d, batch, T, l_cap, rm == nullptr);
     float* part_o = (float*)((char*)ws + p.part_o);
     float* part_lse = (float*)((char*)ws + p.part_ml);
     const int group = d->n_q_heads / d->n_kv_heads;
@@ -563,15 +619,23 @@ static vxl_status run_decode(const vxl_attn_desc* d, float scale, const void* Qd
     const int n_rtile = (n_rows + C::RT - 1) / C::RT;
     static PerDeviceOnce attr;
     const vxl_status ast = attr.run([] {
-        VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_split_kernel<D, QB>,
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_split_kernel<D, QB, false>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_split_kernel<D, QB, true>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
         return VXL_OK;
     });
     if (ast != VXL_OK) return ast;
-    hipLaunchKernelGGL((decode_split_kernel<D, QB>), dim3(p.n_split, n_rtile * d->n_kv_heads, batch), dim3(256),
-                       C::LDS_BYTES, s, (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix,
-                       mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap, n_rtile,
-                       p.split_len, scale);
+    if (rm)
+        hipLaunchKernelGGL((decode_split_kernel<D, QB, true>), dim3(p.n_split, n_rtile * d->n_kv_heads, batch),
+                           dim3(256), C::LDS_BYTES, s, (const uint16_t*)Qd, (const uint16_t*)Kmix,
+                           (const uint16_t*)Vmix, mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group,
+                           l_cap, n_rtile, p.split_len, scale, *rm);
+    else
+        hipLaunchKernelGGL((decode_split_kernel<D, QB, false>), dim3(p.n_split, n_rtile * d->n_kv_heads, batch),
+                           dim3(256), C::LDS_BYTES, s, (const uint16_t*)Qd, (const uint16_t*)Kmix,
+                           (const uint16_t*)Vmix, mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group,
+                           l_cap, n_rtile, p.split_len, scale, RowMap{});
     VXL_HIP_TRY(hipGetLastError());
     const size_t merge_lds = (size_t)(((p.n_split + 3) & ~3) + 256 / (D / 4) * D) * sizeof(float);
     hipLaunchKernelGGL((decode_merge_kernel<D>), dim3(n_rows, d->n_kv_heads, batch), dim3(256), merge_lds, s,
@@ -613,8 +677,8 @@ static vxl_status run_decode_ring(const vxl_attn_desc* d, float scale, const voi
 template <int D>
 static vxl_status run_decode_wave(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
                                   const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len, void* O,
-                                  float* LSE, void* ws, hipStream_t s) {
-    const DecodePlan p = decode_plan(d, batch, T, l_cap);
+                                  float* LSE, void* ws, hipStream_t s, const RowMap* rm = nullptr) {
+    const DecodePlan p = decode_plan(d, batch, T, l_cap, rm == nullptr);
     float* part_o = (float*)((char*)ws + p.part_o);
     float* part_lse = (float*)((char*)ws + p.part_ml);
     const int group = d->n_q_heads / d->n_kv_heads;
@@ -626,19 +690,28 @@ static vxl_status run_decode_wave(const vxl_attn_desc* d, float scale, const voi
                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
         VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_wave_kernel<D, 4, 2>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_wave_kernel<D, 4, 2, true>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
         return VXL_OK;
     });
     if (ast != VXL_OK) return ast;
-    if (p.step_waves == 8)
+    if (rm) {
+        // (the plan of the in-place form always has 4 waves; the row map of a wave's tiles must fit its LDS area)
+        if (p.split_len / (4 * kStepTile) > kMaxStepTpw) return VXL_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL((decode_wave_kernel<D, 4, 2, true>), dim3(p.n_split, d->n_kv_heads, batch), dim3(256),
+                           lds_bytes, s, (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix,
+                           mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap,
+                           p.split_len / (4 * kStepTile), scale, *rm);
+    } else if (p.step_waves == 8)
         hipLaunchKernelGGL((decode_wave_kernel<D, 8, 1>), dim3(p.n_split, d->n_kv_heads, batch), dim3(512),
                            lds_bytes, s, (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix,
                            mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap,
-                           p.split_len / (8 * kStepTile), scale);
+                           p.split_len / (8 * kStepTile), scale, RowMap{});
     else
         hipLaunchKernelGGL((decode_wave_kernel<D, 4, 2>), dim3(p.n_split, d->n_kv_heads, batch), dim3(256),
                            lds_bytes, s, (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix,
                            mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap,
-                           p.split_len / (4 * kStepTile), scale);
+                           p.split_len / (4 * kStepTile), scale, RowMap{});
     VXL_HIP_TRY(hipGetLastError());
     const size_t merge_lds = (size_t)(((p.n_split + 3) & ~3) + 256 / (D / 4) * D) * sizeof(float);
     hipLaunchKernelGGL((decode_merge_kernel<D>), dim3(n_rows, d->n_kv_heads, batch), dim3(256), merge_lds, s,
@@ -683,6 +756,22 @@ vxl_status launch_decode_bf16(const vxl_attn_desc* d, float scale, const void* Q
                    : run_decode<128, 1>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s);
     return big ? run_decode_ring<64>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s)
                : run_decode<64, 1>(d, scale, Qd, batch, T, Kmix, Vmix, l_cap, mix_len, O, LSE, ws, s);
+}
+
+// In-place form: K / V are the dense tensors of the layer, rows reached through src_idx.
+vxl_status launch_decode_bf16_inplace(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Qd,
+                                      int batch, int T, const void* K, const void* V, const void* Ksp,
+                                      const void* Vsp, const int32_t* src_idx, int l_cap, const int32_t* mix_len,
+                                      void* O, float* LSE, void* ws, hipStream_t s) {
+    const TokStrides ts = tok_strides(d, L->n_tokens);
+    const RowMap rm{src_idx, (const uint16_t*)Ksp, (const uint16_t*)Vsp, ts.kh, ts.kt, L->s_total};
+    const int n_rows = (d->n_q_heads / d->n_kv_heads) * T;
+    if (n_rows <= kRowBlock)
+        return d->head_dim == 128
+                   ? run_decode_wave<128>(d, scale, Qd, batch, T, K, V, l_cap, mix_len, O, LSE, ws, s, &rm)
+                   : run_decode_wave<64>(d, scale, Qd, batch, T, K, V, l_cap, mix_len, O, LSE, ws, s, &rm);
+    return d->head_dim == 128 ? run_decode<128, 1>(d, scale, Qd, batch, T, K, V, l_cap, mix_len, O, LSE, ws, s, &rm)
+                              : run_decode<64, 1>(d, scale, Qd, batch, T, K, V, l_cap, mix_len, O, LSE, ws, s, &rm);
 }
 
 }  // namespace vxl

@@ -176,11 +176,28 @@ struct DecodePlan {
     size_t part_ml;
     size_t total;
 };
-DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap);
+// gathered = false plans the in-place form (no 256-row ring kernel, always the 4-wave step kernel)
+DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap, bool gathered = true);
+
+struct InplaceWorkspace {      // byte offsets into the caller's workspace (vxl_bilevel_decode_inplace)
+    size_t partials;           // the decode plan's partial results
+    size_t src_idx;            // [B][l_cap] int32 row map
+    size_t mix_len;            // [B] int32 (used when the caller does not ask for the lengths)
+    size_t total;
+};
+InplaceWorkspace inplace_workspace(const vxl_attn_desc* d, int batch, int T, int l_cap);
 
 vxl_status launch_decode_bf16(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
                               const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len,
                               void* O, float* LSE, void* ws, hipStream_t s);
+vxl_status launch_decode_bf16_inplace(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Qd,
+                                      int batch, int T, const void* K, const void* V, const void* Ksp,
+                                      const void* Vsp, const int32_t* src_idx, int l_cap, const int32_t* mix_len,
+                                      void* O, float* LSE, void* ws, hipStream_t s);
+vxl_status launch_decode_inplace_simple(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Qd,
+                                        int batch, int T, const void* K, const void* V, const void* Ksp,
+                                        const void* Vsp, const int32_t* src_idx, int l_cap,
+                                        const int32_t* mix_len, void* O, float* LSE, hipStream_t s);
 // device address of this device's static decode scratch (VXL_STATIC_SCRATCH_BYTES bytes)
 vxl_status decode_static_scratch(void** ptr);
 vxl_status launch_decode_simple(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,

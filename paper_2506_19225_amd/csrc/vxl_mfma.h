@@ -73,6 +73,27 @@ struct TileRegs {
         }
 #undef VXL_TILE_OFF
     }
+    // The same for rows reached through a row map: tile row r is token src[r] of the dense tensors
+    // (rows kv_tok_bytes apart from kd / vd) or, if src[r] < 0, row -1 - src[r] of the sparse
+    // buffers ks / vs (rows D * 2 bytes apart).  src points at the tile's first entry.
+    __device__ __forceinline__ void fetch_ind(const int32_t* src, const char* kd, const char* vd, const char* ks,
+                                              const char* vs, long long kv_tok_bytes, int ld_r, int ld_part,
+                                              int rlim) {
+#define VXL_TILE_ROW(i_, k_, v_)                                                                      \
+        do {                                                                                          \
+            const int t_ = src[min(ld_r + (i_) * RPP, rlim)];                                         \
+            const size_t o_ = t_ >= 0 ? (size_t)t_ * kv_tok_bytes : (size_t)(-1 - t_) * (D * 2);      \
+            k_ = *(const uint4*)((t_ >= 0 ? kd : ks) + o_ + ld_part * 16);                            \
+            v_ = *(const uint4*)((t_ >= 0 ? vd : vs) + o_ + ld_part * 16);                            \
+        } while (0)
+        VXL_TILE_ROW(0, k0, v0);
+        VXL_TILE_ROW(1, k1, v1);
+        if constexpr (LD > 2) {
+            VXL_TILE_ROW(2, k2, v2);
+            VXL_TILE_ROW(3, k3, v3);
+        }
+#undef VXL_TILE_ROW
+    }
     __device__ __forceinline__ void stage(uint16_t* kt, uint16_t* vt, int ld_r, int ld_part) const {
         *(uint4*)(kt + k_tile_off<D>(ld_r, ld_part)) = k0;
         *(uint4*)(vt + ld_r * VROW + ld_part * 8) = v0;
@@ -279,6 +300,12 @@ __device__ __forceinline__ void wait_vmcnt0_lgkmcnt0() { __builtin_amdgcn_s_wait
 __device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t lds_off) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(lds_off), "v"(off), "s"(base) : "memory");
+}
+
+// The same from a per-lane 64-bit address (rows gathered from anywhere in memory).
+__device__ __forceinline__ void dma16_addr(const void* addr, uint32_t lds_off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_off), "v"(addr) : "memory");
 }
 
 // O^T[qb][db] += V^T . P^T over the 64 keys of the tile.

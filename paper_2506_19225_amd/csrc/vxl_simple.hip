@@ -29,12 +29,11 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// Softmax attention of one query row over n_keys keys; key(slot) returns the row offset (in
-// elements) of key `slot` inside kbase/vbase.  q_lds: this wave's D floats of LDS.
-template <typename T, int D, typename KeyFn>
-__device__ __forceinline__ void attend_row(const T* qrow, const T* kbase, const T* vbase, KeyFn key,
-                                           int n_keys, float scale, float* q_lds, T* orow,
-                                           float* lse_out) {
+// Softmax attention of one query row over n_keys keys; krow(slot) / vrow(slot) return the K and
+// the V row of key `slot`.  q_lds: this wave's D floats of LDS.
+template <typename T, int D, typename KRowFn, typename VRowFn>
+__device__ __forceinline__ void attend_row(const T* qrow, KRowFn krow, VRowFn vrow, int n_keys, float scale,
+                                           float* q_lds, T* orow, float* lse_out) {
     const int lane = threadIdx.x & 63;
     constexpr int X = D / 64;
 #pragma unroll
@@ -49,7 +48,7 @@ __device__ __forceinline__ void attend_row(const T* qrow, const T* kbase, const 
         const bool valid = slot < n_keys;
         float s = -INFINITY;
         if (valid) {
-            const T* kp = kbase + key(slot);
+            const T* kp = krow(slot);
             float a = 0.f;
 #pragma unroll 8
             for (int d = 0; d < D; ++d) a = fmaf(q_lds[d], ld(kp + d), a);
@@ -64,7 +63,7 @@ __device__ __forceinline__ void attend_row(const T* qrow, const T* kbase, const 
         const int cnt = min(64, n_keys - base);
         for (int j = 0; j < cnt; ++j) {
             const float pj = __shfl(p, j);
-            const T* vp = vbase + key(base + j);
+            const T* vp = vrow(base + j);
 #pragma unroll
             for (int x = 0; x < X; ++x) acc[x] = fmaf(pj, ld(vp + lane + 64 * x), acc[x]);
         }
@@ -112,10 +111,11 @@ __global__ __launch_bounds__(256) void prefill_simple_kernel(
         else tok = own_start + (slot - n_hist);
         return (size_t)tok * kv_tok;
     };
-    const size_t kv_head = (size_t)g * kv_head_stride;
+    const T* kh = K + (size_t)g * kv_head_stride;
+    const T* vh = V + (size_t)g * kv_head_stride;
     const size_t q_off = (size_t)h * q_head + (size_t)i * q_tok;
-    attend_row<T, D>(Q + q_off, K + kv_head, V + kv_head, key, n_keys, scale, q_lds[wave], O + q_off,
-                     LSE ? LSE + (size_t)h * n_tokens + i : nullptr);
+    attend_row<T, D>(Q + q_off, [=](int slot) { return kh + key(slot); }, [=](int slot) { return vh + key(slot); },
+                     n_keys, scale, q_lds[wave], O + q_off, LSE ? LSE + (size_t)h * n_tokens + i : nullptr);
 }
 
 template <typename T, int D>
@@ -141,8 +141,43 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(
         if (LSE && lane == 0) LSE[row] = -INFINITY;
         return;
     }
-    attend_row<T, D>(Qd + row * D, Kmix + kv_off, Vmix + kv_off, key, n_keys, scale, q_lds[wave],
-                     O + row * D, LSE ? LSE + row : nullptr);
+    const T* kh = Kmix + kv_off;
+    const T* vh = Vmix + kv_off;
+    attend_row<T, D>(Qd + row * D, [=](int slot) { return kh + key(slot); }, [=](int slot) { return vh + key(slot); },
+                     n_keys, scale, q_lds[wave], O + row * D, LSE ? LSE + row : nullptr);
+}
+
+// The same over the mixed KV set read in place: mixed row `slot` of query b is token src_idx[b, slot]
+// of K / V, or (src < 0) row -1 - src of the sparse buffers Ksp / Vsp [Hkv, S_total, D].
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_inplace_simple_kernel(
+    const T* __restrict__ Qd, const T* __restrict__ K, const T* __restrict__ V, const T* __restrict__ Ksp,
+    const T* __restrict__ Vsp, const int32_t* __restrict__ src_idx, T* __restrict__ O, float* __restrict__ LSE,
+    const int32_t* __restrict__ mix_len, int batch, int T_q, int n_q_heads, int group, int l_cap, int s_total,
+    long long kv_head_stride, long long kv_tok, float scale) {
+    __shared__ float q_lds[4][D];
+    const int wave = threadIdx.x >> 6;
+    const long row = (long)blockIdx.x * 4 + wave;           // (b, t, h) flattened
+    const long n_rows = (long)batch * T_q * n_q_heads;
+    if (row >= n_rows) return;
+    const int h = (int)(row % n_q_heads);
+    const int b = (int)(row / ((long)T_q * n_q_heads));
+    const int g = h / group;
+    const int n_keys = min(max(mix_len[b], 0), l_cap);
+    if (n_keys == 0) {
+        const int lane = threadIdx.x & 63;
+        for (int x = 0; x < D / 64; ++x) st(O + row * D + lane + 64 * x, 0.f);
+        if (LSE && lane == 0) LSE[row] = -INFINITY;
+        return;
+    }
+    const int32_t* src = src_idx + (size_t)b * l_cap;
+    const T* kh = K + (size_t)g * kv_head_stride;
+    const T* vh = V + (size_t)g * kv_head_stride;
+    const T* ksh = Ksp ? Ksp + (size_t)g * s_total * D : nullptr;
+    const T* vsh = Vsp ? Vsp + (size_t)g * s_total * D : nullptr;
+    auto krow = [=](int slot) { const int t = src[slot]; return t >= 0 ? kh + (size_t)t * kv_tok : ksh + (size_t)(-1 - t) * D; };
+    auto vrow = [=](int slot) { const int t = src[slot]; return t >= 0 ? vh + (size_t)t * kv_tok : vsh + (size_t)(-1 - t) * D; };
+    attend_row<T, D>(Qd + row * D, krow, vrow, n_keys, scale, q_lds[wave], O + row * D, LSE ? LSE + row : nullptr);
 }
 
 }  // namespace
@@ -174,6 +209,25 @@ vxl_status launch_decode_simple(const vxl_attn_desc* d, float scale, const void*
     hipLaunchKernelGGL((decode_simple_kernel<T_, D>), grid, block, 0, s, (const T_*)Qd,              \
                        (const T_*)Kmix, (const T_*)Vmix, (T_*)O, LSE, mix_len, batch, T, d->n_q_heads, \
                        group, l_cap, scale)
+    if (d->dtype == VXL_F32) { if (d->head_dim == 64) VXL_LAUNCH(float, 64); else VXL_LAUNCH(float, 128); }
+    else { if (d->head_dim == 64) VXL_LAUNCH(uint16_t, 64); else VXL_LAUNCH(uint16_t, 128); }
+#undef VXL_LAUNCH
+    VXL_HIP_TRY(hipGetLastError());
+    return VXL_OK;
+}
+
+vxl_status launch_decode_inplace_simple(const vxl_layout* L, const vxl_attn_desc* d, float scale, const void* Qd,
+                                        int batch, int T, const void* K, const void* V, const void* Ksp,
+                                        const void* Vsp, const int32_t* src_idx, int l_cap,
+                                        const int32_t* mix_len, void* O, float* LSE, hipStream_t s) {
+    const long n_rows = (long)batch * T * d->n_q_heads;
+    const dim3 grid((unsigned)((n_rows + 3) / 4)), block(256);
+    const int group = d->n_q_heads / d->n_kv_heads;
+    const TokStrides ts = tok_strides(d, L->n_tokens);
+#define VXL_LAUNCH(T_, D)                                                                                    \
+    hipLaunchKernelGGL((decode_inplace_simple_kernel<T_, D>), grid, block, 0, s, (const T_*)Qd, (const T_*)K,  \
+                       (const T_*)V, (const T_*)Ksp, (const T_*)Vsp, src_idx, (T_*)O, LSE, mix_len, batch, T,   \
+                       d->n_q_heads, group, l_cap, L->s_total, ts.kh, ts.kt, scale)
     if (d->dtype == VXL_F32) { if (d->head_dim == 64) VXL_LAUNCH(float, 64); else VXL_LAUNCH(float, 128); }
     else { if (d->head_dim == 64) VXL_LAUNCH(uint16_t, 64); else VXL_LAUNCH(uint16_t, 128); }
 #undef VXL_LAUNCH

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG, "libvxl.so")
 
 VXL_OK, VXL_ERR_INVALID_ARG, VXL_ERR_UNSUPPORTED, VXL_ERR_WORKSPACE, VXL_ERR_HIP, VXL_ERR_ALLOC = range(6)
 VXL_F32, VXL_BF16 = 0, 1
-OP_PREFILL, OP_SCORE_TOPK, OP_GATHER, OP_DECODE, OP_SCORE_MASS = range(5)
+OP_PREFILL, OP_SCORE_TOPK, OP_GATHER, OP_DECODE, OP_SCORE_MASS, OP_DECODE_INPLACE = range(6)
 MAX_CHUNKS = 4096
 
 
@@ -89,6 +89,8 @@ def lib() -> C.CDLL:
     L.vxl_kv_store_reload.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp]
     L.vxl_bilevel_decode.restype = C.c_int
     L.vxl_bilevel_decode.argtypes = [dp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.vxl_bilevel_decode_inplace.restype = C.c_int
+    L.vxl_bilevel_decode_inplace.argtypes = [vp, dp, vp, i32, i32, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
     L.vxl_bilevel_decode_static.restype = C.c_int
     L.vxl_bilevel_decode_static.argtypes = [dp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp]
     L.vxl_debug_force_simple.argtypes = [C.c_int]
@@ -256,6 +258,18 @@ def bilevel_decode(desc: AttnDesc, qd, kmix, vmix, mix_len, out, lse=None, works
                                   _ptr(mix_len), _ptr(out), _ptr(lse), _ptr(workspace),
                                   workspace.numel() if workspace is not None else 0, _stream(stream))
     _check(st, "vxl_bilevel_decode")
+    return out
+
+
+def bilevel_decode_inplace(layout: Layout, desc: AttnDesc, qd, k, v, ksp, vsp, dense_mask, l_cap: int, out,
+                           lse=None, mix_len=None, workspace=None, map_ready: bool = False, stream=None):
+    """vxl_bilevel_decode_inplace: gather-free decode; ksp/vsp [Hkv,S_total,D] or None (kept rows in place)."""
+    b, t = int(qd.shape[0]), int(qd.shape[1])
+    st = lib().vxl_bilevel_decode_inplace(layout.handle, C.byref(desc), _ptr(qd), b, t, _ptr(k), _ptr(v), _ptr(ksp),
+                                          _ptr(vsp), _ptr(dense_mask), int(l_cap), int(bool(map_ready)), _ptr(out), _ptr(lse),
+                                          _ptr(mix_len), _ptr(workspace),
+                                          workspace.numel() if workspace is not None else 0, _stream(stream))
+    _check(st, "vxl_bilevel_decode_inplace")
     return out
 
 
