@@ -487,6 +487,36 @@ def measure_bilevel(torch, vxl, w, gl, desc, dk, dv, dqd, mask, l_cap, mixlen):
     bytes_s = kv_bytes + 2 * B * Hq * D * e
     res["decode_step"] = {"us_per_token": us_s, "GBps": bytes_s / us_s / 1e3,
                           "frac_hbm": bytes_s / us_s / 1e3 / PEAK_HBM_GBS}
+    # gather-free decode: the same rows read in place through the row map (built once per query,
+    # reused by every token: map_ready) -- kept rows where they lie in K / V, and from a compacted
+    # copy of the kept rows [Hkv, S_total, D].  K and V themselves are far larger than the cache
+    # only for the long workloads; the figures are per call, after one call that builds the map.
+    del kmixes, vmixes
+    s_total = int(gl.soff[-1])
+    idx = torch.from_numpy(gl.sidx.astype(np.int64)).cuda()
+    n_in = int(max(1, min(n_rot, 24)))          # distinct copies of K / V (and of the kept rows) to rotate through
+    kvs = [(dk, dv)] + [(dk.clone(), dv.clone()) for _ in range(n_in - 1)]
+    sps = [(k_[:, idx].contiguous(), v_[:, idx].contiguous()) if s_total else (None, None) for k_, v_ in kvs]
+    for tag, use_sp in (("kept_in_place", False), ("kept_compacted", True)):
+        for mode, q_, o_, t_ in (("step", qd1, od1, 1), ("batched", dqd, od, T)):
+            wsi = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_DECODE_INPLACE, gl, desc, B, t_, l_cap))
+
+            def call(i, ready=True):
+                k_, v_ = kvs[i % n_in]
+                ks_, vs_ = sps[i % n_in] if use_sp else (None, None)
+                vxl.bilevel_decode_inplace(gl, desc, q_, k_, v_, ks_, vs_, mask, l_cap, o_, None, None, wsi,
+                                           map_ready=ready)
+            try:
+                call(0, ready=False)            # builds the row map (the same for every copy)
+                us = timed(call, iters)
+            except vxl.VxlError as err:
+                res[f"decode_inplace_{mode}_{tag}"] = {"error": str(err)}
+                continue
+            nbytes = kv_bytes + 2 * B * t_ * Hq * D * e + 4 * B * mixlen
+            res[f"decode_inplace_{mode}_{tag}"] = {"us_per_call": us, "us_per_token": us / t_,
+                                                   "GBps": nbytes / us / 1e3,
+                                                   "frac_hbm": nbytes / us / 1e3 / PEAK_HBM_GBS}
+    res["inplace_copies_rotated"] = n_in
     return res
 
 

@@ -74,6 +74,9 @@ def _check_no_compiler_m0(src: str) -> None:
             code = st.split(";")[0]
             if re.search(r"\bm0\b", code):
                 (hand if in_asm else own).setdefault(name, code.strip())
+            if not in_asm and re.match(r"\s*scratch_(load|store)", code):
+                raise RuntimeError(f"{src}: kernel {name} accesses scratch memory ({code.strip()}); its hand-kept "
+                                   "vmcnt bookkeeping needs a compile without stack traffic")
     for name in hand:             # (an instance without hand-issued loads may use m0 as it likes)
         if name in own:
             raise RuntimeError(f"{src}: kernel {name} has a compiler-generated use of m0 ({own[name]}) "

@@ -96,6 +96,8 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap, bool
         const int kWaves = gathered && g_decode_step_waves == 8 ? 8 : 4;
         p.step_waves = kWaves;
         long n_split = std::min<long>((tiles32 + kWaves - 1) / kWaves, max_split);
+        // (in-place form: a wave's row map lives in LDS, 32 tiles at most -- more splits instead)
+        if (!gathered) n_split = std::max<long>(n_split, (tiles32 + kWaves * 32 - 1) / (kWaves * 32));
         const int tpw = (int)((tiles32 + kWaves * n_split - 1) / (kWaves * n_split));
         n_split = (tiles32 + kWaves * tpw - 1) / (kWaves * tpw);
         p.n_split = (int)n_split;

@@ -92,28 +92,36 @@ __global__ __launch_bounds__(256, (QB == 1 ? 2 : 1)) void decode_split_kernel(
                             : (const char*)(Kmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
     const char* vbase = IND ? (const char*)(Vmix + (size_t)g * rm.kv_head)
                             : (const char*)(Vmix + ((size_t)b * n_kv_heads + g) * (size_t)l_cap * D);
-    const char* ksp_g = IND ? (const char*)(rm.Ksp + (size_t)g * rm.s_total * D) : nullptr;
-    const char* vsp_g = IND ? (const char*)(rm.Vsp + (size_t)g * rm.s_total * D) : nullptr;
+    const long long ksp_delta = IND ? (const char*)(rm.Ksp + (size_t)g * rm.s_total * D) - kbase : 0;
+    const long long vsp_delta = IND ? (const char*)(rm.Vsp + (size_t)g * rm.s_total * D) - vbase : 0;
     const int32_t* src_b = IND ? rm.src_idx + (size_t)b * l_cap : nullptr;
     const int ld_r = tid / (D / 8), ld_part = tid % (D / 8);
     TileRegs<D, C::VROW> tr;
     const int n_t = (k_hi - k_lo + kKeyTile - 1) / kKeyTile;
     // rows past the end of the split are clamped to its last row (scores masked, V finite)
-    auto fetch = [&](int key0_) {
-        const int rlim_ = min(kKeyTile - 1, k_hi - 1 - key0_);
-        if constexpr (IND)
-            tr.fetch_ind(src_b + key0_, kbase, vbase, ksp_g, vsp_g, rm.kv_tok * 2, ld_r, ld_part, rlim_);
-        else
-            tr.fetch(kbase + (size_t)key0_ * (D * 2), vbase + (size_t)key0_ * (D * 2), ld_r, ld_part, rlim_);
+    // IND: the rows of tile t are fetched through the map entries loaded one call earlier, and the
+    // entries of tile t + 1 (clamped to the last tile) are requested in the same call
+    auto load_map = [&](int key0_) {
+        tr.load_map(src_b + key0_, ld_r, min(kKeyTile - 1, k_hi - 1 - key0_));
     };
-    fetch(k_lo);
+    auto fetch = [&](int key0_, int key0_after_) {
+        const int rlim_ = min(kKeyTile - 1, k_hi - 1 - key0_);
+        if constexpr (IND) {
+            tr.fetch_mapped(kbase, vbase, ksp_delta, vsp_delta, rm.kv_tok * 2, ld_part);
+            load_map(key0_after_);
+        } else {
+            tr.fetch(kbase + (size_t)key0_ * (D * 2), vbase + (size_t)key0_ * (D * 2), ld_r, ld_part, rlim_);
+        }
+    };
+    if constexpr (IND) load_map(k_lo);
+    fetch(k_lo, k_lo + min(1, n_t - 1) * kKeyTile);
     tr.stage(Ks, Vs, ld_r, ld_part);
     __syncthreads();
     for (int ti = 0; ti < n_t; ++ti) {
         const int buf = ti & 1;
         const int key0 = k_lo + ti * kKeyTile;
         {   // next tile (the last iteration re-reads its own): unconditional, fenced, in flight below
-            fetch(k_lo + min(ti + 1, n_t - 1) * kKeyTile);
+            fetch(k_lo + min(ti + 1, n_t - 1) * kKeyTile, k_lo + min(ti + 2, n_t - 1) * kKeyTile);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (wave_active) {
@@ -358,11 +366,11 @@ __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
     // first hand-counted request), so that the requests depend on LDS reads only.
     __shared__ int32_t row_src[IND ? NW * kMaxStepTpw * TK : 1];
     int32_t* src_w = row_src + (IND ? wave * kMaxStepTpw * TK : 0);
-    const char* ksp_g = nullptr;
-    const char* vsp_g = nullptr;
+    // byte distances from the dense to the sparse buffers (one base per tensor keeps the addresses in registers)
+    const long long ksp_delta = IND ? (const char*)(rm.Ksp + (size_t)g * rm.s_total * D) - kbase : 0;
+    const long long vsp_delta = IND ? (const char*)(rm.Vsp + (size_t)g * rm.s_total * D) - vbase : 0;
+    const long long kv_tok_bytes = IND ? rm.kv_tok * 2 : 0;
     if constexpr (IND) {
-        ksp_g = (const char*)(rm.Ksp + (size_t)g * rm.s_total * D);
-        vsp_g = (const char*)(rm.Vsp + (size_t)g * rm.s_total * D);
         const int32_t* src_b = rm.src_idx + (size_t)b * l_cap;
         for (int i = 0; i < tiles_per_wave; ++i) {
             const int tile = tile0 + i * NW;
@@ -378,12 +386,27 @@ __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
     constexpr int PPR = D / 8, RPI = 64 / PPR, NL = TK / RPI;  // pieces per row; rows, 1 KiB lines per tile
     const uint32_t lds_w = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)Kw;
     // i_ = position of the tile among this wave's tiles (its row map is src_w + i_ * TK)
-    auto request = [&](int i_, int tile_, int buf) {
+    auto request = [&](int i_, int tile_, int buf) __attribute__((always_inline)) {
         const int key0_ = tile_ * TK;
         const int rlim_ = min(TK - 1, len - 1 - key0_);
         const char* kb = kbase + (size_t)key0_ * (D * 2);
         const char* vb = vbase + (size_t)key0_ * (D * 2);
         const int r_in = lane / PPR, pp = lane % PPR;
+        int src_row[NL];                                       // IND: source row of this lane's row in every load
+        if constexpr (IND) {
+            // rows x * RPI + r_in, clamped to the last valid one: a constant stride except at the clamp
+            const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(src_w + i_ * TK);
+            if (rlim_ == TK - 1) {
+                lds_read_i32_hidden<NL>(base + r_in * 4, RPI * 4, src_row);
+            } else {
+#pragma unroll
+                for (int x = 0; x < NL; ++x) {
+                    int one[1];
+                    lds_read_i32_hidden<1>(base + min(x * RPI + r_in, rlim_) * 4, 0, one);
+                    src_row[x] = one[0];
+                }
+            }
+        }
 #pragma unroll
         for (int x = 0; x < NL; ++x) {
             const int row = x * RPI + r_in;
@@ -393,10 +416,11 @@ __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
             const uint32_t kdst = lds_w + (uint32_t)buf * (4 * TILE_ELEMS) + x * 1024;
             const uint32_t vdst = kdst + 2 * TILE_ELEMS;
             if constexpr (IND) {
-                const int t = src_w[i_ * TK + min(row, rlim_)];
-                const size_t o = t >= 0 ? (size_t)t * (size_t)(rm.kv_tok * 2) : (size_t)(-1 - t) * (D * 2);
-                dma16_addr((t >= 0 ? kbase : ksp_g) + o + kp * 16, kdst);
-                dma16_addr((t >= 0 ? vbase : vsp_g) + o + vp * 16, vdst);
+                const int t = src_row[x];
+                const long long ko = t >= 0 ? (long long)t * kv_tok_bytes : ksp_delta + (long long)(-1 - t) * (D * 2);
+                const long long vo = t >= 0 ? (long long)t * kv_tok_bytes : vsp_delta + (long long)(-1 - t) * (D * 2);
+                dma16_addr(kbase + ko + kp * 16, kdst);
+                dma16_addr(vbase + vo + vp * 16, vdst);
             } else {
                 const uint32_t roff = (uint32_t)min(row, rlim_) * (D * 2);
                 dma16(kb, roff + kp * 16, kdst);

@@ -75,22 +75,31 @@ struct TileRegs {
     }
     // The same for rows reached through a row map: tile row r is token src[r] of the dense tensors
     // (rows kv_tok_bytes apart from kd / vd) or, if src[r] < 0, row -1 - src[r] of the sparse
-    // buffers ks / vs (rows D * 2 bytes apart).  src points at the tile's first entry.
-    __device__ __forceinline__ void fetch_ind(const int32_t* src, const char* kd, const char* vd, const char* ks,
-                                              const char* vs, long long kv_tok_bytes, int ld_r, int ld_part,
-                                              int rlim) {
-#define VXL_TILE_ROW(i_, k_, v_)                                                                      \
-        do {                                                                                          \
-            const int t_ = src[min(ld_r + (i_) * RPP, rlim)];                                         \
-            const size_t o_ = t_ >= 0 ? (size_t)t_ * kv_tok_bytes : (size_t)(-1 - t_) * (D * 2);      \
-            k_ = *(const uint4*)((t_ >= 0 ? kd : ks) + o_ + ld_part * 16);                            \
-            v_ = *(const uint4*)((t_ >= 0 ? vd : vs) + o_ + ld_part * 16);                            \
-        } while (0)
-        VXL_TILE_ROW(0, k0, v0);
-        VXL_TILE_ROW(1, k1, v1);
+    // buffers (rows D * 2 bytes apart, ks_delta / vs_delta bytes from kd / vd).  The map entries of a
+    // tile are requested one tile before its rows (load_map), so that the two dependent loads of a
+    // row do not both fall into one tile's arithmetic.  src points at the tile's first entry.
+    int m0_, m1_, m2_, m3_;
+    __device__ __forceinline__ void load_map(const int32_t* src, int ld_r, int rlim) {
+        m0_ = src[min(ld_r, rlim)];
+        m1_ = src[min(ld_r + RPP, rlim)];
         if constexpr (LD > 2) {
-            VXL_TILE_ROW(2, k2, v2);
-            VXL_TILE_ROW(3, k3, v3);
+            m2_ = src[min(ld_r + 2 * RPP, rlim)];
+            m3_ = src[min(ld_r + 3 * RPP, rlim)];
+        }
+    }
+    __device__ __forceinline__ void fetch_mapped(const char* kd, const char* vd, long long ks_delta,
+                                                 long long vs_delta, long long kv_tok_bytes, int ld_part) {
+#define VXL_TILE_ROW(t_, k_, v_)                                                                      \
+        do {                                                                                          \
+            const long long r_ = (t_) >= 0 ? (long long)(t_) * kv_tok_bytes : (long long)(-1 - (t_)) * (D * 2); \
+            k_ = *(const uint4*)(kd + ((t_) >= 0 ? 0 : ks_delta) + r_ + ld_part * 16);                \
+            v_ = *(const uint4*)(vd + ((t_) >= 0 ? 0 : vs_delta) + r_ + ld_part * 16);                \
+        } while (0)
+        VXL_TILE_ROW(m0_, k0, v0);
+        VXL_TILE_ROW(m1_, k1, v1);
+        if constexpr (LD > 2) {
+            VXL_TILE_ROW(m2_, k2, v2);
+            VXL_TILE_ROW(m3_, k3, v3);
         }
 #undef VXL_TILE_ROW
     }
@@ -306,6 +315,19 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t l
 __device__ __forceinline__ void dma16_addr(const void* addr, uint32_t lds_off) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                  :: "s"(lds_off), "v"(addr) : "memory");
+}
+
+// N 32-bit LDS reads issued and awaited inside inline assembly.  For kernels that keep their own
+// vmcnt count: an LDS read the compiler can see, placed after a hand-issued direct load (whose
+// statement clobbers memory), makes it wait for vmcnt(0) first, which empties the ring.
+template <int N>
+__device__ __forceinline__ void lds_read_i32_hidden(uint32_t byte_addr, uint32_t stride_bytes, int (&v)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+        asm volatile("ds_read_b32 %0, %1" : "=v"(v[i]) : "v"(byte_addr + i * stride_bytes) : "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(v[i]));       // uses stay behind the wait
 }
 
 // O^T[qb][db] += V^T . P^T over the 64 keys of the tile.
