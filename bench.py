@@ -345,8 +345,38 @@ def measure_attained_peaks(torch, vxl):
     b.record()
     torch.cuda.synchronize()
     copy = 10 * 2.0 * src.numel() * 4 / (a.elapsed_time(b) * 1e-3) / 1e9
-    return {"mfma_bf16_stream_TFLOPs": mfma, "mfma_frac_of_published": mfma / PEAK_BF16_TFLOPS,
-            "copy_1GiB_GBps_read_plus_write": copy, "copy_frac_of_published": copy / PEAK_HBM_GBS}
+    res = {"mfma_bf16_stream_TFLOPs": mfma, "mfma_frac_of_published": mfma / PEAK_BF16_TFLOPS,
+           "copy_1GiB_GBps_read_plus_write": copy, "copy_frac_of_published": copy / PEAK_HBM_GBS}
+    # a bare streaming read of one decode call's KV bytes (config1 / config3 layer / config2 / 1 GiB), launches
+    # replayed from a graph over distinct regions of a 4 GiB buffer: the floor of a split-KV kernel
+    del dst
+    big = torch.empty(1 << 30, dtype=torch.float32, device="cuda")          # 4 GiB
+    big.normal_()
+    sink = torch.empty((n_cu * 4 * 256,), dtype=torch.float32, device="cuda")
+    for tag, nbytes in (("8MB", 8388608), ("37MB", 37224448), ("49MB", 48758784), ("1GiB", 1 << 30)):
+        n_reg = max(1, min(64, (4 << 30) // nbytes))
+        views = [big.view(torch.uint8)[i * nbytes:(i + 1) * nbytes] for i in range(n_reg)]
+        best = None
+        for wgs in (n_cu, 2 * n_cu, 4 * n_cu):
+            for v in views[:2]:
+                vxl.debug_read_stream(v, nbytes, sink, wgs)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for v in views:
+                    vxl.debug_read_stream(v, nbytes, sink, wgs)
+            graph.replay()
+            torch.cuda.synchronize()
+            a.record()
+            graph.replay()
+            b.record()
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) * 1e3 / n_reg
+            if best is None or us < best[0]:
+                best = (us, wgs)
+        res[f"read_stream_{tag}"] = {"us": best[0], "GBps": nbytes / best[0] / 1e3,
+                                     "frac_of_published": nbytes / best[0] / 1e3 / PEAK_HBM_GBS, "workgroups": best[1]}
+    return res
 
 
 def measure_widening(torch, vxl, wl, w):

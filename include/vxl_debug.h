@@ -9,6 +9,8 @@
 #ifndef VXL_DEBUG_H
 #define VXL_DEBUG_H
 
+#include <stddef.h>
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -38,6 +40,12 @@ void vxl_debug_prefill_events(void* start_event, void* stop_event);
  * peak.  out: device float [n_workgroups * 512].  Returns the floating-point operations
  * launched, 0 on a bad argument or a failed launch. */
 double vxl_debug_mfma_stream(float* out, int n_workgroups, int iters, void* stream);
+
+/* Launches a bare streaming read of `bytes` (a multiple of 16) of device memory at `src` by
+ * `n_workgroups` workgroups of 256 threads on `stream`; out: device float [n_workgroups * 256].
+ * What a bandwidth-bound kernel could at best take for a buffer of that size.  Returns a
+ * vxl_status value (0 = launched). */
+int vxl_debug_read_stream(const void* src, size_t bytes, float* out, int n_workgroups, void* stream);
 
 #ifdef __cplusplus
 }

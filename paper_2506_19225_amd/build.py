@@ -13,7 +13,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libvxl.so")
 
-SOURCES = ["vxl_api.hip", "vxl_simple.hip", "vxl_bilevel.hip", "vxl_prefill.hip", "vxl_decode.hip", "vxl_mass.hip", "vxl_store.hip"]
+SOURCES = ["vxl_api.hip", "vxl_simple.hip", "vxl_bilevel.hip", "vxl_prefill.hip", "vxl_decode.hip", "vxl_mass.hip", "vxl_store.hip", "vxl_debug.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=default",

@@ -389,41 +389,6 @@ static vxl_status run_prefill_dma(const vxl_layout* L, const vxl_attn_desc* d, f
     return VXL_OK;
 }
 
-// Measurement only: a register-resident stream of the matrix instruction the kernels use (four
-// independent accumulators per wave, 8 waves per workgroup, one workgroup per compute unit,
-// `iters` x 4 instructions per wave), for reading kernel rates against an attained peak.
-namespace {
-__global__ __launch_bounds__(512, 2) void mfma_stream_kernel(float* __restrict__ out, int iters, float seed) {
-    f32x16 acc[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) acc[i] = zero16();
-    bf16x8 a, b;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        a[e] = (__bf16)(seed + (float)e);
-        b[e] = (__bf16)(seed * 0.5f + (float)(threadIdx.x & 7));
-    }
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int m = 0; m < 4; ++m) acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[m], 0, 0, 0);
-    }
-    float t = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) t += acc[i][r];
-    out[(size_t)blockIdx.x * 512 + threadIdx.x] = t;
-}
-}  // namespace
-// out: device float [n_workgroups * 512]; returns the number of floating-point operations launched
-// (0 on a bad argument).
-extern "C" double vxl_debug_mfma_stream(float* out, int n_workgroups, int iters, void* stream) {
-    if (!out || n_workgroups <= 0 || iters <= 0) return 0.0;
-    hipLaunchKernelGGL(mfma_stream_kernel, dim3(n_workgroups), dim3(512), 0, (hipStream_t)stream, out, iters, 1.0f);
-    if (hipGetLastError() != hipSuccess) return 0.0;
-    return (double)n_workgroups * 8.0 * iters * 4.0 * 2.0 * 32 * 32 * 16;
-}
-
 vxl_status device_cu_count(int* n_cus) {
     static std::mutex mu;
     static int count[kMaxDevices] = {};

@@ -99,6 +99,8 @@ def lib() -> C.CDLL:
     L.vxl_debug_decode_step_waves.argtypes = [C.c_int]
     L.vxl_debug_mfma_stream.argtypes = [vp, C.c_int, C.c_int, vp]
     L.vxl_debug_mfma_stream.restype = C.c_double
+    L.vxl_debug_read_stream.argtypes = [vp, sz, vp, C.c_int, vp]
+    L.vxl_debug_read_stream.restype = C.c_int
     _lib = L
     return L
 
@@ -333,6 +335,12 @@ def debug_force_simple(on: bool) -> None:
 def debug_mfma_stream(out, n_workgroups: int, iters: int, stream=None) -> float:
     """Measurement only: launches a register-resident matrix-instruction stream; returns its FLOP count."""
     return float(lib().vxl_debug_mfma_stream(_ptr(out), int(n_workgroups), int(iters), _stream(stream)))
+
+
+def debug_read_stream(src, nbytes: int, out, n_workgroups: int, stream=None) -> None:
+    """Measurement only: a bare streaming read of the first nbytes of `src` (out: float32 [n_workgroups*256])."""
+    _check(lib().vxl_debug_read_stream(_ptr(src), int(nbytes), _ptr(out), int(n_workgroups), _stream(stream)),
+           "vxl_debug_read_stream")
 
 
 def debug_decode_step_waves(waves: int) -> None:
