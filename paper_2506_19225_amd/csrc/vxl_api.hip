@@ -360,10 +360,11 @@ size_t vxl_workspace_bytes(vxl_op op, const vxl_layout* L, const vxl_attn_desc* 
         case VXL_OP_PREFILL:
             if (!L) return 0;
             return std::max<size_t>(256, prefill_workspace(L, d).total);
-        case VXL_OP_SCORE_TOPK:     // mean queries [B][Hkv][D], then mean keys [Hkv][C][D] (used when no cache is given)
+        case VXL_OP_SCORE_TOPK:     // mean queries [B][Hkv][D], mean keys [Hkv][C][D] (used when no cache is given), scores [B][C]
             if (!L || batch <= 0) return 0;
             return align_up((size_t)batch * d->n_kv_heads * d->head_dim * 4, 256) +
-                   align_up((size_t)d->n_kv_heads * std::max(1, L->n_chunks) * d->head_dim * 4, 256);
+                   align_up((size_t)d->n_kv_heads * std::max(1, L->n_chunks) * d->head_dim * 4, 256) +
+                   align_up((size_t)batch * std::max(1, L->n_chunks) * 4, 256);
         case VXL_OP_GATHER:          // the gather keeps its per-query offsets in LDS: no workspace
             return 0;
         case VXL_OP_DECODE:
@@ -415,11 +416,13 @@ vxl_status vxl_chunk_score_topk(const vxl_layout* L, const vxl_attn_desc* d, con
     const size_t need = vxl_workspace_bytes(VXL_OP_SCORE_TOPK, L, d, batch, n_q_tokens, 0);
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return VXL_ERR_WORKSPACE;
     float* qbar = (float*)workspace;
-    float* kb = kbar ? kbar : (float*)((char*)workspace + align_up((size_t)batch * d->n_kv_heads * d->head_dim * 4, 256));
+    const size_t o_kbar = align_up((size_t)batch * d->n_kv_heads * d->head_dim * 4, 256);
+    const size_t o_sc = o_kbar + align_up((size_t)d->n_kv_heads * std::max(1, L->n_chunks) * d->head_dim * 4, 256);
+    float* kb = kbar ? kbar : (float*)((char*)workspace + o_kbar);
     st = launch_summaries(L, d, K, kb, !kbar_ready, Qd, batch, n_q_tokens, qbar, (hipStream_t)stream);
     if (st != VXL_OK) return st;
     return launch_score_topk(L, d, resolve_scale(d), batch, kk, qbar, kb, topk_idx, dense_mask, scores,
-                             (hipStream_t)stream);
+                             (float*)((char*)workspace + o_sc), (hipStream_t)stream);
 }
 
 vxl_status vxl_chunk_score_topk_mass(const vxl_layout* L, const vxl_attn_desc* d, const void* Qd,

@@ -139,12 +139,13 @@ __device__ __forceinline__ bool ranks_before(float sa, int ia, float sb, int ib)
 __device__ __forceinline__ void sort_select(float* s_val, int* s_idx, int n_sort, int n_chunks, int k, int b,
                                             int32_t* __restrict__ topk_idx, uint8_t* __restrict__ dense_mask) {
     const int tid = threadIdx.x;
-    if (n_sort <= 256) {
-        // Few chunks: every thread ranks one chunk by counting the chunks that come before it in
-        // the order (score descending, id ascending) -- a total order, so the ranks are a permutation
-        // -- instead of the barrier-per-step sort below.
-        const int c = tid;
-        if (c < n_chunks) {
+    if (n_sort <= 1024) {
+        // Up to 1024 chunks: every thread ranks its chunks (tid, tid + 256, ...) by counting the
+        // chunks that come before them in the order (score descending, id ascending) -- a total
+        // order, so the ranks are a permutation -- instead of the barrier-per-step sort below
+        // (n^2 / 256 comparisons per thread: 4 us at 640 chunks, where the 55 barrier steps of
+        // the sort took 25).
+        for (int c = tid; c < n_chunks; c += 256) {
             const float sc = s_val[c];
             int rank = 0;
             for (int o = 0; o < n_chunks; ++o) rank += ranks_before(s_val[o], o, sc, c) ? 1 : 0;
@@ -180,6 +181,38 @@ __device__ __forceinline__ void sort_select(float* s_val, int* s_idx, int n_sort
     }
     __syncthreads();
     for (int c = tid; c < n_chunks; c += 256) dense_mask[(size_t)b * n_chunks + c] = (uint8_t)flag[c];
+}
+
+// The scores alone, 32 chunks per block (grid: chunk groups x queries): the same lanes, slices and
+// add tree as score_topk_kernel, so a chunk's score does not depend on which of the two computed it.
+template <int D>
+__global__ __launch_bounds__(256) void chunk_score_kernel(const float* __restrict__ qbar_g,
+                                                          const float* __restrict__ kbar, int n_kv_heads,
+                                                          int n_chunks, float scale, float* __restrict__ scores) {
+    extern __shared__ unsigned char smem[];
+    float* qbar = (float*)smem;                               // [Hkv][D]
+    const int b = blockIdx.y, tid = threadIdx.x;
+    for (int e = tid; e < n_kv_heads * D; e += 256) qbar[e] = qbar_g[(size_t)b * n_kv_heads * D + e];
+    __syncthreads();
+    const int part = tid & 7, c = blockIdx.x * 32 + (tid >> 3);
+    const int slice = n_kv_heads * D / 8;
+    float a0 = 0.f;
+    if (c < n_chunks) {
+#pragma unroll 8
+        for (int x = 0; x < slice; x += 4) {
+            const int e = part * slice + x, g = e / D, dd = e % D;
+            const float4 kv = *(const float4*)(kbar + ((size_t)g * n_chunks + c) * D + dd);
+            const float* qg = qbar + e;
+            a0 = fmaf(qg[0], kv.x, a0);
+            a0 = fmaf(qg[1], kv.y, a0);
+            a0 = fmaf(qg[2], kv.z, a0);
+            a0 = fmaf(qg[3], kv.w, a0);
+        }
+    }
+    a0 += __shfl_xor(a0, 1);
+    a0 += __shfl_xor(a0, 2);
+    a0 += __shfl_xor(a0, 4);
+    if (part == 0 && c < n_chunks) scores[(size_t)b * n_chunks + c] = a0 * (scale / (float)n_kv_heads);
 }
 
 template <int D>
@@ -424,9 +457,24 @@ vxl_status launch_summaries(const vxl_layout* L, const vxl_attn_desc* d, const v
 
 vxl_status launch_score_topk(const vxl_layout* L, const vxl_attn_desc* d, float scale, int batch, int k,
                              const float* qbar, const float* kbar, int32_t* topk_idx, uint8_t* dense_mask,
-                             float* scores, hipStream_t s) {
+                             float* scores, float* scores_ws, hipStream_t s) {
     int n_sort = 2;
     while (n_sort < L->n_chunks) n_sort <<= 1;
+    // Beyond 128 chunks one block per query is a serial chain (90 us at 640 chunks): the scores are
+    // then formed by 32 chunks per block and the selection reads them back.
+    if (L->n_chunks > 128) {
+        float* sc = scores ? scores : scores_ws;
+        const size_t smem_q = (size_t)d->n_kv_heads * d->head_dim * 4;
+        const dim3 grid((L->n_chunks + 31) / 32, batch);
+        if (d->head_dim == 64)
+            hipLaunchKernelGGL((chunk_score_kernel<64>), grid, dim3(256), smem_q, s, qbar, kbar, d->n_kv_heads,
+                               L->n_chunks, scale, sc);
+        else
+            hipLaunchKernelGGL((chunk_score_kernel<128>), grid, dim3(256), smem_q, s, qbar, kbar, d->n_kv_heads,
+                               L->n_chunks, scale, sc);
+        VXL_HIP_TRY(hipGetLastError());
+        return launch_topk_from_scores(L, sc, batch, k, topk_idx, dense_mask, s);
+    }
     const size_t smem = (size_t)d->n_kv_heads * d->head_dim * 4 + (size_t)n_sort * 8;
     if (smem > 64 * 1024) return VXL_ERR_UNSUPPORTED;
     const dim3 grid(batch), block(256);

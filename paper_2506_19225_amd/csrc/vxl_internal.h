@@ -143,7 +143,7 @@ vxl_status launch_summaries(const vxl_layout* L, const vxl_attn_desc* d, const v
                             bool do_chunks, const void* Qd, int batch, int T, float* qbar, hipStream_t s);
 vxl_status launch_score_topk(const vxl_layout* L, const vxl_attn_desc* d, float scale, int batch, int k,
                              const float* qbar, const float* kbar, int32_t* topk_idx, uint8_t* dense_mask,
-                             float* scores, hipStream_t s);
+                             float* scores, float* scores_ws /*[B][C], used when scores is null*/, hipStream_t s);
 vxl_status launch_topk_from_scores(const vxl_layout* L, const float* scores, int batch, int k,
                                    int32_t* topk_idx, uint8_t* dense_mask, hipStream_t s);
 
