@@ -373,23 +373,36 @@ __global__ __launch_bounds__(256) void gather_kernel(
     const uint8_t* mask = dense_mask + (size_t)b * n_chunks;
     if (tid == 0) carry = n_prefix;
     __syncthreads();
-    for (int base = 0; base < n_chunks; base += 256) {
-        const int c = base + tid;
-        int v = 0;
-        if (c < n_chunks) v = mask[c] ? bounds[c + 1] - bounds[c] : soff[c + 1] - soff[c];
-        int inc = v;                                          // inclusive scan inside the wave
-        for (int o = 1; o < 64; o <<= 1) {
-            const int t = __shfl_up(inc, o);
-            if (lane >= o) inc += t;
+    // The rows every chunk contributes, four 256-chunk passes at a time: their loads are all
+    // requested before the first scan (one memory round trip per 1024 chunks, not per 256).
+    for (int base4 = 0; base4 < n_chunks; base4 += 1024) {
+        int v4[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = base4 + u * 256 + tid;
+            v4[u] = 0;
+            if (c < n_chunks) v4[u] = mask[c] ? bounds[c + 1] - bounds[c] : soff[c + 1] - soff[c];
         }
-        if (lane == 63) wave_tot[wave] = inc;
-        __syncthreads();
-        int before = carry;
-        for (int w = 0; w < wave; ++w) before += wave_tot[w];
-        if (c < n_chunks) off[c] = before + inc - v;
-        __syncthreads();
-        if (tid == 0) carry += wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
-        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int base = base4 + u * 256;
+            if (base >= n_chunks) break;                      // (uniform)
+            const int c = base + tid;
+            const int v = v4[u];
+            int inc = v;                                      // inclusive scan inside the wave
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(inc, o);
+                if (lane >= o) inc += t;
+            }
+            if (lane == 63) wave_tot[wave] = inc;
+            __syncthreads();
+            int before = carry;
+            for (int w = 0; w < wave; ++w) before += wave_tot[w];
+            if (c < n_chunks) off[c] = before + inc - v;
+            __syncthreads();
+            if (tid == 0) carry += wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+            __syncthreads();
+        }
     }
     if (tid == 0) {
         off[n_chunks] = carry;
