@@ -75,7 +75,7 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap, bool
     // chip; at short mixed sets the split cap below leaves it a fraction of the compute units
     // (measured at 224 rows: 64 and 120 workgroups, 4-wave kernel 9 % and 5 % faster; 176 and
     // 256 workgroups, ring kernel 5 % and 8 % faster).
-    bool ring = gathered && rows > 128;
+    bool ring = rows > 128;
     if (ring && rows <= 256) {
         const long blocks = (long)batch * d->n_kv_heads;
         const long splits = std::max<long>(1, std::min<long>(std::min<long>((256 + blocks - 1) / blocks, (long)l_cap / rows), tiles));

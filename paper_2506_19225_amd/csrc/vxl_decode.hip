@@ -193,11 +193,15 @@ struct DecodeRingCfg {
     static constexpr int GROUP = 2 * IPW;                     // loads per wave per tile (K and V)
 };
 
-template <int D, int NS>
+// IND (in-place form): the rows of a tile are reached through the row map.  A lane needs one map
+// entry per load slot and tile; the entries of tiles t+2, t+3 are fetched (by loads issued from
+// inline assembly, so that they ride in the hand-kept vmcnt count) when the loads of tiles t, t+1 are
+// issued, and are complete behind the same vmcnt(0) that tiles t, t+1 wait for.
+template <int D, int NS, bool IND = false>
 __global__ __launch_bounds__(512, 2) void decode_ring_kernel(
     const uint16_t* __restrict__ Qd, const uint16_t* __restrict__ Kmix, const uint16_t* __restrict__ Vmix,
     const int32_t* __restrict__ mix_len, float* __restrict__ part_o, float* __restrict__ part_lse, int T_q,
-    int n_q_heads, int n_kv_heads, int group, int l_cap, int n_rtile, int split_len, float scale) {
+    int n_q_heads, int n_kv_heads, int group, int l_cap, int n_rtile, int split_len, float scale, RowMap rm) {
     using C = DecodeRingCfg<D, NS>;
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
@@ -220,13 +224,29 @@ __global__ __launch_bounds__(512, 2) void decode_ring_kernel(
         return;
     }
     const int n_t = (k_hi - k_lo + kKeyTile - 1) / kKeyTile;
-    const char* kbase = (const char*)(Kmix + (((size_t)b * n_kv_heads + g) * (size_t)l_cap + k_lo) * D);
-    const char* vbase = (const char*)(Vmix + (((size_t)b * n_kv_heads + g) * (size_t)l_cap + k_lo) * D);
+    // (IND: Kmix / Vmix are the dense K / V of the layer)
+    const char* kbase = IND ? (const char*)(Kmix + (size_t)g * rm.kv_head)
+                            : (const char*)(Kmix + (((size_t)b * n_kv_heads + g) * (size_t)l_cap + k_lo) * D);
+    const char* vbase = IND ? (const char*)(Vmix + (size_t)g * rm.kv_head)
+                            : (const char*)(Vmix + (((size_t)b * n_kv_heads + g) * (size_t)l_cap + k_lo) * D);
+    const long long ksp_delta = IND ? (const char*)(rm.Ksp + (size_t)g * rm.s_total * D) - kbase : 0;
+    const long long vsp_delta = IND ? (const char*)(rm.Vsp + (size_t)g * rm.s_total * D) - vbase : 0;
+    const long long kv_tok_bytes = IND ? rm.kv_tok * 2 : 0;
+    const int32_t* src_s = IND ? rm.src_idx + (size_t)b * l_cap + k_lo : nullptr;      // map entries of this split
     const int r_in = lane / C::PPR, pp = lane % C::PPR;
 
+    // IND: map entries of this lane's load slots for one tile
+    struct TileMap { int e[C::IPW]; };
+    auto load_map = [&](int t, TileMap& m) __attribute__((always_inline)) {
+        const int row0 = t * kKeyTile;
+        const int rlim = min(kKeyTile - 1, k_hi - k_lo - 1 - row0);
+#pragma unroll
+        for (int i = 0; i < C::IPW; ++i)
+            m.e[i] = load_i32_hidden(src_s + row0 + min((wave + i * C::WAVES) * C::RPI + r_in, rlim));
+    };
     // Tile t -> stage t % NS.  Every wave issues GROUP loads: instruction slots wave, wave + 8, ...
     // Rows past the end of the split are clamped to its last row (scores masked, V finite).
-    auto issue = [&](int t) {
+    auto issue = [&](int t, const TileMap& m) __attribute__((always_inline)) {
         const int row0 = t * kKeyTile;
         const int rlim = min(kKeyTile - 1, k_hi - k_lo - 1 - row0);
         const char* kb = kbase + (size_t)row0 * (D * 2);
@@ -236,20 +256,39 @@ __global__ __launch_bounds__(512, 2) void decode_ring_kernel(
         for (int i = 0; i < C::IPW; ++i) {
             const int slot = wave + i * C::WAVES;
             const int row = slot * C::RPI + r_in;
-            const uint32_t roff = (uint32_t)min(row, rlim) * (D * 2);
             const int kp = pp ^ ((row / (16 / C::PPR)) & (C::PPR - 1));
             constexpr int CPR = D * 2 / 64, RPL = D == 128 ? 1 : 2;
             const int vp = (((pp >> 2) ^ ((row / RPL) & (CPR - 1))) << 2) | (pp & 3);
-            dma16(kb, roff + kp * 16, st + slot * 1024);
-            dma16(vb, roff + vp * 16, st + C::TILE * 2 + slot * 1024);
+            if constexpr (IND) {
+                const long long ko = mapped_row_offset(m.e[i], kv_tok_bytes, D * 2, ksp_delta);
+                const long long vo = mapped_row_offset(m.e[i], kv_tok_bytes, D * 2, vsp_delta);
+                dma16_addr(kbase + ko + kp * 16, st + slot * 1024);
+                dma16_addr(vbase + vo + vp * 16, st + C::TILE * 2 + slot * 1024);
+            } else {
+                const uint32_t roff = (uint32_t)min(row, rlim) * (D * 2);
+                dma16(kb, roff + kp * 16, st + slot * 1024);
+                dma16(vb, roff + vp * 16, st + C::TILE * 2 + slot * 1024);
+            }
         }
     };
     // Two groups of TPB stages: one is consumed while the other is refilled, one workgroup barrier
     // per TPB tiles.
     constexpr int TPB = 2;
     static_assert(NS == 2 * TPB, "two groups of TPB stages");
+    TileMap ma{}, mb{};                                       // entries of the next two tiles to be issued
+    if constexpr (IND) {
+        load_map(0, ma);
+        load_map(min(1, n_t - 1), mb);
+        wait_vmcnt<0>();
 #pragma unroll
-    for (int t = 0; t < TPB; ++t) issue(min(t, n_t - 1));
+        for (int i = 0; i < C::IPW; ++i) { settle_i32(ma.e[i]); settle_i32(mb.e[i]); }
+    }
+    issue(0, ma);
+    issue(min(1, n_t - 1), mb);
+    if constexpr (IND) {                                      // entries of tiles 2, 3: complete behind the first meeting's wait
+        load_map(min(2, n_t - 1), ma);
+        load_map(min(3, n_t - 1), mb);
+    }
 
     // Query rows: loaded after the ring has been started (the latencies overlap) and forced
     // complete here; from here on no load the compiler knows of is outstanding.
@@ -295,9 +334,15 @@ __global__ __launch_bounds__(512, 2) void decode_ring_kernel(
     for (int t0 = 0; t0 < n_t; t0 += TPB) {
         wait_vmcnt<0>();                                      // this wave's parts of tiles t0, t0+1 have landed
         __builtin_amdgcn_s_barrier();                         // ... and everyone's; the other group is free
-        issue(min(t0 + TPB, n_t - 1));
+        if constexpr (IND) {
+#pragma unroll
+            for (int i = 0; i < C::IPW; ++i) { settle_i32(ma.e[i]); settle_i32(mb.e[i]); }
+        }
+        issue(min(t0 + TPB, n_t - 1), ma);
+        if constexpr (IND) load_map(min(t0 + 2 * TPB, n_t - 1), ma);
         process(t0);
-        issue(min(t0 + TPB + 1, n_t - 1));
+        issue(min(t0 + TPB + 1, n_t - 1), mb);
+        if constexpr (IND) load_map(min(t0 + 2 * TPB + 1, n_t - 1), mb);
         if (t0 + 1 < n_t) process(t0 + 1);
     }
     wait_vmcnt<0>();                                          // drain the refills before the wave ends
@@ -416,9 +461,8 @@ __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
             const uint32_t kdst = lds_w + (uint32_t)buf * (4 * TILE_ELEMS) + x * 1024;
             const uint32_t vdst = kdst + 2 * TILE_ELEMS;
             if constexpr (IND) {
-                const int t = src_row[x];
-                const long long ko = t >= 0 ? (long long)t * kv_tok_bytes : ksp_delta + (long long)(-1 - t) * (D * 2);
-                const long long vo = t >= 0 ? (long long)t * kv_tok_bytes : vsp_delta + (long long)(-1 - t) * (D * 2);
+                const long long ko = mapped_row_offset(src_row[x], kv_tok_bytes, D * 2, ksp_delta);
+                const long long vo = mapped_row_offset(src_row[x], kv_tok_bytes, D * 2, vsp_delta);
                 dma16_addr(kbase + ko + kp * 16, kdst);
                 dma16_addr(vbase + vo + vp * 16, vdst);
             } else {
@@ -671,9 +715,9 @@ static vxl_status run_decode(const vxl_attn_desc* d, float scale, const void* Qd
 template <int D>
 static vxl_status run_decode_ring(const vxl_attn_desc* d, float scale, const void* Qd, int batch, int T,
                                   const void* Kmix, const void* Vmix, int l_cap, const int32_t* mix_len, void* O,
-                                  float* LSE, void* ws, hipStream_t s) {
+                                  float* LSE, void* ws, hipStream_t s, const RowMap* rm = nullptr) {
     using C = DecodeRingCfg<D, 4>;
-    const DecodePlan p = decode_plan(d, batch, T, l_cap);
+    const DecodePlan p = decode_plan(d, batch, T, l_cap, rm == nullptr);
     float* part_o = (float*)((char*)ws + p.part_o);
     float* part_lse = (float*)((char*)ws + p.part_ml);
     const int group = d->n_q_heads / d->n_kv_heads;
@@ -681,15 +725,23 @@ static vxl_status run_decode_ring(const vxl_attn_desc* d, float scale, const voi
     const int n_rtile = (n_rows + C::RT - 1) / C::RT;
     static PerDeviceOnce attr;
     const vxl_status ast = attr.run([] {
-        VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_ring_kernel<D, 4>,
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_ring_kernel<D, 4, false>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)decode_ring_kernel<D, 4, true>,
                                         hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
         return VXL_OK;
     });
     if (ast != VXL_OK) return ast;
-    hipLaunchKernelGGL((decode_ring_kernel<D, 4>), dim3(p.n_split, n_rtile * d->n_kv_heads, batch), dim3(512),
-                       C::LDS_BYTES, s, (const uint16_t*)Qd, (const uint16_t*)Kmix, (const uint16_t*)Vmix,
-                       mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group, l_cap, n_rtile,
-                       p.split_len, scale);
+    if (rm)
+        hipLaunchKernelGGL((decode_ring_kernel<D, 4, true>), dim3(p.n_split, n_rtile * d->n_kv_heads, batch),
+                           dim3(512), C::LDS_BYTES, s, (const uint16_t*)Qd, (const uint16_t*)Kmix,
+                           (const uint16_t*)Vmix, mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group,
+                           l_cap, n_rtile, p.split_len, scale, *rm);
+    else
+        hipLaunchKernelGGL((decode_ring_kernel<D, 4, false>), dim3(p.n_split, n_rtile * d->n_kv_heads, batch),
+                           dim3(512), C::LDS_BYTES, s, (const uint16_t*)Qd, (const uint16_t*)Kmix,
+                           (const uint16_t*)Vmix, mix_len, part_o, part_lse, T, d->n_q_heads, d->n_kv_heads, group,
+                           l_cap, n_rtile, p.split_len, scale, RowMap{});
     VXL_HIP_TRY(hipGetLastError());
     const size_t merge_lds = (size_t)(((p.n_split + 3) & ~3) + 256 / (D / 4) * D) * sizeof(float);
     hipLaunchKernelGGL((decode_merge_kernel<D>), dim3(n_rows, d->n_kv_heads, batch), dim3(256), merge_lds, s,
@@ -794,8 +846,12 @@ vxl_status launch_decode_bf16_inplace(const vxl_layout* L, const vxl_attn_desc* 
         return d->head_dim == 128
                    ? run_decode_wave<128>(d, scale, Qd, batch, T, K, V, l_cap, mix_len, O, LSE, ws, s, &rm)
                    : run_decode_wave<64>(d, scale, Qd, batch, T, K, V, l_cap, mix_len, O, LSE, ws, s, &rm);
-    return d->head_dim == 128 ? run_decode<128, 1>(d, scale, Qd, batch, T, K, V, l_cap, mix_len, O, LSE, ws, s, &rm)
-                              : run_decode<64, 1>(d, scale, Qd, batch, T, K, V, l_cap, mix_len, O, LSE, ws, s, &rm);
+    const bool big = decode_plan(d, batch, T, l_cap, false).use_ring != 0;
+    if (d->head_dim == 128)
+        return big ? run_decode_ring<128>(d, scale, Qd, batch, T, K, V, l_cap, mix_len, O, LSE, ws, s, &rm)
+                   : run_decode<128, 1>(d, scale, Qd, batch, T, K, V, l_cap, mix_len, O, LSE, ws, s, &rm);
+    return big ? run_decode_ring<64>(d, scale, Qd, batch, T, K, V, l_cap, mix_len, O, LSE, ws, s, &rm)
+               : run_decode<64, 1>(d, scale, Qd, batch, T, K, V, l_cap, mix_len, O, LSE, ws, s, &rm);
 }
 
 }  // namespace vxl

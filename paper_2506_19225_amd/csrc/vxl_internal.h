@@ -176,7 +176,7 @@ struct DecodePlan {
     size_t part_ml;
     size_t total;
 };
-// gathered = false plans the in-place form (no 256-row ring kernel, always the 4-wave step kernel)
+// gathered = false plans the in-place form (always the 4-wave step kernel, splits bounded by its row-map area)
 DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap, bool gathered = true);
 
 struct InplaceWorkspace {      // byte offsets into the caller's workspace (vxl_bilevel_decode_inplace)

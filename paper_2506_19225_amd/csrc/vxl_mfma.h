@@ -317,6 +317,26 @@ __device__ __forceinline__ void dma16_addr(const void* addr, uint32_t lds_off) {
                  :: "s"(lds_off), "v"(addr) : "memory");
 }
 
+// Byte offset (from the dense K or V base of the KV head) of the row a map entry names: entry e >= 0
+// is dense token e (rows tok_bytes apart); e < 0 is row -1 - e of the sparse buffer, which starts
+// sp_delta bytes from the dense base (rows row_bytes apart).  One multiplication and two selects, so
+// that a per-lane mix of the two kinds does not become divergent control flow.
+__device__ __forceinline__ long long mapped_row_offset(int e, long long tok_bytes, int row_bytes, long long sp_delta) {
+    const bool dense = e >= 0;
+    const long long idx = dense ? e : ~e;
+    return idx * (dense ? tok_bytes : (long long)row_bytes) + (dense ? 0ll : sp_delta);
+}
+
+// A 32-bit global load issued from inline assembly: it enters the hand-kept vmcnt count like a direct
+// load, and its result is valid only behind a vmcnt wait that covers it (see settle_i32).
+__device__ __forceinline__ int load_i32_hidden(const int32_t* p) {
+    int v;
+    asm volatile("global_load_dword %0, %1, off" : "=&v"(v) : "v"(p) : "memory");
+    return v;
+}
+// Marks the point behind the wait from which a hidden load's result may be used.
+__device__ __forceinline__ void settle_i32(int& v) { asm volatile("" : "+v"(v)); }
+
 // N 32-bit LDS reads issued and awaited inside inline assembly.  For kernels that keep their own
 // vmcnt count: an LDS read the compiler can see, placed after a hand-issued direct load (whose
 // statement clobbers memory), makes it wait for vmcnt(0) first, which empties the ring.
