@@ -416,11 +416,14 @@ __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
     const long long vsp_delta = IND ? (const char*)(rm.Vsp + (size_t)g * rm.s_total * D) - vbase : 0;
     const long long kv_tok_bytes = IND ? rm.kv_tok * 2 : 0;
     if constexpr (IND) {
+        // (all entries up to the capacity, so that these loads do not wait for the length; entries at
+        // and past the length may be anything and are never turned into addresses: request() clamps the
+        // row index to the last valid one before it reads the map)
         const int32_t* src_b = rm.src_idx + (size_t)b * l_cap;
         for (int i = 0; i < tiles_per_wave; ++i) {
             const int tile = tile0 + i * NW;
-            if (tile >= n_tiles) break;
-            if (lane < TK) src_w[i * TK + lane] = src_b[min(tile * TK + lane, len - 1)];
+            if (tile * TK >= l_cap) break;
+            if (lane < TK) src_w[i * TK + lane] = src_b[min(tile * TK + lane, l_cap - 1)];
         }
         __builtin_amdgcn_s_waitcnt(0x0070);                    // vmcnt(0) lgkmcnt(0): the map is in LDS
         __builtin_amdgcn_wave_barrier();
@@ -431,9 +434,11 @@ __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
     constexpr int PPR = D / 8, RPI = 64 / PPR, NL = TK / RPI;  // pieces per row; rows, 1 KiB lines per tile
     const uint32_t lds_w = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)Kw;
     // i_ = position of the tile among this wave's tiles (its row map is src_w + i_ * TK)
-    auto request = [&](int i_, int tile_, int buf) __attribute__((always_inline)) {
+    // n_valid = rows that may be read: the mixed length, or (gathered form, first request only) the
+    // capacity of the buffers, so that the first request does not wait for the load of the length.
+    auto request = [&](int i_, int tile_, int buf, int n_valid) __attribute__((always_inline)) {
         const int key0_ = tile_ * TK;
-        const int rlim_ = min(TK - 1, len - 1 - key0_);
+        const int rlim_ = min(TK - 1, n_valid - 1 - key0_);
         const char* kb = kbase + (size_t)key0_ * (D * 2);
         const char* vb = vbase + (size_t)key0_ * (D * 2);
         const int r_in = lane / PPR, pp = lane % PPR;
@@ -473,7 +478,11 @@ __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
         }
     };
     if constexpr (NBUF == 2) {
-        if (tile0 < n_tiles) request(0, tile0, 0);
+        // Gathered form: rows up to the capacity are readable memory whatever the length turns out
+        // to be (rows past it are masked when the tile is worked on, and a wave without tiles drains
+        // the request before the merge), so tile 0 is requested before the length has arrived.
+        if constexpr (IND) { if (tile0 < n_tiles) request(0, tile0, 0, len); }
+        else { if (tile0 * TK < l_cap) request(0, tile0, 0, l_cap); }
     }
 
     bf16x8 qreg[1][D / 16];
@@ -490,6 +499,15 @@ __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
                 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
                 asm volatile("" :: "v"(__builtin_bit_cast(u32x4, qreg[0][ks])));
             }
+        }
+    }
+    if constexpr (NBUF == 2 && !IND) {
+        // The early request took rows past the mixed length as they are; their V values may be anything
+        // (0 x NaN), so the one tile that straddles the length is fetched again with its rows clamped.
+        // Loads of a wave return in order: the second copy lands on top of the first.
+        if (tile0 < n_tiles && tile0 * TK + TK > len) {
+            request(0, tile0, 0, len);
+            wait_vmcnt<0>();
         }
     }
     f32x16 o[1][D / 32];
@@ -522,13 +540,13 @@ __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
         }
     } else {
         // tile i lives in pair i & 1; tile i + 1 is requested as soon as tile i - 1 has been worked on
-        if (tiles_per_wave > 1 && tile0 + NW < n_tiles) request(1, tile0 + NW, 1);
+        if (tiles_per_wave > 1 && tile0 + NW < n_tiles) request(1, tile0 + NW, 1, len);
         for (int i = 0; i < tiles_per_wave; ++i) {
             const int tile = tile0 + i * NW;
             if (tile >= n_tiles) break;
             if (i >= 1) {
                 const bool more = i + 1 < tiles_per_wave && tile + NW < n_tiles;
-                if (more) request(i + 1, tile + NW, (i + 1) & 1);
+                if (more) request(i + 1, tile + NW, (i + 1) & 1, len);
                 if (more) wait_vmcnt<2 * NL>(); else wait_vmcnt<0>();      // tile i has landed
             }
             __builtin_amdgcn_wave_barrier();
@@ -536,6 +554,7 @@ __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
             work(kt, kt + TILE_ELEMS, min(TK - 1, len - 1 - tile * TK));
             __builtin_amdgcn_wave_barrier();
         }
+        wait_vmcnt<0>();                                       // (a wave without tiles: its early request of tile 0)
     }
 
     // ---- merge the waves (their tile buffers are free now): area [32 rows][D] floats per wave ----

@@ -566,6 +566,31 @@ def test_decode_step_mode_more_splits_than_the_merge_prefetches(d, lens):
     assert np.abs(lse - wlse).max() < 2e-2
 
 
+@pytest.mark.parametrize("t_q,d,lens", [(1, 128, [1000, 37, 4096]), (4, 64, [33, 2047]), (1, 64, [1, 64]),
+                                        (10, 128, [500, 1]), (40, 128, [777]), (30, 64, [1500, 90])],
+                         ids=lambda x: str(x))
+def test_decode_never_uses_rows_past_the_mixed_length(t_q, d, lens):
+    """Rows of the mixed buffers at and past mix_len[b] are NaN (what an uninitialised buffer may
+    hold): no kernel form (step, 128-row, 256-row ring) may let them reach O or LSE, also where
+    the length falls inside a tile, at a tile border and in a wave's first tile."""
+    rng = np.random.default_rng(900 + t_q + d)
+    hq, hkv, l_cap, bsz = 14, 2, 4096, len(lens)
+    w = wl.tiny_workload("bf16", hq, hkv, d, T=t_q, B=bsz, k=1, seed=900 + d)
+    kmix = wl.round_to_bf16(rng.standard_normal((bsz, hkv, l_cap, d)).astype(np.float32) * np.float32(0.5))
+    vmix = wl.round_to_bf16(rng.standard_normal((bsz, hkv, l_cap, d)).astype(np.float32) * np.float32(0.5))
+    qd = wl.round_to_bf16(rng.standard_normal((bsz, t_q, hq, d)).astype(np.float32) * np.float32(0.5))
+    mix_len = np.array(lens, dtype=np.int32)
+    dk, dv = vxl.to_device(kmix, "bf16"), vxl.to_device(vmix, "bf16")
+    for b, n in enumerate(lens):
+        dk[b, :, n:] = float("nan")
+        dv[b, :, n:] = float("nan")
+    got, lse = gpu_decode(w, qd, dk, dv, torch.from_numpy(mix_len).cuda(), want_lse=True)
+    assert np.isfinite(got).all() and np.isfinite(lse).all()
+    want, wlse = oracle.decode_lse(qd, kmix, vmix, mix_len)
+    assert_close(got, want, "bf16", head_axis=2, what=f"decode with NaN rows past the length, T={t_q} d={d}")
+    assert np.abs(lse - wlse).max() < 2e-2
+
+
 @pytest.fixture
 def step_waves(request):
     """Both forms of the step-mode kernel: 0 = the default (4 double-buffered waves), 8 = the
