@@ -275,17 +275,19 @@ vxl_status vxl_bilevel_decode(const vxl_attn_desc* desc, const void* Qd, int32_t
  *               k that produced the mask; a query that needs more is reported as in
  *               vxl_gather_bilevel_kv (length = -(rows needed), O = 0, LSE = -inf)
  *   map_ready   0: build the row map and the lengths first (one more launch, a few microseconds);
- *               != 0: reuse those an earlier call with the same layout, mask, l_cap, batch,
- *               n_q_tokens and sparse source left in this workspace (and in mix_len, if given) --
- *               the later tokens of a query, whose selection does not change
+ *               != 0: reuse those an earlier call with the same layout, mask, l_cap, batch and
+ *               sparse source left in this workspace (and in mix_len, if given) -- the later
+ *               tokens of a query, whose selection does not change.  n_q_tokens may differ from
+ *               that call's (the question in one call, then one token per call) if the workspace
+ *               is large enough for both.  A workspace that holds no such map must not be passed
+ *               with map_ready != 0: its entries are used as row addresses unchecked.
  *   O, LSE      as vxl_bilevel_decode
  *   mix_len     device int32 [batch] (the mixed lengths: written when map_ready == 0, read
  *               otherwise) or NULL (they are then kept in the workspace)
  *   workspace   sized by vxl_workspace_bytes(VXL_OP_DECODE_INPLACE, layout, desc, batch, n_q_tokens, l_cap)
  * The set of rows a query attends to is exactly that of the gathered path; the summation order
  * differs, so results agree with it within the tolerance of the path, not bit for bit.
- * Errors: VXL_ERR_INVALID_ARG, VXL_ERR_UNSUPPORTED (also: a mixed set so long that one wave of the
- * step-mode kernel would own more than 32 tiles of 32 rows), VXL_ERR_WORKSPACE, VXL_ERR_HIP.
+ * Errors: VXL_ERR_INVALID_ARG, VXL_ERR_UNSUPPORTED, VXL_ERR_WORKSPACE, VXL_ERR_HIP.
  */
 vxl_status vxl_bilevel_decode_inplace(const vxl_layout* layout, const vxl_attn_desc* desc, const void* Qd,
                                       int32_t batch, int32_t n_q_tokens, const void* K, const void* V,

@@ -134,13 +134,15 @@ DecodePlan decode_plan(const vxl_attn_desc* d, int batch, int T, int l_cap, bool
 // Workspace of the in-place decode: split-KV partial results, then the row map and the lengths.
 InplaceWorkspace inplace_workspace(const vxl_attn_desc* d, int batch, int T, int l_cap) {
     InplaceWorkspace w{};
+    // The row map and the lengths come first: their places do not depend on the number of query
+    // tokens, so a map survives calls with another n_q_tokens on the same workspace.
     size_t off = 0;
-    w.partials = off;
-    off += align_up(std::max<size_t>(256, decode_plan(d, batch, T, l_cap, false).total), 256);
     w.src_idx = off;
     off += align_up((size_t)batch * l_cap * sizeof(int32_t), 256);
     w.mix_len = off;
     off += align_up((size_t)batch * sizeof(int32_t), 256);
+    w.partials = off;
+    off += align_up(std::max<size_t>(256, decode_plan(d, batch, T, l_cap, false).total), 256);
     w.total = off;
     return w;
 }

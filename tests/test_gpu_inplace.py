@@ -111,6 +111,33 @@ def test_inplace_ragged_bf16(mode, t_q, bsz, d):
         assert_close(got, ref, "bf16", head_axis=2, what="in-place vs gathered decode")
 
 
+def test_inplace_map_survives_a_change_of_query_token_count():
+    """The question in one call (40 tokens, which builds the row map), then one token per call with
+    map_ready on the same workspace: the map's place does not depend on n_q_tokens."""
+    rng = np.random.default_rng(4040)
+    w = wl.tiny_workload("bf16", 14, 2, 128, T=40, B=2, k=2, seed=4040, value_scale=0.5)
+    lay = wl.random_layout(rng, 17, 11, 1, 150)
+    _, k, v = wl.make_qkv(w, lay, with_q=False)
+    qd = wl.make_decode_queries(w)
+    masks = rng.integers(0, 2, size=(2, lay.n_chunks)).astype(np.uint8)
+    gl, desc, l_cap = make_layout(lay), desc_of(w), lay.n_tokens
+    dk, dv, dqd = (vxl.to_device(x, "bf16") for x in (k, v, qd))
+    dm = torch.from_numpy(masks).cuda()
+    ws = vxl.alloc_workspace(max(vxl.workspace_bytes(vxl.OP_DECODE_INPLACE, gl, desc, 2, t, l_cap) for t in (40, 1)))
+    out = torch.full_like(dqd, float("nan"))
+    vxl.bilevel_decode_inplace(gl, desc, dqd, dk, dv, None, None, dm, l_cap, out, None, None, ws)
+    wk, wv, wlen, _ = oracle.gather_bilevel(k, v, masks, *lay_args(lay), l_cap=l_cap)
+    want, _ = oracle.decode_lse(qd, wk, wv, wlen)
+    torch.cuda.synchronize()
+    assert_close(vxl.to_host(out), want, "bf16", head_axis=2, what="in-place decode, the question")
+    for t in (0, 17, 39):                                           # single tokens, the map reused
+        one = dqd[:, t:t + 1].contiguous()
+        out1 = torch.full_like(one, float("nan"))
+        vxl.bilevel_decode_inplace(gl, desc, one, dk, dv, None, None, dm, l_cap, out1, None, None, ws, map_ready=True)
+        torch.cuda.synchronize()
+        assert_close(vxl.to_host(out1), want[:, t:t + 1], "bf16", head_axis=2, what=f"in-place decode, token {t} on the reused map")
+
+
 def test_inplace_overflow_and_empty():
     """A selection that does not fit the row map is reported (negative length, O = 0, LSE = -inf);
     a layout without prefix and kept rows with nothing selected is an empty set."""
