@@ -231,6 +231,9 @@ def main():
     if not args.no_extras:
         result["decode_all_layers"] = measure_layer_stack_decode(torch, vxl, w, desc, dqds, kmixes, vmixes,
                                                                  mix_lens, l_cap, mixlen)
+        for tag, compacted in (("decode_all_layers_in_place", False), ("decode_all_layers_in_place_kept_compacted", True)):
+            result[tag] = measure_layer_stack_decode_inplace(torch, vxl, w, gl, desc, dqds, dks, dvs, mask, l_cap,
+                                                             mixlen, compacted)
         # the same calls per launch shape, on buffers rotated through > 1 GiB
         shapes = {}
         for name, kk in (("config1", None), ("config2", None), ("config3", None), ("config4_k_all", 1 << 30)):
@@ -319,6 +322,55 @@ def measure_layer_stack_decode(torch, vxl, w, desc, dqds, kmixes, vmixes, mix_le
             "frac_hbm": bytes_token / us_token / 1e3 / PEAK_HBM_GBS, "timing": "HIP graph replay",
             "cache_note": "the mixed KV sets of all layers together exceed the on-package cache only when "
                           "layers x bytes per layer > 256 MiB"}
+
+
+def measure_layer_stack_decode_inplace(torch, vxl, w, gl, desc, dqds, dks, dvs, mask, l_cap, mixlen, compacted):
+    """The same token without mixed buffers: every layer's decode reads the dense rows of the
+    selected chunks in that layer's resident K / V and the kept rows of the others where they lie
+    (compacted = False) or in a compacted copy [Hkv, S_total, D] of them per layer (True), through
+    the row map that the layer's first call left in its workspace."""
+    n_layers = len(dks)
+    sp = [(None, None)] * n_layers
+    if compacted and int(gl.soff[-1]) > 0:
+        idx = torch.from_numpy(gl.sidx.astype(np.int64)).cuda()
+        sp = [(k_[:, idx].contiguous(), v_[:, idx].contiguous()) for k_, v_ in zip(dks, dvs)]
+    B, D, Hkv, Hq = w.B, w.head_dim, w.n_kv_heads, w.n_q_heads
+    q1 = [qd[:, :1].contiguous() for qd in dqds]
+    o1 = [torch.empty_like(x) for x in q1]
+    nbytes = vxl.workspace_bytes(vxl.OP_DECODE_INPLACE, gl, desc, B, 1, l_cap)
+    wss = [vxl.alloc_workspace(nbytes) for _ in range(n_layers)]
+    for l in range(n_layers):                                  # builds the row maps
+        vxl.bilevel_decode_inplace(gl, desc, q1[l], dks[l], dvs[l], sp[l][0], sp[l][1], mask, l_cap, o1[l], None, None,
+                                   wss[l])
+
+    def token():
+        for l in range(n_layers):
+            vxl.bilevel_decode_inplace(gl, desc, q1[l], dks[l], dvs[l], sp[l][0], sp[l][1], mask, l_cap, o1[l], None,
+                                       None, wss[l], map_ready=True)
+
+    for _ in range(3):
+        token()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    reps_in_graph = max(1, 64 // n_layers)
+    with torch.cuda.graph(graph):
+        for _ in range(reps_in_graph):
+            token()
+    graph.replay()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 5
+    a.record()
+    for _ in range(reps):
+        graph.replay()
+    b.record()
+    torch.cuda.synchronize()
+    us_token = a.elapsed_time(b) * 1e3 / (reps * reps_in_graph)
+    bytes_token = n_layers * (2 * B * Hkv * mixlen * D * 2 + 2 * B * Hq * D * 2 + B * mixlen * 4)
+    return {"layers": n_layers, "us_per_token": us_token, "us_per_layer": us_token / n_layers,
+            "bytes_per_token": bytes_token, "GBps": bytes_token / us_token / 1e3,
+            "frac_hbm": bytes_token / us_token / 1e3 / PEAK_HBM_GBS, "timing": "HIP graph replay",
+            "mixed_buffers": "none (row maps of %d bytes per layer)" % (B * l_cap * 4)}
 
 
 def measure_attained_peaks(torch, vxl):

@@ -446,6 +446,32 @@ __global__ __launch_bounds__(64 * NW, 2) void decode_wave_kernel(
         if constexpr (IND) {
             // rows x * RPI + r_in, clamped to the last valid one: a constant stride except at the clamp
             const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(src_w + i_ * TK);
+            // A full tile whose 32 entries are consecutive rows of one source (a dense chunk: e0, e0 + 1,
+            // ...; the sparse buffer: e0, e0 - 1, ...) is fetched like a tile of a gathered buffer, from
+            // one scalar base with 32-bit lane offsets: the same number of loads, far fewer instructions.
+            if (rlim_ == TK - 1) {
+                int ent[1];
+                lds_read_i32_hidden<1>(base + (lane & (TK - 1)) * 4, 0, ent);
+                const int e0 = __builtin_amdgcn_readfirstlane(ent[0]);
+                const int step = e0 >= 0 ? 1 : -1;
+                if (kv_tok_bytes < (1ll << 26) &&                // (32 rows x stride must fit the 32-bit lane offset)
+                    __builtin_amdgcn_ballot_w64(ent[0] != e0 + step * (lane & (TK - 1))) == 0) {
+                    const char* kb1 = kbase + mapped_row_offset(e0, kv_tok_bytes, D * 2, ksp_delta);
+                    const char* vb1 = vbase + mapped_row_offset(e0, kv_tok_bytes, D * 2, vsp_delta);
+                    const uint32_t row_bytes = e0 >= 0 ? (uint32_t)kv_tok_bytes : (uint32_t)(D * 2);
+#pragma unroll
+                    for (int x = 0; x < NL; ++x) {
+                        const int row = x * RPI + r_in;
+                        const int kp = pp ^ ((row / (16 / PPR)) & (PPR - 1));
+                        constexpr int CPR = D * 2 / 64, RPL = D == 128 ? 1 : 2;
+                        const int vp = (((pp >> 2) ^ ((row / RPL) & (CPR - 1))) << 2) | (pp & 3);
+                        const uint32_t kdst = lds_w + (uint32_t)buf * (4 * TILE_ELEMS) + x * 1024;
+                        dma16(kb1, (uint32_t)row * row_bytes + kp * 16, kdst);
+                        dma16(vb1, (uint32_t)row * row_bytes + vp * 16, kdst + 2 * TILE_ELEMS);
+                    }
+                    return;
+                }
+            }
             if (rlim_ == TK - 1) {
                 lds_read_i32_hidden<NL>(base + r_in * 4, RPI * 4, src_row);
             } else {
