@@ -124,3 +124,70 @@ def gpu_score_topk_mass(w, lay, qd, k, top_k, gl=None, scale=0.0):
     vxl.chunk_score_topk_mass(gl, desc, dqd, dk, top_k, idx, mask, scores, workspace=ws)
     torch.cuda.synchronize()
     return idx.cpu().numpy()[:, :kk], mask.cpu().numpy()[:, :c_n], scores.cpu().numpy()[:, :c_n]
+
+
+def full_sort_selection(scores, k):
+    """(idx [B, min(k, C)] best first, mask [B, C]) that a full sort of `scores` gives: score
+    descending, equal scores to the lower chunk id.  Used to check the device's selection against the
+    device's OWN fp32 scores -- a property of the selection kernel, in which the oracle has no part."""
+    scores = np.asarray(scores)
+    bsz, n = scores.shape
+    kk = min(k, n)
+    idx = np.zeros((bsz, kk), dtype=np.int32)
+    mask = np.zeros((bsz, n), dtype=np.uint8)
+    for b in range(bsz):
+        order = np.lexsort((np.arange(n), -scores[b].astype(np.float64)))     # last key is the primary one
+        idx[b] = order[:kk]
+        mask[b, order[:kk]] = 1
+    return idx, mask
+
+
+def check_selection_valid(idx, mask, want_scores, want_mask, k, tol):
+    """Several selections are correct where oracle scores are closer than the score tolerance: the
+    device's must leave out nothing clearly better than what it takes, take exactly min(k, C) chunks,
+    agree with its own index list, and equal the oracle's mask wherever the rank-k margin is clear."""
+    bsz, n = want_scores.shape
+    kk = min(k, n)
+    for b in range(bsz):
+        assert mask[b].sum() == kk and sorted(idx[b].tolist()) == np.flatnonzero(mask[b]).tolist()
+        if 0 < kk < n:
+            srt = np.sort(want_scores[b])[::-1]
+            assert (want_scores[b, idx[b]] >= srt[kk - 1] - 2 * tol).all()
+            assert mask[b][want_scores[b] > srt[kk - 1] + 2 * tol].all()
+            if srt[kk - 1] - srt[kk] > 2 * tol:
+                assert np.array_equal(mask[b], want_mask[b])
+        else:
+            assert np.array_equal(mask[b], want_mask[b])
+
+
+def storage_round(w, x):
+    """A float64 result of the oracle as the storage dtype of the workload holds it."""
+    return wl.round_to_bf16(x.astype(np.float32)) if w.dtype == "bf16" else x.astype(np.float32)
+
+
+def kept_rows(k, lay):
+    """[Hkv, S_total, D] kept rows in chunk order (host)."""
+    return np.ascontiguousarray(k[:, lay.sparse_idx]) if len(lay.sparse_idx) else np.zeros((k.shape[0], 1, k.shape[2]), k.dtype)
+
+
+def gpu_decode_inplace(w, lay, qd, dk, dv, masks, l_cap, sparse=None, gl=None, desc=None, scale=0.0, want_lse=True):
+    """sparse: None (kept rows in place) or (ksp, vsp) device tensors."""
+    gl = gl or make_layout(lay)
+    desc = desc or desc_of(w, scale)
+    dqd = vxl.to_device(qd, w.dtype)
+    dm = torch.from_numpy(np.ascontiguousarray(masks, dtype=np.uint8)).cuda()
+    bsz, t = qd.shape[0], qd.shape[1]
+    out = torch.full_like(dqd, float("nan"))
+    lse = torch.full(dqd.shape[:3], float("nan"), dtype=torch.float32, device="cuda")
+    lens = torch.full((bsz,), -77, dtype=torch.int32, device="cuda")
+    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_DECODE_INPLACE, gl, desc, bsz, t, l_cap))
+    ksp, vsp = sparse if sparse is not None else (None, None)
+    vxl.bilevel_decode_inplace(gl, desc, dqd, dk, dv, ksp, vsp, dm, l_cap, out, lse, lens, ws)
+    torch.cuda.synchronize()
+    first = out.clone()
+    # the later tokens of a query reuse the row map that is in the workspace
+    out.fill_(float("nan"))
+    vxl.bilevel_decode_inplace(gl, desc, dqd, dk, dv, ksp, vsp, dm, l_cap, out, lse, lens, ws, map_ready=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.uint8), first.view(torch.uint8)), "map_ready call differs"
+    return vxl.to_host(out), vxl.to_host(lse), lens.cpu().numpy()

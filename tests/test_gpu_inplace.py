@@ -10,41 +10,14 @@ import torch
 import oracle
 from paper_2506_19225_amd import vxl, workloads as wl
 
-from gpu_util import assert_close, desc_of, gpu_decode, gpu_gather, make_layout
+from gpu_util import (assert_close, desc_of, gpu_decode, gpu_decode_inplace as inplace, gpu_gather, kept_rows,
+                      make_layout, storage_round)
 
 pytestmark = pytest.mark.gpu
 
 
 def lay_args(lay):
     return lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx
-
-
-def kept_rows(k, lay):
-    """[Hkv, S_total, D] kept rows in chunk order (host)."""
-    return np.ascontiguousarray(k[:, lay.sparse_idx]) if len(lay.sparse_idx) else np.zeros((k.shape[0], 1, k.shape[2]), k.dtype)
-
-
-def inplace(w, lay, qd, dk, dv, masks, l_cap, sparse=None, gl=None, desc=None, scale=0.0, want_lse=True):
-    """sparse: None (kept rows in place) or (ksp, vsp) device tensors."""
-    gl = gl or make_layout(lay)
-    desc = desc or desc_of(w, scale)
-    dqd = vxl.to_device(qd, w.dtype)
-    dm = torch.from_numpy(np.ascontiguousarray(masks, dtype=np.uint8)).cuda()
-    bsz, t = qd.shape[0], qd.shape[1]
-    out = torch.full_like(dqd, float("nan"))
-    lse = torch.full(dqd.shape[:3], float("nan"), dtype=torch.float32, device="cuda")
-    lens = torch.full((bsz,), -77, dtype=torch.int32, device="cuda")
-    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_DECODE_INPLACE, gl, desc, bsz, t, l_cap))
-    ksp, vsp = sparse if sparse is not None else (None, None)
-    vxl.bilevel_decode_inplace(gl, desc, dqd, dk, dv, ksp, vsp, dm, l_cap, out, lse, lens, ws)
-    torch.cuda.synchronize()
-    first = out.clone()
-    # the later tokens of a query reuse the row map that is in the workspace
-    out.fill_(float("nan"))
-    vxl.bilevel_decode_inplace(gl, desc, dqd, dk, dv, ksp, vsp, dm, l_cap, out, lse, lens, ws, map_ready=True)
-    torch.cuda.synchronize()
-    assert torch.equal(out.view(torch.uint8), first.view(torch.uint8)), "map_ready call differs"
-    return vxl.to_host(out), vxl.to_host(lse), lens.cpu().numpy()
 
 
 def check_case(w, lay, k, v, qd, masks, mode, l_cap=None, tol_lse=2e-2):
@@ -65,8 +38,10 @@ def check_case(w, lay, k, v, qd, masks, mode, l_cap=None, tol_lse=2e-2):
         vxl.pool_sparse_kv(gl, desc, dk, dv, ksp, vsp)
         torch.cuda.synchronize()
         sparse = (ksp, vsp)
-        wk, wv, wlen, _ = oracle.gather_bilevel_pooled(k, v, vxl.to_host(ksp), vxl.to_host(vsp), masks, lay.n_prefix,
-                                                       lay.chunk_bounds, lay.sparse_offsets, l_cap=l_cap)
+        # (the oracle pools for itself: its inputs never come from the device)
+        ok, ov = oracle.pool_sparse_kv(k, v, lay.chunk_bounds, lay.sparse_offsets)
+        wk, wv, wlen, _ = oracle.gather_bilevel_pooled(k, v, storage_round(w, ok), storage_round(w, ov), masks,
+                                                       lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, l_cap=l_cap)
     got, lse, lens = inplace(w, lay, qd, dk, dv, masks, l_cap, sparse, gl=gl)
     assert np.array_equal(lens, wlen)
     want, wlse = oracle.decode_lse(qd, wk, wv, wlen)

@@ -8,7 +8,7 @@ import pytest
 import oracle
 from paper_2506_19225_amd import vxl, workloads as wl
 
-from gpu_util import gpu_score_topk_mass
+from gpu_util import check_selection_valid, full_sort_selection, gpu_score_topk_mass
 
 pytestmark = pytest.mark.gpu
 
@@ -22,20 +22,11 @@ def check_mass(w, lay, qd, k, top_k, scale=0.0, rtol=RTOL):
     assert np.isfinite(scores).all()
     assert np.abs(scores - want).max() <= tol, (np.abs(scores - want).max(), tol)
     assert (scores.sum(axis=1) <= 1.0 + 1e-4).all()          # the prefix holds the rest of the mass
-    kk = min(top_k, lay.n_chunks)
     # the device's selection is the full-sort selection of its own scores, bit for bit
-    own_idx, own_mask = oracle.select_topk(scores, top_k)
+    own_idx, own_mask = full_sort_selection(scores, top_k)
     assert np.array_equal(idx, own_idx) and np.array_equal(mask, own_mask)
     # and a valid selection for the oracle's scores: nothing clearly better is left out
-    for b in range(scores.shape[0]):
-        if 0 < kk < lay.n_chunks:
-            kth = np.sort(want[b])[::-1][kk - 1]
-            assert (want[b, idx[b]] >= kth - 2 * tol).all()
-            assert mask[b][want[b] > kth + 2 * tol].all()
-            srt = np.sort(want[b])[::-1]
-            if srt[kk - 1] - srt[kk] > 2 * tol:
-                assert np.array_equal(mask[b], oracle.select_topk(want[b:b + 1], top_k)[1][0])
-        assert mask[b].sum() == kk
+    check_selection_valid(idx, mask, want, oracle.select_topk(want, top_k)[1], top_k, tol)
     return idx, mask, scores
 
 

@@ -10,13 +10,9 @@ import torch
 import oracle
 from paper_2506_19225_amd import vxl, workloads as wl
 
-from gpu_util import assert_close, desc_of, gpu_decode, make_layout
+from gpu_util import assert_close, desc_of, gpu_decode, make_layout, storage_round
 
 pytestmark = pytest.mark.gpu
-
-
-def storage_round(w, x):
-    return wl.round_to_bf16(x.astype(np.float32)) if w.dtype == "bf16" else x.astype(np.float32)
 
 
 def run_pool(w, lay, k, v, gl=None):

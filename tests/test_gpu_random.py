@@ -8,7 +8,9 @@ import torch
 import oracle
 from paper_2506_19225_amd import vxl, workloads as wl
 
-from gpu_util import (assert_close, gpu_decode, gpu_gather, gpu_score_topk, gpu_score_topk_mass, make_layout)
+from gpu_util import (assert_close, check_selection_valid, desc_of, full_sort_selection, gpu_decode,
+                      gpu_decode_inplace, gpu_gather, gpu_score_topk, gpu_score_topk_mass, kept_rows, make_layout,
+                      storage_round)
 
 pytestmark = pytest.mark.gpu
 
@@ -62,7 +64,7 @@ def test_bilevel_random_sweep(seed):
         nc = int(rng.integers(1, 12))
         hi = int(rng.choice([40, 130, 300]))
         lo = int(rng.integers(1, hi + 1))
-        t_q = int(rng.choice([1, 2, 4, 5, 16, 33]))
+        t_q = int(rng.choice([1, 2, 4, 5, 16, 33, 48, 80]))
         bsz = int(rng.choice([1, 2, 3]))
         k_top = int(rng.integers(0, nc + 2))
         s = int(rng.integers(1 << 30))
@@ -78,12 +80,19 @@ def test_bilevel_random_sweep(seed):
         idx, mask, sc = gpu_score_topk(w, lay, qd, k, k_top, gl=gl)
         wsc = oracle.chunk_scores(qd, k, lay.chunk_bounds)
         assert np.abs(sc - wsc).max() <= 1e-4 * max(1.0, np.abs(wsc).max()), what
-        # the selection is decided on fp32 scores on both sides: the device's own
-        widx, wmask = oracle.select_topk(sc, k_top)
-        assert np.array_equal(idx, widx) and np.array_equal(mask, wmask), what
+        # the selection: the full sort of the device's own fp32 scores, and valid for the oracle's
+        tol = 1e-4 * max(1.0, np.abs(wsc).max())
+        own_idx, own_mask = full_sort_selection(sc, k_top)
+        assert np.array_equal(idx, own_idx) and np.array_equal(mask, own_mask), what
+        check_selection_valid(idx, mask, wsc, oracle.select_topk(wsc, k_top)[1], k_top, tol)
+        mask = oracle.select_topk(wsc, k_top)[1]               # what follows takes the oracle's selection on both sides
         midx, mmask, msc = gpu_score_topk_mass(w, lay, qd, k, k_top, gl=gl)
-        widx2, wmask2 = oracle.select_topk(msc, k_top)
-        assert np.array_equal(midx, widx2) and np.array_equal(mmask, wmask2), what
+        wms = oracle.chunk_scores_mass(qd, k, lay.n_prefix, lay.chunk_bounds)
+        mtol = 1e-4 * np.abs(wms).max()
+        assert np.abs(msc - wms).max() <= mtol, what
+        own_idx, own_mask = full_sort_selection(msc, k_top)
+        assert np.array_equal(midx, own_idx) and np.array_equal(mmask, own_mask), what
+        check_selection_valid(midx, mmask, wms, oracle.select_topk(wms, k_top)[1], k_top, mtol)
         l_cap = gl.mixed_kv_capacity(min(k_top, nc))
         kmix, vmix, mix_len, src = gpu_gather(w, lay, k, v, mask, l_cap, gl=gl)
         wk, wv, wlen, wsrc = oracle.gather_bilevel(k, v, mask, lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets,
@@ -98,3 +107,22 @@ def test_bilevel_random_sweep(seed):
             got = gpu_decode(w, qd, kmix, vmix, mix_len)
             want = oracle.decode_mixed(qd, wk, wv, wlen)
             assert_close(got, want, dtype, head_axis=2, what=what)
+            # the same rows read in place: kept rows where they lie, then from a compacted copy
+            dk, dv = vxl.to_device(k, dtype), vxl.to_device(v, dtype)
+            for sparse in (None, (vxl.to_device(kept_rows(k, lay), dtype), vxl.to_device(kept_rows(v, lay), dtype))):
+                got, _, lens = gpu_decode_inplace(w, lay, qd, dk, dv, mask, l_cap, sparse, gl=gl)
+                assert np.array_equal(lens, wlen), what
+                assert_close(got, want, dtype, head_axis=2, what=what + (" in place" if sparse is None else " in place, compacted"))
+            # pooled sparse rows: gather + decode and in place, against the oracle's pooled mixed set
+            if lay.sparse_offsets[-1] > 0:
+                desc = desc_of(w)
+                ksp = torch.empty((hkv, int(lay.sparse_offsets[-1]), d), dtype=dk.dtype, device="cuda")
+                vsp = torch.empty_like(ksp)
+                vxl.pool_sparse_kv(gl, desc, dk, dv, ksp, vsp)
+                torch.cuda.synchronize()
+                ok, ov = oracle.pool_sparse_kv(k, v, lay.chunk_bounds, lay.sparse_offsets)
+                pk, pv, plen, _ = oracle.gather_bilevel_pooled(k, v, storage_round(w, ok), storage_round(w, ov), mask,
+                                                               lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, l_cap=l_cap)
+                got, _, lens = gpu_decode_inplace(w, lay, qd, dk, dv, mask, l_cap, (ksp, vsp), gl=gl)
+                assert np.array_equal(lens, plen), what
+                assert_close(got, oracle.decode_mixed(qd, pk, pv, plen), dtype, head_axis=2, what=what + " in place, pooled")
