@@ -242,6 +242,11 @@ def main():
         result["bilevel"] = shapes
         result["prefill_other_workloads"] = {n: prefill_only(torch, vxl, wl, n) for n in ("config1", "config2", "config4")
                                              if n != args.workload}
+        # a diagnostic, not a result: the same launch on all-zero Q, K, V.  The instruction stream is the
+        # same; the chip holds its clock on operands that toggle no wires and lowers it on real data.
+        result["prefill_clock_diagnostic"] = {"config2_zero_inputs": prefill_only(torch, vxl, wl, "config2", zero=True),
+                                              "note": "same kernel and launch as prefill_other_workloads.config2 (or the "
+                                                      "headline at --workload config2); inputs all zero"}
         w1 = wl.WORKLOADS["config1"]
         result["widening"] = measure_widening(torch, vxl, wl, w1)
         result["attained_peaks"] = measure_attained_peaks(torch, vxl)
@@ -251,15 +256,16 @@ def main():
     print(json.dumps(result))
 
 
-def prefill_only(torch, vxl, wl, name, steps=10, warmup=3):
-    """vxl_chunk_prefill alone on another workload's layout (device-drawn values of its scale)."""
+def prefill_only(torch, vxl, wl, name, steps=10, warmup=3, zero=False):
+    """vxl_chunk_prefill alone on another workload's layout (device-drawn values of its scale;
+    zero = True: all-zero inputs, for the clock diagnostic only)."""
     w = wl.WORKLOADS[name]
     lay = wl.make_layout(w)
     gl = vxl.Layout(lay.n_prefix, lay.chunk_bounds, lay.sparse_offsets, lay.sparse_idx)
     desc = vxl.make_desc(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
     gen = torch.Generator(device="cuda").manual_seed(w.seed)
     draw = lambda h: (torch.randn((h, lay.n_tokens, w.head_dim), device="cuda", generator=gen)
-                      * w.value_scale).to(torch.bfloat16)
+                      * (0.0 if zero else w.value_scale)).to(torch.bfloat16)
     q, k, v = draw(w.n_q_heads), draw(w.n_kv_heads), draw(w.n_kv_heads)
     out = torch.empty_like(q)
     ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_PREFILL, gl, desc))
@@ -387,6 +393,15 @@ def measure_attained_peaks(torch, vxl):
     b.record()
     torch.cuda.synchronize()
     mfma = flops / (a.elapsed_time(b) * 1e-3) / 1e12
+    # the same instruction stream with pseudo-random operands that change every instruction (what the
+    # attention kernels feed it): the chip lowers its clock under it
+    vxl.debug_mfma_stream_random(out, n_cu, iters)
+    torch.cuda.synchronize()
+    a.record()
+    flops_r = vxl.debug_mfma_stream_random(out, n_cu, iters)
+    b.record()
+    torch.cuda.synchronize()
+    mfma_random = flops_r / (a.elapsed_time(b) * 1e-3) / 1e12
     src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
     dst = torch.empty_like(src)
     dst.copy_(src)
@@ -398,7 +413,27 @@ def measure_attained_peaks(torch, vxl):
     torch.cuda.synchronize()
     copy = 10 * 2.0 * src.numel() * 4 / (a.elapsed_time(b) * 1e-3) / 1e9
     res = {"mfma_bf16_stream_TFLOPs": mfma, "mfma_frac_of_published": mfma / PEAK_BF16_TFLOPS,
+           "mfma_bf16_stream_random_operands_TFLOPs": mfma_random,
+           "mfma_random_operands_frac_of_published": mfma_random / PEAK_BF16_TFLOPS,
            "copy_1GiB_GBps_read_plus_write": copy, "copy_frac_of_published": copy / PEAK_HBM_GBS}
+    # the pre-filling kernel's tile loop on its own, one ingredient at a time (vxl_debug.h): what the matrix
+    # instructions alone take on this data, and what LDS operands, softmax and ring refills add
+    kvbuf = torch.empty(vxl.debug_tile_loop_bytes(n_cu) // 2, dtype=torch.bfloat16, device="cuda").normal_()
+    tl = {}
+    n_tiles = 4000
+    for tag, mode in (("matrix_instructions_only", 0), ("operands_from_registers", 4), ("no_softmax", 3), ("full_tile_code", 1),
+                      ("full_tile_code_with_ring_refills", 2)):
+        vxl.debug_tile_loop(mode, kvbuf, out, n_cu, n_tiles)
+        torch.cuda.synchronize()
+        a.record()
+        fl = vxl.debug_tile_loop(mode, kvbuf, out, n_cu, n_tiles)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b)
+        tl[tag] = {"ns_per_tile": ms * 1e6 / n_tiles, "TFLOPs": fl / (ms * 1e-3) / 1e12,
+                   "frac_of_published": fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+    res["prefill_tile_loop"] = tl
+    del kvbuf
     # a bare streaming read of one decode call's KV bytes (config1 / config3 layer / config2 / 1 GiB), launches
     # replayed from a graph over distinct regions of a 4 GiB buffer: the floor of a split-KV kernel
     del dst

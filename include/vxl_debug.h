@@ -41,6 +41,24 @@ void vxl_debug_prefill_events(void* start_event, void* stop_event);
  * launched, 0 on a bad argument or a failed launch. */
 double vxl_debug_mfma_stream(float* out, int n_workgroups, int iters, void* stream);
 
+/* The same stream with operands as an attention kernel sees them -- eight register sets of
+ * pseudo-random bf16 values in (-1, 1), another pair in every instruction -- instead of a few
+ * small integers repeated: the chip lowers its clock under it, so this, not the stream above, is
+ * what a matrix-bound kernel on real data can attain.  `iters` must be even.  Same return value. */
+double vxl_debug_mfma_stream_random(float* out, int n_workgroups, int iters, void* stream);
+
+/* The tile loop of the pre-filling kernel on its own (its tile functions over four LDS-resident
+ * 64-key tiles, 8 waves x 32 rows per workgroup, head_dim 128; no work items, masks, query or
+ * output traffic), with one ingredient left in or taken out by `mode`, for pricing the
+ * ingredients of a tile against the bare matrix-instruction stream on the same data:
+ *   0 matrix instructions only   1 the full tile code   2 = 1 + ring refills by direct loads
+ *   3 = 1 without the softmax arithmetic   4 = 1 with both operand streams from registers.
+ * kv: device bf16 values (any finite data), at least vxl_debug_tile_loop_bytes(n_workgroups) bytes;
+ * out: device float [n_workgroups * 512]; n_tiles even.  Returns the floating-point operations of
+ * the matrix instructions launched, 0 on a bad argument or a failed launch. */
+size_t vxl_debug_tile_loop_bytes(int n_workgroups);
+double vxl_debug_tile_loop(int mode, const void* kv, float* out, int n_workgroups, int n_tiles, void* stream);
+
 /* Launches a bare streaming read of `bytes` (a multiple of 16) of device memory at `src` by
  * `n_workgroups` workgroups of 256 threads on `stream`; out: device float [n_workgroups * 256].
  * What a bandwidth-bound kernel could at best take for a buffer of that size.  Returns a

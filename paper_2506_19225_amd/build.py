@@ -35,7 +35,8 @@ def _hipcc() -> str:
 # would add scratch loads and stores to that count behind the kernel's back, so the build refuses
 # a compile in which one of them uses scratch memory.
 NO_SCRATCH = {"vxl_prefill.hip": ("prefill_dma_kernel",),
-              "vxl_decode.hip": ("decode_ring_kernel", "decode_wave_kernel")}
+              "vxl_decode.hip": ("decode_ring_kernel", "decode_wave_kernel"),
+              "vxl_debug.hip": ("tile_loop_kernel",)}
 
 
 def _check_no_scratch(src: str, remarks: str) -> None:

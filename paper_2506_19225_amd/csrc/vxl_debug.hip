@@ -30,7 +30,44 @@ __global__ __launch_bounds__(512, 2) void mfma_stream_kernel(float* __restrict__
         for (int r = 0; r < 16; ++r) t += acc[i][r];
     out[(size_t)blockIdx.x * 512 + threadIdx.x] = t;
 }
+// The same stream fed with operands as the attention kernels see them: eight register sets of
+// pseudo-random bf16 values in (-1, 1), a different pair in every instruction.  The chip holds its
+// clock under the stream above (few mantissa bits set, the same operands every time) and lowers it
+// under this one, so this is the rate a matrix-bound kernel on real data can be read against.
+__global__ __launch_bounds__(512, 2) void mfma_stream_random_kernel(float* __restrict__ out, int iters, uint32_t seed) {
+    f32x16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = zero16();
+    bf16x8 r[8];
+    uint32_t x = seed ^ (threadIdx.x * 0x9E3779B9u) ^ (blockIdx.x * 0x85EBCA6Bu);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            x ^= x << 13; x ^= x >> 17; x ^= x << 5;              // xorshift32
+            r[j][e] = (__bf16)((float)(int32_t)x * (1.0f / 2147483648.0f));
+        }
+    for (int it = 0; it < iters; it += 2) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            acc[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r[j], r[(j + 3) & 7], acc[j & 3], 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) t += acc[i][q];
+    out[(size_t)blockIdx.x * 512 + threadIdx.x] = t;
+}
 }  // namespace
+extern "C" double vxl_debug_mfma_stream_random(float* out, int n_workgroups, int iters, void* stream) {
+    if (!out || n_workgroups <= 0 || iters <= 0 || (iters & 1)) return 0.0;
+    hipLaunchKernelGGL(mfma_stream_random_kernel, dim3(n_workgroups), dim3(512), 0, (hipStream_t)stream, out, iters,
+                       0x2545F491u);
+    if (hipGetLastError() != hipSuccess) return 0.0;
+    return (double)n_workgroups * 8.0 * iters * 4.0 * 2.0 * 32 * 32 * 16;
+}
+
 // out: device float [n_workgroups * 512]; returns the number of floating-point operations launched
 // (0 on a bad argument).
 extern "C" double vxl_debug_mfma_stream(float* out, int n_workgroups, int iters, void* stream) {
@@ -40,6 +77,142 @@ extern "C" double vxl_debug_mfma_stream(float* out, int n_workgroups, int iters,
     return (double)n_workgroups * 8.0 * iters * 4.0 * 2.0 * 32 * 32 * 16;
 }
 
+
+// The tile loop of the pre-filling kernel on its own: the kernel's tile functions (score product
+// with the K operands from LDS, online softmax, second product with the transposed V operands from
+// LDS) over a ring of four LDS-resident 64-key tiles, 8 waves x 32 rows, one meeting per two tiles
+// -- no work items, no masks, no query / output traffic.  What is left in or taken out by `mode`
+// prices the ingredients of a tile against the bare matrix-instruction stream on the same data:
+//   0  matrix instructions only (32 per wave and tile, operands = the query registers)
+//   1  the full tile code on resident tiles
+//   2  1 + the ring refilled two tiles ahead by direct global->LDS loads (source resident in L2)
+//   3  1 without the softmax arithmetic (weights = converted scores)
+//   4  1 with both operand streams taken from registers instead of LDS
+namespace {
+template <int MODE>
+__global__ __launch_bounds__(512, 1) void tile_loop_kernel(const uint16_t* __restrict__ kv, float* __restrict__ out,
+                                                           int n_tiles, float c2) {
+    constexpr int D = 128, NS = 4, TILE = kKeyTile * D, STAGE = 2 * TILE;
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    for (int i = tid; i < NS * STAGE / 8; i += 512) ((uint4*)lds)[i] = ((const uint4*)kv)[i + blockIdx.x * 64];
+    __syncthreads();
+    bf16x8 qreg[1][D / 16];
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) qreg[0][ks] = __builtin_bit_cast(bf16x8, ((const uint4*)kv)[tid * 16 + ks]);
+    f32x16 o[1][D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) o[0][db] = zero16();
+    float m_run = -INFINITY, l_run = 0.f;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
+    const char* gbase = (const char*)kv + (size_t)blockIdx.x * 4096;
+    auto issue = [&](int t) {                                  // 4 loads of 1 KiB per wave: its share of a K and a V tile
+        const uint32_t st = lds_base + (uint32_t)(t % NS) * (STAGE * 2);
+        const uint32_t goff = (uint32_t)(t & 63) * (STAGE * 2);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int slot = wave + i * 8;
+            dma16(gbase, goff + slot * 1024 + lane * 16, st + slot * 1024);
+            dma16(gbase, goff + TILE * 2 + slot * 1024 + lane * 16, st + TILE * 2 + slot * 1024);
+        }
+    };
+    if (MODE == 2) { issue(0); issue(1); }
+    auto process = [&](int ti) {
+        const uint16_t* kt = lds + (ti % NS) * STAGE;
+        const uint16_t* vt = kt + TILE;
+        if (MODE == 0) {
+#pragma unroll
+            for (int j = 0; j < 32; ++j)
+                o[0][j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[0][j & 7], qreg[0][(j + 3) & 7], o[0][j & 3], 0, 0, 0);
+            return;
+        }
+        f32x16 s[1][2];
+        if (MODE == 4) {
+            s[0][0] = zero16();
+            s[0][1] = zero16();
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ++ks)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+                    s[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[0][(ks + kb + 1) & 7], qreg[0][ks], s[0][kb], 0, 0, 0);
+        } else {
+            qk_tile_ahead<D, 1>(kt, qreg, l32, hi, s);
+        }
+        bf16x8 pb[1][2][2];
+        if (MODE == 3) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) pb[0][kb][j][e] = (__bf16)s[0][kb][j * 8 + e];
+        } else {
+            softmax_tile<D / 32>(s[0], c2, m_run, l_run, o[0], pb[0]);
+        }
+        if (MODE == 4) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int db = 0; db < D / 32; ++db)
+                        o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[0][(kb * 2 + j + db) & 7], pb[0][kb][j], o[0][db], 0, 0, 0);
+        } else {
+            pv_tile_ahead<D, 2>(vt, pb, lane, o);
+        }
+    };
+    for (int t0 = 0; t0 < n_tiles; t0 += 2) {
+        wait_vmcnt0_lgkmcnt0();
+        __builtin_amdgcn_s_barrier();
+        if (MODE == 2) issue(t0 + 2);
+        process(t0);
+        if (MODE == 2) issue(t0 + 3);
+        process(t0 + 1);
+    }
+    wait_vmcnt<0>();
+    float r = l_run + m_run;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) r += o[0][db][q];
+    out[(size_t)blockIdx.x * 512 + tid] = r;
+}
+}  // namespace
+// kv: device bf16 values, at least vxl_debug_tile_loop_bytes(n_workgroups) bytes; out: device float
+// [n_workgroups * 512].  Returns the floating-point operations of the matrix instructions launched
+// (n_workgroups x 8 waves x n_tiles x 32 instructions), 0 on a bad argument or a failed launch.
+extern "C" size_t vxl_debug_tile_loop_bytes(int n_workgroups) {
+    return n_workgroups <= 0 ? 0 : (size_t)66 * (2 * kKeyTile * 128 * 2) + (size_t)n_workgroups * 4096 + 16384;
+}
+extern "C" double vxl_debug_tile_loop(int mode, const void* kv, float* out, int n_workgroups, int n_tiles,
+                                      void* stream) {
+    if (!kv || !out || n_workgroups <= 0 || n_tiles <= 0 || (n_tiles & 1) || mode < 0 || mode > 4) return 0.0;
+    constexpr int lds_bytes = 4 * 2 * kKeyTile * 128 * 2;
+    static PerDeviceOnce attr;
+    const vxl_status ast = attr.run([] {
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)tile_loop_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)tile_loop_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)tile_loop_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)tile_loop_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+        VXL_HIP_TRY(hipFuncSetAttribute((const void*)tile_loop_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+        return VXL_OK;
+    });
+    if (ast != VXL_OK) return 0.0;
+    const float c2 = 0.0883883f * kLog2e;
+#define VXL_TL(M) hipLaunchKernelGGL(tile_loop_kernel<M>, dim3(n_workgroups), dim3(512), lds_bytes, (hipStream_t)stream, \
+                                     (const uint16_t*)kv, out, n_tiles, c2)
+    switch (mode) {
+        case 0: VXL_TL(0); break;
+        case 1: VXL_TL(1); break;
+        case 2: VXL_TL(2); break;
+        case 3: VXL_TL(3); break;
+        default: VXL_TL(4); break;
+    }
+#undef VXL_TL
+    if (hipGetLastError() != hipSuccess) return 0.0;
+    return (double)n_workgroups * 8.0 * n_tiles * 32.0 * 2.0 * 32 * 32 * 16;
+}
 
 // A bare streaming read: `n_workgroups` workgroups of 256 threads read `bytes` (a multiple of 16) of
 // `src` once, 16 bytes per thread and step, eight loads in flight per thread, and write one float

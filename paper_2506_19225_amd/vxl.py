@@ -99,6 +99,12 @@ def lib() -> C.CDLL:
     L.vxl_debug_decode_step_waves.argtypes = [C.c_int]
     L.vxl_debug_mfma_stream.argtypes = [vp, C.c_int, C.c_int, vp]
     L.vxl_debug_mfma_stream.restype = C.c_double
+    L.vxl_debug_mfma_stream_random.argtypes = [vp, C.c_int, C.c_int, vp]
+    L.vxl_debug_mfma_stream_random.restype = C.c_double
+    L.vxl_debug_tile_loop_bytes.argtypes = [C.c_int]
+    L.vxl_debug_tile_loop_bytes.restype = sz
+    L.vxl_debug_tile_loop.argtypes = [C.c_int, vp, vp, C.c_int, C.c_int, vp]
+    L.vxl_debug_tile_loop.restype = C.c_double
     L.vxl_debug_read_stream.argtypes = [vp, sz, vp, C.c_int, vp]
     L.vxl_debug_read_stream.restype = C.c_int
     _lib = L
@@ -335,6 +341,20 @@ def debug_force_simple(on: bool) -> None:
 def debug_mfma_stream(out, n_workgroups: int, iters: int, stream=None) -> float:
     """Measurement only: launches a register-resident matrix-instruction stream; returns its FLOP count."""
     return float(lib().vxl_debug_mfma_stream(_ptr(out), int(n_workgroups), int(iters), _stream(stream)))
+
+
+def debug_mfma_stream_random(out, n_workgroups: int, iters: int, stream=None) -> float:
+    """Measurement only: the same stream with pseudo-random bf16 operands that change every instruction."""
+    return float(lib().vxl_debug_mfma_stream_random(_ptr(out), int(n_workgroups), int(iters), _stream(stream)))
+
+
+def debug_tile_loop_bytes(n_workgroups: int) -> int:
+    return int(lib().vxl_debug_tile_loop_bytes(int(n_workgroups)))
+
+
+def debug_tile_loop(mode: int, kv, out, n_workgroups: int, n_tiles: int, stream=None) -> float:
+    """Measurement only: the pre-filling tile loop on LDS-resident tiles (mode: see vxl_debug.h); returns its FLOP count."""
+    return float(lib().vxl_debug_tile_loop(int(mode), _ptr(kv), _ptr(out), int(n_workgroups), int(n_tiles), _stream(stream)))
 
 
 def debug_read_stream(src, nbytes: int, out, n_workgroups: int, stream=None) -> None:
