@@ -422,7 +422,8 @@ def measure_attained_peaks(torch, vxl):
     tl = {}
     n_tiles = 4000
     for tag, mode in (("matrix_instructions_only", 0), ("operands_from_registers", 4), ("no_softmax", 3), ("full_tile_code", 1),
-                      ("full_tile_code_with_ring_refills", 2)):
+                      ("full_tile_code_with_ring_refills", 2), ("alt_16x16x32_matrix_instructions_only", 7),
+                      ("alt_16x16x32_full_tile_code", 5), ("alt_16x16x32_full_tile_code_with_ring_refills", 6)):
         vxl.debug_tile_loop(mode, kvbuf, out, n_cu, n_tiles)
         torch.cuda.synchronize()
         a.record()

@@ -52,7 +52,9 @@ double vxl_debug_mfma_stream_random(float* out, int n_workgroups, int iters, voi
  * output traffic), with one ingredient left in or taken out by `mode`, for pricing the
  * ingredients of a tile against the bare matrix-instruction stream on the same data:
  *   0 matrix instructions only   1 the full tile code   2 = 1 + ring refills by direct loads
- *   3 = 1 without the softmax arithmetic   4 = 1 with both operand streams from registers.
+ *   3 = 1 without the softmax arithmetic   4 = 1 with both operand streams from registers
+ *   5 the full tile code written for v_mfma_f32_16x16x32_bf16 (a measured alternative that no
+ *     kernel uses)   6 = 5 + ring refills   7 matrix instructions only, 16x16x32 (64 per wave, tile).
  * kv: device bf16 values (any finite data), at least vxl_debug_tile_loop_bytes(n_workgroups) bytes;
  * out: device float [n_workgroups * 512]; n_tiles even.  Returns the floating-point operations of
  * the matrix instructions launched, 0 on a bad argument or a failed launch. */
