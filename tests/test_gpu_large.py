@@ -121,6 +121,44 @@ def test_config4_variable_chunks():
             assert (lens == lay.n_tokens).all()
 
 
+@pytest.mark.parametrize("name,layer", [("config2", 0), ("config4", 0), ("config3", 20)])
+def test_every_row_at_full_size_against_the_vector_kernel(name, layer):
+    """The oracle checks sampled rows at these sizes; the rows it does not reach are checked here on
+    the device: EVERY output row of the matrix-core kernel against the fp32 vector-ALU kernel (a
+    second implementation with its own tile walk, itself compared with the oracle on the sampled
+    rows below), each row bounded on its own as in assert_close."""
+    w = wl.WORKLOADS[name]
+    lay = wl.make_layout(w)
+    q, k, v = wl.make_qkv(w, lay, layer=layer)
+    gl, desc = make_layout(lay), desc_of(w)
+    dq, dk, dv = (vxl.to_device(x, w.dtype) for x in (q, k, v))
+    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_PREFILL, gl, desc))
+    out = torch.full_like(dq, float("nan"))
+    vxl.chunk_prefill(gl, desc, dq, dk, dv, out, None, ws)
+    ref = torch.full_like(dq, float("nan"))
+    vxl.debug_force_simple(True)
+    try:
+        vxl.chunk_prefill(gl, desc, dq, dk, dv, ref, None, ws)
+        torch.cuda.synchronize()
+    finally:
+        vxl.debug_force_simple(False)
+    assert bool(torch.isfinite(out).all()) and bool(torch.isfinite(ref).all())
+    worst = 0.0
+    for h in range(w.n_q_heads):                                   # head by head: fp32 copies of 1/28 of O at a time
+        a, b = out[h].float(), ref[h].float()
+        row_ref = b.norm(dim=-1)
+        floor = 0.05 * float(row_ref.median())
+        ratio = (a - b).norm(dim=-1) / torch.clamp(row_ref, min=max(floor, 1e-30))
+        worst = max(worst, float(ratio.max()))
+        assert float((a - b).abs().max()) <= 2e-2
+    assert worst <= 3e-2, f"{name}: worst row of {w.n_q_heads * lay.n_tokens}: ||mfma - vector|| / ||row|| = {worst:.3e}"
+    # and the vector kernel itself against the oracle on a sample of rows (all rows of two chunks)
+    c_n = lay.n_chunks
+    rows = sampled_rows(lay, [1, c_n - 2], max(1, c_n // 8))
+    want = oracle.prefill_blk(q, k, v, *lay_args(lay), rows=rows)
+    assert_close(vxl.to_host(ref[:, torch.from_numpy(rows).cuda()]), want, w.dtype, what=f"{name}: vector kernel, sampled rows")
+
+
 @pytest.mark.parametrize("layer", [0, 13, 27])
 def test_config3_layers(layer):
     """Three of the 28 independent layers (first, middle, last); the dense-chunk selection is made at layer 0 and reused
