@@ -50,6 +50,31 @@ def test_library_exports_nothing_that_no_header_declares():
     assert not any(n.startswith("vxl_debug_") for n in declared_symbols(("vxl.h",)))
 
 
+def test_headers_are_plain_c_and_the_library_links_from_c(tmp_path):
+    """The boundary is a C ABI: both headers compile as strict C99 (no C++ types, no torch), and a C
+    program that links libvxl.so can call it without Python."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_vxl.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "vxl.h"\n#include "vxl_debug.h"\n'
+        'int main(void) {\n'
+        '    int32_t bounds[3] = {2, 6, 9}, soff[3] = {0, 1, 2}, sidx[2] = {2, 6};\n'
+        '    vxl_layout* h = NULL;\n'
+        '    vxl_status st = vxl_layout_create(10, 2, 2, bounds, soff, sidx, NULL, &h);   /* last bound != n_tokens */\n'
+        '    printf("%d %d %s|%d\\n", vxl_version(), (int)st, vxl_status_string(st), h == NULL);\n'
+        '    return 0;\n}\n')
+    exe = tmp_path / "use_vxl"
+    libdir = os.path.dirname(vxl.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-l:libvxl.so", f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout
+    version, status, rest = out.split(" ", 2)
+    assert int(version) >= 100 and int(status) == vxl.VXL_ERR_INVALID_ARG and rest.strip().endswith("|1")
+
+
 def test_failing_runtime_call_is_reported_as_hip_error():
     """Without a GPU the first runtime call of vxl_layout_create (well-formed arguments) fails: the
     call must return VXL_ERR_HIP, leave the handle null and keep the text of the failing call."""
