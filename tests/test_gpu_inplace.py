@@ -113,6 +113,48 @@ def test_inplace_map_survives_a_change_of_query_token_count():
         assert_close(vxl.to_host(out1), want[:, t:t + 1], "bf16", head_axis=2, what=f"in-place decode, token {t} on the reused map")
 
 
+def test_inplace_decode_in_a_replayed_graph():
+    """Both forms of the call (building the row map, and reusing it) captured into one HIP graph on a
+    side stream; every replay, with eager calls and synchronisations in between, reproduces the
+    eager result bit for bit."""
+    rng = np.random.default_rng(4141)
+    w = wl.tiny_workload("bf16", 14, 2, 128, T=3, B=2, k=2, seed=4141, value_scale=0.5)
+    lay = wl.random_layout(rng, 33, 9, 20, 300)
+    _, k, v = wl.make_qkv(w, lay, with_q=False)
+    qd = wl.make_decode_queries(w)
+    masks = rng.integers(0, 2, size=(2, lay.n_chunks)).astype(np.uint8)
+    gl, desc, l_cap = make_layout(lay), desc_of(w), lay.n_tokens
+    dk, dv, dqd = (vxl.to_device(x, "bf16") for x in (k, v, qd))
+    dm = torch.from_numpy(masks).cuda()
+    ws = vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_DECODE_INPLACE, gl, desc, 2, 3, l_cap))
+    eager = torch.full_like(dqd, float("nan"))
+    vxl.bilevel_decode_inplace(gl, desc, dqd, dk, dv, None, None, dm, l_cap, eager, None, None, ws)
+    torch.cuda.synchronize()
+    out_a, out_b = torch.zeros_like(dqd), torch.zeros_like(dqd)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        vxl.bilevel_decode_inplace(gl, desc, dqd, dk, dv, None, None, dm, l_cap, out_a, None, None, ws)      # warm-up on the stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            vxl.bilevel_decode_inplace(gl, desc, dqd, dk, dv, None, None, dm, l_cap, out_a, None, None, ws)
+            vxl.bilevel_decode_inplace(gl, desc, dqd, dk, dv, None, None, dm, l_cap, out_b, None, None, ws, map_ready=True)
+    for rep in range(3):
+        out_a.zero_()
+        out_b.zero_()
+        ws.zero_()                                                  # the map is rebuilt inside the graph
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_a.view(torch.uint8), eager.view(torch.uint8)), f"replay {rep}: map-building call differs"
+        assert torch.equal(out_b.view(torch.uint8), eager.view(torch.uint8)), f"replay {rep}: map-reusing call differs"
+        vxl.bilevel_decode_inplace(gl, desc, dqd, dk, dv, None, None, dm, l_cap, out_a, None, None, ws)      # eager work in between
+        torch.cuda.synchronize()
+    wk, wv, wlen, _ = oracle.gather_bilevel(k, v, masks, *lay_args(lay), l_cap=l_cap)
+    assert_close(vxl.to_host(eager), oracle.decode_mixed(qd, wk, wv, wlen), "bf16", head_axis=2, what="in-place decode (graph test)")
+
+
 def test_inplace_overflow_and_empty():
     """A selection that does not fit the row map is reported (negative length, O = 0, LSE = -inf);
     a layout without prefix and kept rows with nothing selected is an empty set."""
