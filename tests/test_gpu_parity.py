@@ -545,6 +545,65 @@ def test_whole_path_on_a_side_stream_and_in_a_replayed_graph():
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), f"replay {rep} differs"
 
 
+def test_whole_path_from_several_host_threads_sharing_one_layout():
+    """The library keeps no per-call state outside the caller's buffers: four host threads, each with
+    its own stream, workspaces and outputs but the SAME layout handle and inputs, run the whole path
+    concurrently (ctypes releases the interpreter lock during a call) and must each reproduce the
+    single-threaded result bit for bit, call after call."""
+    import threading
+    w = wl.tiny_workload("bf16", 14, 2, 128, T=8, B=2, k=2, seed=96, value_scale=0.4)
+    rng = np.random.default_rng(96)
+    lay = wl.random_layout(rng, 40, 7, 60, 400)
+    q, k, v = wl.make_qkv(w, lay)
+    qd = wl.make_decode_queries(w)
+    gl = make_layout(lay)
+    desc = desc_of(w)
+    dq, dk, dv, dqd = (vxl.to_device(x, w.dtype) for x in (q, k, v, qd))
+    l_cap = gl.mixed_kv_capacity(w.k)
+
+    def buffers():
+        return (torch.full_like(dq, float("nan")),
+                torch.zeros((w.B, w.k), dtype=torch.int32, device="cuda"),
+                torch.zeros((w.B, lay.n_chunks), dtype=torch.uint8, device="cuda"),
+                torch.zeros((w.B, w.n_kv_heads, l_cap, w.head_dim), dtype=dk.dtype, device="cuda"),
+                torch.zeros((w.B, w.n_kv_heads, l_cap, w.head_dim), dtype=dk.dtype, device="cuda"),
+                torch.zeros((w.B,), dtype=torch.int32, device="cuda"),
+                torch.full_like(dqd, float("nan")),
+                [vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_PREFILL, gl, desc)),
+                 vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_SCORE_TOPK, gl, desc, w.B, w.T)),
+                 vxl.alloc_workspace(vxl.workspace_bytes(vxl.OP_DECODE, None, desc, w.B, w.T, l_cap))])
+
+    eager = buffers()
+    _whole_path(w, lay, gl, desc, dq, dk, dv, dqd, eager)
+    torch.cuda.synchronize()
+    n_threads, n_rounds = 4, 8
+    per_thread = [buffers() for _ in range(n_threads)]
+    streams = [torch.cuda.Stream() for _ in range(n_threads)]
+    torch.cuda.synchronize()
+    failures = []
+
+    def worker(i):
+        try:
+            with torch.cuda.stream(streams[i]):
+                for rnd in range(n_rounds):
+                    per_thread[i][0].fill_(float("nan"))
+                    per_thread[i][6].fill_(float("nan"))
+                    _whole_path(w, lay, gl, desc, dq, dk, dv, dqd, per_thread[i])
+                    streams[i].synchronize()
+                    for a, b in zip(eager[:7], per_thread[i][:7]):
+                        if not torch.equal(a.view(torch.uint8), b.view(torch.uint8)):
+                            failures.append((i, rnd))
+        except Exception as err:                                    # noqa: BLE001 -- reported below
+            failures.append((i, repr(err)))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(n_threads)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not failures, failures
+
+
 @pytest.mark.parametrize("d,lens", [(128, [40001, 711]), (64, [40001]), (64, [711])],
                          ids=["d128-long+short", "d64-long", "d64-short"])
 def test_decode_step_mode_more_splits_than_the_merge_prefetches(d, lens):
